@@ -1,0 +1,265 @@
+/*
+ * nexus.h -- C ABI of the MI355X-native hot path of intra-GPU prefill/decode
+ * disaggregation: one mixed-batch transformer step in which a chunked-prefill
+ * sub-batch and a decode sub-batch run concurrently on disjoint compute-unit
+ * (CU) partitions of one GPU (paper Sec. 4 overview and Fig. 6: the inputs of
+ * a partitioned step are the CU shares R_p / R_d, the prefill chunk tokens
+ * P_T with the KV they attend to, and the decode batch B_d with its KV).
+ *
+ * Conventions
+ *   - Every function returns 0 (NEXUS_OK) or a negative nexus_status; no C++
+ *     exception crosses this boundary.  nexus_last_error() returns a
+ *     thread-local, library-owned, NUL-terminated description of the last
+ *     failure on the calling thread.
+ *   - "device" pointers are HIP device memory on the context's GPU, owned by
+ *     the caller (e.g. torch tensors); "host" pointers are ordinary memory.
+ *     The library owns the context, its streams, its workspace and its packed
+ *     copies of the weights.
+ *   - bf16 = IEEE bfloat16, 2 bytes, round-to-nearest-even.  All lengths,
+ *     offsets and page ids are int32.
+ *   - All argument checks happen on the host before anything is launched; a
+ *     call that fails launches nothing.  The contents of device-side integer
+ *     arrays (lengths, page ids) cannot be checked without a device-to-host
+ *     copy; kernels skip page ids outside [0, n_pages) instead of
+ *     dereferencing them.
+ *   - Step calls enqueue work and return; nexus_sync() (or a timing request)
+ *     waits.  Calls on one context must not overlap from several threads.
+ */
+#ifndef NEXUS_H
+#define NEXUS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NEXUS_OK = 0,
+    NEXUS_EINVAL = -1, /* bad argument (null pointer, negative size, bad enum)       */
+    NEXUS_ESHAPE = -2, /* shape outside what the kernels or the context limits allow */
+    NEXUS_ENOMEM = -3, /* device or host allocation failed                           */
+    NEXUS_EHIP = -4,   /* a HIP runtime call failed; see nexus_last_error()          */
+    NEXUS_ESTATE = -5  /* call order violated (e.g. layer weights not loaded)        */
+} nexus_status;
+
+typedef struct nexus_ctx nexus_ctx; /* opaque */
+
+/*
+ * Decoder-layer shape (Sec. 2.2, Eq. 1-3, in the RMSNorm / rotary / grouped-
+ * query / SwiGLU form of the models of Sec. 6.1).  Requirements: head_dim is
+ * 64 or 128; n_q_heads is a multiple of n_kv_heads with a ratio of at most 16;
+ * hidden and ffn are multiples of 32; page_size is 16.
+ */
+typedef struct {
+    int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers, page_size;
+    float rms_eps, rope_theta;
+} nexus_model_desc;
+
+/* Upper bounds that size the context's workspace; step calls beyond them fail with NEXUS_ESHAPE. */
+typedef struct {
+    int32_t max_prefill_tokens; /* sum of chunk lengths in one prefill sub-batch  */
+    int32_t max_prefill_reqs;
+    int32_t max_decode_reqs;
+    int32_t max_positions;      /* largest absolute position + 1 (rotary table)   */
+} nexus_limits;
+
+/*
+ * One layer's weights, device bf16, row-major [out_features][in_features]
+ * (Eq. 1-3 with each W stored transposed).  w_gate_up holds the ffn gate rows
+ * followed by the ffn up rows.  b_qkv may be NULL.  nexus_load_layer() packs
+ * them into a library-owned copy; the caller may free its tensors afterwards.
+ */
+typedef struct {
+    const void *attn_norm_g; /* [hidden]                              */
+    const void *w_qkv;       /* [(Hq + 2*Hkv)*head_dim][hidden]: q rows, k rows, v rows */
+    const void *b_qkv;       /* [(Hq + 2*Hkv)*head_dim] or NULL       */
+    const void *w_o;         /* [hidden][Hq*head_dim]                 */
+    const void *ffn_norm_g;  /* [hidden]                              */
+    const void *w_gate_up;   /* [2*ffn][hidden]                       */
+    const void *w_down;      /* [hidden][ffn]                         */
+} nexus_layer_weights;
+
+/*
+ * Paged KV cache (the paper leaves block management to the serving engine;
+ * the caller owns the pools and the page allocator).  Each pool is device
+ * memory of n_pages * Hkv * page_size * head_dim bf16 per layer; layer l
+ * starts layer_stride_bytes * l after the pool pointer.  The token at
+ * position pos of a request lives in page page_table[req][pos / page_size],
+ * slot pos % page_size.  The element order INSIDE one (page, kv head) block is
+ * private to the library (it is chosen so that the attention kernels read it
+ * with full-width coalesced loads); use nexus_kv_import / nexus_kv_export to
+ * convert whole pages from / to the canonical order
+ * [n_pages][Hkv][page_size][head_dim].  Keys are cached after rotation.
+ */
+typedef struct {
+    void *k_pool, *v_pool;
+    int64_t layer_stride_bytes;
+    int32_t n_pages;
+} nexus_kv_cache;
+
+/*
+ * Chunked-prefill sub-batch (Sec. 2.4 / Sec. 3.3: each chunk attends to the KV
+ * cached by earlier chunks and appends its own).  Requests are packed along
+ * the token axis.  x and y may alias.
+ */
+typedef struct {
+    int32_t n_reqs, n_tokens;    /* host scalars; n_tokens = cu_chunk[n_reqs]                       */
+    const void *x;               /* device bf16 [n_tokens][hidden], layer input                     */
+    void *y;                     /* device bf16 [n_tokens][hidden], output of the last layer run    */
+    const int32_t *cu_chunk;     /* device [n_reqs + 1], exclusive prefix sum of chunk lengths      */
+    const int32_t *prefix_len;   /* device [n_reqs], tokens of the request already cached           */
+    const int32_t *page_table;   /* device [n_reqs][max_pages]                                      */
+    int32_t max_pages;           /* row length of page_table                                        */
+    int32_t max_chunk;           /* host hint: >= every chunk length (sizes the launch grids)       */
+    int32_t max_total_len;       /* host hint: >= every prefix_len + chunk length                   */
+} nexus_prefill_batch;
+
+/*
+ * Decode sub-batch (Sec. 2.3: one new token per request against all of its
+ * cached KV).  ctx_len[j] counts the tokens cached BEFORE this step: the new
+ * token is stored at position ctx_len[j] and attends to ctx_len[j] + 1 keys;
+ * the page table row must hold ceil((ctx_len[j] + 1) / page_size) valid pages.
+ */
+typedef struct {
+    int32_t n_reqs;
+    const void *x;               /* device bf16 [n_reqs][hidden] */
+    void *y;                     /* device bf16 [n_reqs][hidden] */
+    const int32_t *ctx_len;      /* device [n_reqs]              */
+    const int32_t *page_table;   /* device [n_reqs][max_pages]   */
+    int32_t max_pages;
+    int32_t max_ctx;             /* host hint: >= every ctx_len[j] + 1 */
+} nexus_decode_batch;
+
+/* Filled by nexus_mixed_step when requested (the call then waits for the step to finish). */
+typedef struct {
+    float t_prefill_ms; /* fork -> prefill chain complete                       */
+    float t_decode_ms;  /* fork -> decode chain complete (decode-step latency)  */
+    float t_step_ms;    /* fork -> both complete                                */
+} nexus_step_timing;
+
+/* How a CU share is laid out over the chip's accelerator dies (XCDs), each of which has its own L2. */
+typedef enum {
+    NEXUS_PART_SLICED = 0, /* every XCD gives each phase the same fraction of its CUs (default) */
+    NEXUS_PART_WHOLE_XCD = 1 /* each phase gets whole XCDs; shares are multiples of one XCD    */
+} nexus_partition_mode;
+
+/* Split-selection rule applied to measured latency curves (Sec. 4.1.2 objectives; alpha, beta as in Sec. 5). */
+typedef enum {
+    NEXUS_POLICY_PREFILL_PRIORITIZED = 0, /* min t_prefill  s.t. t_decode  <= beta  * t_decode(all CUs)  */
+    NEXUS_POLICY_DECODE_PRIORITIZED = 1,  /* min t_decode   s.t. t_prefill <= alpha * t_prefill(all CUs) */
+    NEXUS_POLICY_MIN_STEP = 2             /* min measured concurrent step time                           */
+} nexus_policy;
+
+#define NEXUS_CUS_ALL (-1) /* nexus_set_cu_split(ctx, NEXUS_CUS_ALL, NEXUS_CUS_ALL): unpartitioned, serialized */
+
+/* ---- context ---------------------------------------------------------------------------------------------- */
+
+/* Creates a context on `device` (HIP ordinal): streams, workspace sized by `limits`, rotary table. */
+int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int device, nexus_ctx **out);
+void nexus_destroy(nexus_ctx *ctx);
+/* Packs one layer's weights (device pointers) into the library's own tile-ordered copy.  Synchronous. */
+int nexus_load_layer(nexus_ctx *ctx, int layer, const nexus_layer_weights *w);
+/* Waits for everything the context has enqueued. */
+int nexus_sync(nexus_ctx *ctx);
+const char *nexus_last_error(void);
+/* Number of CUs of the context's GPU (256 on MI355X). */
+int nexus_cu_count(nexus_ctx *ctx);
+
+/* ---- KV cache layout conversion (whole pages; device pointers; enqueued on the context's main stream) ------ */
+
+/* canonical bf16 [page_count][Hkv][page_size][head_dim] -> pages [page_begin, page_begin + page_count) of layer */
+int nexus_kv_import(nexus_ctx *ctx, const nexus_kv_cache *kv, int layer, const void *k_canon, const void *v_canon,
+                    int32_t page_begin, int32_t page_count);
+/* the reverse; used by tests to compare appended K/V and untouched slots with the oracle's pools */
+int nexus_kv_export(nexus_ctx *ctx, const nexus_kv_cache *kv, int layer, void *k_canon, void *v_canon,
+                    int32_t page_begin, int32_t page_count);
+
+/* ---- CU partitioning (Sec. 5: partition layouts are created ahead of use and switched at run time) --------- */
+
+int nexus_set_partition_mode(nexus_ctx *ctx, int mode /* nexus_partition_mode */);
+/*
+ * Selects the CU share of each phase: prefill_cus + decode_cus <= nexus_cu_count(), both positive multiples of
+ * 8 (of one XCD's CU count in WHOLE_XCD mode).  The two phases then run on two streams whose CU masks are
+ * disjoint.  The stream pair of a layout is created on first use and kept.  (NEXUS_CUS_ALL, NEXUS_CUS_ALL)
+ * selects the unpartitioned layout: one unmasked stream, the mixed step runs prefill then decode back to back
+ * (the serialized baseline of Sec. 3.1).
+ */
+int nexus_set_cu_split(nexus_ctx *ctx, int prefill_cus, int decode_cus);
+
+/* ---- the step (layers [layer_begin, layer_end); output of layer l feeds layer l + 1) ----------------------- */
+
+/* Chunked-prefill phase alone, on the prefill stream of the current layout. */
+int nexus_prefill_chunk(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_prefill_batch *pb,
+                        const nexus_kv_cache *kv);
+/* Decode phase alone, on the decode stream of the current layout. */
+int nexus_decode_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_decode_batch *db,
+                      const nexus_kv_cache *kv);
+/*
+ * Both phases of one step.  With a partitioned layout they are enqueued on the two CU-masked streams after a
+ * common fork event and run concurrently; with the unpartitioned layout they run back to back.  The two
+ * sub-batches must touch disjoint requests and pages.  caller_stream (a hipStream_t, may be NULL) is made to
+ * precede the fork and to wait for both phases.  timing may be NULL; when given the call blocks until done.
+ */
+int nexus_mixed_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_prefill_batch *pb,
+                     const nexus_decode_batch *db, const nexus_kv_cache *kv, void *caller_stream,
+                     nexus_step_timing *timing);
+/*
+ * Latency-vs-CUs profiling (Sec. 3.2) and split choice (Sec. 4.1.2 on measured curves).  For each candidate i,
+ * prefill gets cand_prefill_cus[i] CUs and decode the remaining ones; the phases are timed alone (median of
+ * `repeats` runs after one warm-up) and together.  Host output arrays have n_cand entries; t_alone_all_ms[2]
+ * receives each phase alone on the whole GPU.  The chosen layout is left active.  KV pools are overwritten at
+ * the appended positions only (re-running a step rewrites the same slots with the same values).
+ */
+int nexus_profile_split(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_prefill_batch *pb,
+                        const nexus_decode_batch *db, const nexus_kv_cache *kv, const int32_t *cand_prefill_cus,
+                        int n_cand, int policy, float alpha, float beta, int repeats, float *t_prefill_ms,
+                        float *t_decode_ms, float *t_step_ms, float *t_alone_all_ms, int32_t *chosen_prefill_cus);
+
+/*
+ * The selection rule of nexus_profile_split on its own (host only, no GPU work): returns the index of the chosen
+ * candidate given the measured curves, or a negative status.  When no candidate meets the slack the one that
+ * violates it least is taken; ties go to the lower index.
+ */
+int nexus_choose_split(int n_cand, const float *t_prefill_ms, const float *t_decode_ms, const float *t_step_ms,
+                       float t_prefill_all_ms, float t_decode_all_ms, int policy, float alpha, float beta);
+
+/* ---- measurement and test hooks ----------------------------------------------------------------------------- */
+
+/* Kernel ids for nexus_trace_*: one per kernel family on the path. */
+typedef enum {
+    NEXUS_K_RMSNORM = 0, NEXUS_K_GEMM_QKV, NEXUS_K_ROPE_APPEND, NEXUS_K_ATTN_PREFILL, NEXUS_K_GEMM_O,
+    NEXUS_K_GEMM_GATE_UP, NEXUS_K_GEMM_DOWN, NEXUS_K_ATTN_DECODE, NEXUS_K_ATTN_MERGE, NEXUS_K_SPLITK_REDUCE,
+    NEXUS_K_COUNT
+} nexus_kernel_id;
+typedef enum { NEXUS_PHASE_PREFILL = 0, NEXUS_PHASE_DECODE = 1 } nexus_phase;
+
+/*
+ * While tracing is on, every launch of (phase, kernel) is bracketed by HIP events on the stream it runs on.
+ * nexus_trace_read waits, returns the mean duration in milliseconds and the number of launches seen since
+ * nexus_trace_begin, and turns tracing off.  At most 4096 launches are recorded.
+ */
+int nexus_trace_begin(nexus_ctx *ctx, int phase, int kernel);
+int nexus_trace_read(nexus_ctx *ctx, float *mean_ms, int32_t *launches);
+
+/* Intermediate buffers of the last step of a phase, converted to row-major bf16 (device out pointer). */
+typedef enum {
+    NEXUS_BUF_NORM1 = 0, /* [T][hidden]   RMSNorm output feeding the QKV projection */
+    NEXUS_BUF_Q,         /* [T][Hq*hd]    rotated queries                           */
+    NEXUS_BUF_ATTN,      /* [T][Hq*hd]    attention output                          */
+    NEXUS_BUF_X1,        /* [T][hidden]   residual stream after attention           */
+    NEXUS_BUF_ACT        /* [T][ffn]      SwiGLU activation feeding the down projection */
+} nexus_debug_buf;
+int nexus_debug_fetch(nexus_ctx *ctx, int phase, int which, int32_t n_tokens, void *out);
+
+/*
+ * Runs a probe kernel of n_blocks one-wave workgroups on the stream of `phase` in the current layout and
+ * returns, per hardware (XCD, shader engine, CU), how many workgroups ran there: host out_counts[8 * 128] int32,
+ * index xcd * 128 + shader_engine * 16 + cu, from the wave's hardware-id registers.
+ */
+int nexus_debug_cu_probe(nexus_ctx *ctx, int phase, int n_blocks, int32_t *out_counts);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NEXUS_H */

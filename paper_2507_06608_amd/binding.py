@@ -1,0 +1,277 @@
+"""ctypes binding of libnexus.so (the C ABI of include/nexus.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch is used for device memory (tensors whose data_ptr() is handed
+over) and for the caller's stream.  There is no CPU fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+from .synth import DecodeBatch, ModelShape, PrefillBatch, Workload
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnexus.so")
+
+CUS_ALL = -1
+PHASE_PREFILL, PHASE_DECODE = 0, 1
+PART_SLICED, PART_WHOLE_XCD = 0, 1
+POLICY_PREFILL_PRIORITIZED, POLICY_DECODE_PRIORITIZED, POLICY_MIN_STEP = 0, 1, 2
+KERNELS = ("rmsnorm", "gemm_qkv", "rope_append", "attn_prefill", "gemm_o", "gemm_gate_up", "gemm_down",
+           "attn_decode", "attn_merge", "splitk_reduce")
+BUF_NORM1, BUF_Q, BUF_ATTN, BUF_X1, BUF_ACT = range(5)
+
+EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "nexus_last_error", "nexus_cu_count",
+           "nexus_kv_import", "nexus_kv_export", "nexus_set_partition_mode", "nexus_set_cu_split",
+           "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_profile_split",
+           "nexus_choose_split", "nexus_trace_begin", "nexus_trace_read", "nexus_debug_fetch",
+           "nexus_debug_cu_probe")
+
+
+class NexusError(RuntimeError):
+    pass
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn", C.c_int32), ("n_layers", C.c_int32), ("page_size", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class Limits(C.Structure):
+    _fields_ = [("max_prefill_tokens", C.c_int32), ("max_prefill_reqs", C.c_int32),
+                ("max_decode_reqs", C.c_int32), ("max_positions", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("attn_norm_g", "w_qkv", "b_qkv", "w_o", "ffn_norm_g", "w_gate_up", "w_down")]
+
+
+class KVCache(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("layer_stride_bytes", C.c_int64),
+                ("n_pages", C.c_int32)]
+
+
+class PrefillBatchC(C.Structure):
+    _fields_ = [("n_reqs", C.c_int32), ("n_tokens", C.c_int32), ("x", C.c_void_p), ("y", C.c_void_p),
+                ("cu_chunk", C.c_void_p), ("prefix_len", C.c_void_p), ("page_table", C.c_void_p),
+                ("max_pages", C.c_int32), ("max_chunk", C.c_int32), ("max_total_len", C.c_int32)]
+
+
+class DecodeBatchC(C.Structure):
+    _fields_ = [("n_reqs", C.c_int32), ("x", C.c_void_p), ("y", C.c_void_p), ("ctx_len", C.c_void_p),
+                ("page_table", C.c_void_p), ("max_pages", C.c_int32), ("max_ctx", C.c_int32)]
+
+
+class StepTiming(C.Structure):
+    _fields_ = [("t_prefill_ms", C.c_float), ("t_decode_ms", C.c_float), ("t_step_ms", C.c_float)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads libnexus.so; raises if it has not been built (see build.py / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise NexusError(f"{LIB_PATH} not found: build it with `python -m paper_2507_06608_amd.build`")
+        _lib = C.CDLL(LIB_PATH)
+        _lib.nexus_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if name not in ("nexus_last_error", "nexus_destroy"):
+                getattr(_lib, name).restype = C.c_int
+        _lib.nexus_destroy.restype = None
+        _lib.nexus_choose_split.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
+                                            C.c_int, C.c_float, C.c_float]
+    return _lib
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise NexusError(f"nexus error {rc}: {lib().nexus_last_error().decode()}")
+    return rc
+
+
+def choose_split(t_p, t_d, t_step, t_p_all: float, t_d_all: float, policy: int, alpha: float, beta: float) -> int:
+    """Host-only selection rule on measured curves (no GPU needed)."""
+    a, b, s = (np.ascontiguousarray(v, np.float32) for v in (t_p, t_d, t_step))
+    return _check(lib().nexus_choose_split(len(a), a.ctypes.data, b.ctypes.data, s.ctypes.data, t_p_all, t_d_all,
+                                           policy, alpha, beta))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class DevPrefill:
+    """A prefill sub-batch resident on the GPU; keeps the tensors alive and builds the C descriptor."""
+
+    def __init__(self, b: PrefillBatch, device):
+        self.host = b
+        self.x = b.x.to(device).contiguous()
+        self.y = torch.empty_like(self.x)
+        self.cu = torch.from_numpy(b.cu_chunk.astype(np.int32)).to(device)
+        self.prefix = torch.from_numpy(b.prefix_len.astype(np.int32)).to(device)
+        self.pt = torch.from_numpy(np.ascontiguousarray(b.page_table, np.int32)).to(device)
+        total = b.prefix_len + b.chunk_len
+        self.c = PrefillBatchC(b.n_reqs, b.n_tokens, self.x.data_ptr(), self.y.data_ptr(), self.cu.data_ptr(),
+                               self.prefix.data_ptr(), self.pt.data_ptr(), b.page_table.shape[1],
+                               int(b.chunk_len.max()), int(total.max()))
+
+
+class DevDecode:
+    def __init__(self, b: DecodeBatch, device):
+        self.host = b
+        self.x = b.x.to(device).contiguous()
+        self.y = torch.empty_like(self.x)
+        self.ctx = torch.from_numpy(b.ctx_len.astype(np.int32)).to(device)
+        self.pt = torch.from_numpy(np.ascontiguousarray(b.page_table, np.int32)).to(device)
+        self.c = DecodeBatchC(b.n_reqs, self.x.data_ptr(), self.y.data_ptr(), self.ctx.data_ptr(),
+                              self.pt.data_ptr(), b.page_table.shape[1], int(b.ctx_len.max()) + 1)
+
+
+class Nexus:
+    """One context: model shape, workspace limits, packed weights, CU layouts."""
+
+    def __init__(self, shape: ModelShape, *, max_prefill_tokens: int, max_prefill_reqs: int, max_decode_reqs: int,
+                 max_positions: int, device: int = 0, n_layers: Optional[int] = None):
+        self.shape = shape
+        self.device = torch.device("cuda", device)
+        self.n_layers = n_layers or shape.n_layers
+        desc = ModelDesc(shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, self.n_layers,
+                         shape.page_size, shape.rms_eps, shape.rope_theta)
+        lim = Limits(max_prefill_tokens, max_prefill_reqs, max_decode_reqs, max_positions)
+        self._ctx = C.c_void_p()
+        torch.cuda.init()
+        _check(lib().nexus_create(C.byref(desc), C.byref(lim), device, C.byref(self._ctx)))
+        self._kv_keep = None
+
+    # -- lifetime
+    def close(self):
+        if self._ctx:
+            lib().nexus_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def sync(self):
+        _check(lib().nexus_sync(self._ctx))
+
+    @property
+    def cu_count(self) -> int:
+        return _check(lib().nexus_cu_count(self._ctx))
+
+    # -- weights
+    def load_layer(self, layer: int, w: Dict[str, torch.Tensor]):
+        dev = {k: (None if v is None else v.to(self.device, torch.bfloat16).contiguous()) for k, v in w.items()}
+        cw = LayerWeights(*[None if dev.get(k) is None else dev[k].data_ptr() for k in
+                            ("attn_norm_g", "w_qkv", "b_qkv", "w_o", "ffn_norm_g", "w_gate_up", "w_down")])
+        _check(lib().nexus_load_layer(self._ctx, layer, C.byref(cw)))
+        torch.cuda.synchronize(self.device)
+
+    # -- KV cache
+    def make_kv(self, k_canon: torch.Tensor, v_canon: torch.Tensor, layers: int = 1):
+        """Allocates private pools for `layers` layers and imports the canonical pools
+        [n_pages, Hkv, page, hd] (bf16, any device) into every layer."""
+        s = self.shape
+        n_pages = k_canon.shape[0]
+        assert tuple(k_canon.shape) == (n_pages, s.n_kv_heads, s.page_size, s.head_dim)
+        per_layer = n_pages * s.n_kv_heads * s.page_size * s.head_dim
+        kp = torch.empty(layers * per_layer, dtype=torch.bfloat16, device=self.device)
+        vp = torch.empty(layers * per_layer, dtype=torch.bfloat16, device=self.device)
+        kv = KVCache(kp.data_ptr(), vp.data_ptr(), per_layer * 2, n_pages)
+        kc = k_canon.to(self.device).contiguous()
+        vc = v_canon.to(self.device).contiguous()
+        torch.cuda.synchronize(self.device)
+        for l in range(layers):
+            _check(lib().nexus_kv_import(self._ctx, C.byref(kv), l, _ptr(kc), _ptr(vc), 0, n_pages))
+        self._kv_keep = (kp, vp)
+        return kv
+
+    def kv_export(self, kv: KVCache, layer: int = 0):
+        s = self.shape
+        shape = (kv.n_pages, s.n_kv_heads, s.page_size, s.head_dim)
+        kc = torch.empty(shape, dtype=torch.bfloat16, device=self.device)
+        vc = torch.empty(shape, dtype=torch.bfloat16, device=self.device)
+        _check(lib().nexus_kv_export(self._ctx, C.byref(kv), layer, _ptr(kc), _ptr(vc), 0, kv.n_pages))
+        return kc, vc
+
+    # -- partitioning
+    def set_partition_mode(self, mode: int):
+        _check(lib().nexus_set_partition_mode(self._ctx, mode))
+
+    def set_cu_split(self, prefill_cus: int, decode_cus: int):
+        _check(lib().nexus_set_cu_split(self._ctx, prefill_cus, decode_cus))
+
+    # -- steps
+    def prefill_chunk(self, pb: DevPrefill, kv: KVCache, layers=(0, 1)):
+        _check(lib().nexus_prefill_chunk(self._ctx, layers[0], layers[1], C.byref(pb.c), C.byref(kv)))
+
+    def decode_step(self, db: DevDecode, kv: KVCache, layers=(0, 1)):
+        _check(lib().nexus_decode_step(self._ctx, layers[0], layers[1], C.byref(db.c), C.byref(kv)))
+
+    def mixed_step(self, pb: DevPrefill, db: DevDecode, kv: KVCache, layers=(0, 1), stream=None, timing=False):
+        tm = StepTiming() if timing else None
+        sp = C.c_void_p(stream.cuda_stream) if stream is not None else None
+        _check(lib().nexus_mixed_step(self._ctx, layers[0], layers[1], C.byref(pb.c), C.byref(db.c), C.byref(kv), sp,
+                                      C.byref(tm) if timing else None))
+        return tm
+
+    def profile_split(self, pb: DevPrefill, db: DevDecode, kv: KVCache, cand_prefill_cus: Sequence[int], policy: int,
+                      alpha: float = 1.3, beta: float = 1.1, repeats: int = 5, layers=(0, 1)):
+        n = len(cand_prefill_cus)
+        cand = (C.c_int32 * n)(*cand_prefill_cus)
+        tp, td, ts = (C.c_float * n)(), (C.c_float * n)(), (C.c_float * n)()
+        tall = (C.c_float * 2)()
+        chosen = C.c_int32()
+        _check(lib().nexus_profile_split(self._ctx, layers[0], layers[1], C.byref(pb.c), C.byref(db.c), C.byref(kv),
+                                         cand, n, policy, C.c_float(alpha), C.c_float(beta), repeats, tp, td, ts, tall,
+                                         C.byref(chosen)))
+        return {"cand_prefill_cus": list(cand_prefill_cus), "t_prefill_ms": list(tp), "t_decode_ms": list(td),
+                "t_step_ms": list(ts), "t_prefill_all_ms": tall[0], "t_decode_all_ms": tall[1],
+                "chosen_prefill_cus": chosen.value}
+
+    # -- measurement / debug
+    def trace_begin(self, phase: int, kernel: str):
+        _check(lib().nexus_trace_begin(self._ctx, phase, KERNELS.index(kernel)))
+
+    def trace_read(self):
+        ms, n = C.c_float(), C.c_int32()
+        _check(lib().nexus_trace_read(self._ctx, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
+    def debug_fetch(self, phase: int, which: int, n_tokens: int) -> torch.Tensor:
+        s = self.shape
+        width = {BUF_Q: s.q_dim, BUF_ATTN: s.q_dim, BUF_X1: s.hidden, BUF_ACT: s.ffn}[which]
+        out = torch.empty((n_tokens, width), dtype=torch.bfloat16, device=self.device)
+        _check(lib().nexus_debug_fetch(self._ctx, phase, which, n_tokens, _ptr(out)))
+        return out
+
+    def cu_probe(self, phase: int, n_blocks: int = 8192) -> np.ndarray:
+        out = np.zeros(8 * 128, np.int32)
+        _check(lib().nexus_debug_cu_probe(self._ctx, phase, n_blocks, out.ctypes.data_as(C.c_void_p)))
+        return out.reshape(8, 8, 16)
+
+
+def context_for(w: Workload, device: int = 0, n_layers: int = 1) -> Nexus:
+    """A context sized for one workload."""
+    p, d = w.prefill, w.decode
+    max_pos = 1
+    if p is not None:
+        max_pos = max(max_pos, int((p.prefix_len + p.chunk_len).max()))
+    if d is not None:
+        max_pos = max(max_pos, int(d.ctx_len.max()) + 1)
+    return Nexus(w.shape, max_prefill_tokens=p.n_tokens if p else 1, max_prefill_reqs=p.n_reqs if p else 1,
+                 max_decode_reqs=d.n_reqs if d else 1, max_positions=max_pos, device=device, n_layers=n_layers)

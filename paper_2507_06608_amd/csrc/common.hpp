@@ -1,0 +1,49 @@
+// Shared device-side definitions of the gfx950 kernels: vector types, the MFMA operand tile order used for every
+// GEMM operand ("P32"), and the private KV page layouts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nexus {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // 16-byte staging register
+typedef unsigned short bf16_t;  // raw storage
+
+constexpr int kWave = 64;
+constexpr int kPage = 16;  // tokens per KV page
+
+// ---- bf16 <-> fp32 (round to nearest even; NaN kept quiet) ------------------------------------------------
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+
+// ---- P32: MFMA-operand tile order of a [rows][K] matrix ----------------------------------------------------
+// The matrix is cut into tiles of 32 rows x 16 k (1 KiB).  Inside a tile the 64 lanes of a wavefront each own
+// 8 consecutive k of one row: lane = row % 32 + 32 * ((k % 16) / 8).  That is exactly the register image of one
+// operand of v_mfma_f32_32x32x16_bf16, so a wave loads a tile with one 16-byte access per lane at lane * 16, fully
+// coalesced from global memory and conflict-free from LDS.  Tiles of one 32-row strip are contiguous along k;
+// Kp (the padded K) is a multiple of 64 and padding holds zeros.
+__host__ __device__ __forceinline__ int round_up(int v, int m) { return (v + m - 1) / m * m; }
+__host__ __device__ __forceinline__ int p32_kp(int K) { return round_up(K, 64); }
+__host__ __device__ __forceinline__ size_t p32_offset(int r, int k, int Kp) {
+    return ((size_t)(r >> 5) * (size_t)(Kp >> 4) + (size_t)(k >> 4)) * 512 + (size_t)((r & 31) + 32 * ((k >> 3) & 1)) * 8 +
+           (size_t)(k & 7);
+}
+__host__ __device__ __forceinline__ size_t p32_elems(int rows, int K) { return (size_t)round_up(rows, 32) * p32_kp(K); }
+
+// ---- private KV page layouts (one (page, kv head) block = 16 tokens x hd) ---------------------------------
+// K block: [hd / 8][16 tokens][8]   -> a wave reads 16 tokens x 32 hd (one 16x16x32 operand) as 1 KiB contiguous.
+// V block: [4 token groups][hd][4]  -> lanes own hd rows and read 4 consecutive tokens of a group.
+__host__ __device__ __forceinline__ int kblk_offset(int tok, int i) { return ((i >> 3) * kPage + tok) * 8 + (i & 7); }
+__host__ __device__ __forceinline__ int vblk_offset(int tok, int i, int hd) { return ((tok >> 2) * hd + i) * 4 + (tok & 3); }
+
+}  // namespace nexus

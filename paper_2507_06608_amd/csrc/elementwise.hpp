@@ -1,0 +1,231 @@
+// Small memory-bound kernels around the GEMMs: RMSNorm, rotary embedding + KV append, weight packing, KV page
+// layout conversion, the rotary table and the debug unpack.
+#pragma once
+#include "common.hpp"
+
+namespace nexus {
+
+// ---- RMSNorm: h = x * rsqrt(mean(x^2) + eps) * g, one workgroup per token, fp32 statistics -----------------
+// Input row-major [T][d]; output in P32 tile order (operand of the following GEMM).
+template <int MAXC>  // 8-element chunks per thread, d <= MAXC * 256 * 8
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ g,
+                                                      bf16_t *__restrict__ out_p32, int d, int Kp, float eps) {
+    __shared__ float red[4];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const int nchunk = d >> 3;
+    const uint4 *row = (const uint4 *)(x + (size_t)t * d);
+    float v[MAXC][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ci = tid + c * 256;
+        if (ci < nchunk) {
+            uint4 u = row[ci];
+            uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                v[c][2 * e] = bf2f(wds[e] & 0xffff);
+                v[c][2 * e + 1] = bf2f(wds[e] >> 16);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += v[c][e] * v[c][e];
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float inv = rsqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ci = tid + c * 256;
+        if (ci < nchunk) {
+            uint4 gu = ((const uint4 *)g)[ci];
+            uint32_t gw[4] = {gu.x, gu.y, gu.z, gu.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o[e] = pack2(v[c][2 * e] * inv * bf2f(gw[e] & 0xffff), v[c][2 * e + 1] * inv * bf2f(gw[e] >> 16));
+            *(uint4 *)(out_p32 + p32_offset(t, ci * 8, Kp)) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
+// ---- rotary table: tab[pos][j] = (cos, sin)(pos * theta^(-2j/hd)), angles in fp64 ------------------------
+__global__ void rope_table_kernel(float2 *tab, int n_pos, int half, double theta) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)n_pos * half) return;
+    const int pos = (int)(i / half), j = (int)(i % half);
+    const double freq = pow(theta, -(double)j / (double)half);
+    const double phi = (double)pos * freq;
+    tab[i] = make_float2((float)cos(phi), (float)sin(phi));
+}
+
+// ---- rotary embedding + KV append ---------------------------------------------------------------------------
+// Reads the QKV projection output (row-major [T][(Hq+2Hkv)*hd]); rotates q and k at the token's absolute
+// position; writes q for the attention kernel and k, v into the token's (page, slot) of the pools.
+struct RopeArgs {
+    const bf16_t *qkv;
+    int T, Hq, Hkv, hd;
+    const float2 *rope_tab;
+    int n_pos;
+    // prefill: requests packed, positions prefix_len[r] + local; decode (cu_chunk == null): pos = ctx_len[t]
+    const int32_t *cu_chunk;
+    const int32_t *pos_base;  // prefix_len or ctx_len
+    int n_reqs;
+    const int32_t *page_table;
+    int max_pages;
+    bf16_t *k_pool, *v_pool;
+    int n_pages;
+    bf16_t *q_out;  // prefill: P32 with request-aligned 32-row tiles; decode: row-major [T][Hq*hd]
+};
+
+template <bool PREFILL>
+__global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
+    const int t = blockIdx.x;
+    const int hd = a.hd, half = hd >> 1, cph = half >> 3;  // chunks of 8 rotary pairs per head
+    int r, pos, qrow;
+    if (PREFILL) {
+        r = 0;
+        int tile_base = 0;
+        while (r + 1 < a.n_reqs && a.cu_chunk[r + 1] <= t) {
+            tile_base += (a.cu_chunk[r + 1] - a.cu_chunk[r] + 31) >> 5;
+            ++r;
+        }
+        const int local = t - a.cu_chunk[r];
+        pos = a.pos_base[r] + local;
+        qrow = tile_base * 32 + local;
+    } else {
+        r = t;
+        pos = a.pos_base[t];
+        qrow = t;
+    }
+    const int qd = a.Hq * hd, kvd = a.Hkv * hd;
+    const bf16_t *row = a.qkv + (size_t)t * (qd + 2 * kvd);
+    int page = -1;
+    const int lp = pos >> 4, slot = pos & 15;
+    if (lp < a.max_pages) page = a.page_table[(size_t)r * a.max_pages + lp];
+    const bool page_ok = (unsigned)page < (unsigned)a.n_pages;
+    const int ptab = pos < a.n_pos ? pos : a.n_pos - 1;
+    const float2 *tab = a.rope_tab + (size_t)ptab * half;
+
+    const int rope_units = (a.Hq + a.Hkv) * cph;
+    const int v_units = a.Hkv * (hd >> 3);
+    for (int u = threadIdx.x; u < rope_units + v_units; u += 256) {
+        if (u < rope_units) {
+            const int h = u / cph, c = u % cph;  // head (q heads first, then k heads), pair chunk
+            const bf16_t *src = row + (size_t)h * hd + c * 8;
+            uint4 lo = *(const uint4 *)src, hi = *(const uint4 *)(src + half);
+            uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+            float ol[8], oh[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float x0 = bf2f((lw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+                const float x1 = bf2f((hw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+                const float2 cs = tab[c * 8 + e];
+                ol[e] = x0 * cs.x - x1 * cs.y;
+                oh[e] = x1 * cs.x + x0 * cs.y;
+            }
+            uint4 plo = make_uint4(pack2(ol[0], ol[1]), pack2(ol[2], ol[3]), pack2(ol[4], ol[5]), pack2(ol[6], ol[7]));
+            uint4 phi = make_uint4(pack2(oh[0], oh[1]), pack2(oh[2], oh[3]), pack2(oh[4], oh[5]), pack2(oh[6], oh[7]));
+            if (h < a.Hq) {
+                if (PREFILL) {
+                    *(uint4 *)(a.q_out + p32_offset(qrow, h * hd + c * 8, qd)) = plo;
+                    *(uint4 *)(a.q_out + p32_offset(qrow, h * hd + half + c * 8, qd)) = phi;
+                } else {
+                    *(uint4 *)(a.q_out + (size_t)qrow * qd + h * hd + c * 8) = plo;
+                    *(uint4 *)(a.q_out + (size_t)qrow * qd + h * hd + half + c * 8) = phi;
+                }
+            } else if (page_ok) {
+                const int kvh = h - a.Hq;
+                bf16_t *blk = a.k_pool + ((size_t)page * a.Hkv + kvh) * (kPage * hd);
+                *(uint4 *)(blk + kblk_offset(slot, c * 8)) = plo;
+                *(uint4 *)(blk + kblk_offset(slot, half + c * 8)) = phi;
+            }
+        } else if (page_ok) {
+            const int vu = u - rope_units;
+            const int kvh = vu / (hd >> 3), c = vu % (hd >> 3);
+            uint4 vv = *(const uint4 *)(row + qd + kvd + (size_t)kvh * hd + c * 8);
+            uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
+            bf16_t *blk = a.v_pool + ((size_t)page * a.Hkv + kvh) * (kPage * hd);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                blk[vblk_offset(slot, c * 8 + e, hd)] = (bf16_t)((vw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+        }
+    }
+}
+
+// ---- weight packing: row-major [N][K] -> P32 [round_up(N,32)][Kp], zero padded ----------------------------
+// interleave_F > 0 reorders gate/up rows so that 32-row strips alternate: strip 2s = gate rows [32s, 32s+32),
+// strip 2s+1 = up rows [32s, 32s+32) (a lane of the GEMM then holds a gate value and its up value).
+__global__ void pack_weight_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int K, int Kp,
+                                   int interleave_F) {
+    const int Np = round_up(N, 32);
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int kchunks = Kp >> 3;
+    if (idx >= (size_t)Np * kchunks) return;
+    const int n = (int)(idx / kchunks), k = (int)(idx % kchunks) * 8;
+    int srow = n;
+    if (interleave_F > 0) {
+        const int strip = n >> 5;
+        srow = (strip & 1) * interleave_F + (strip >> 1) * 32 + (n & 31);
+    }
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < N && k < K) {
+        if (k + 8 <= K && (K & 7) == 0) {
+            v = *(const uint4 *)(src + (size_t)srow * K + k);
+        } else {
+            bf16_t tmp[8];
+            for (int e = 0; e < 8; ++e) tmp[e] = (k + e < K) ? src[(size_t)srow * K + k + e] : (bf16_t)0;
+            v = *(uint4 *)tmp;
+        }
+    }
+    *(uint4 *)(dst + p32_offset(n, k, Kp)) = v;
+}
+
+// ---- KV page layout conversion (canonical [pages][Hkv][16][hd] <-> private blocks) -------------------------
+template <bool IMPORT>
+__global__ void kv_convert_kernel(bf16_t *k_priv, bf16_t *v_priv, bf16_t *k_canon, bf16_t *v_canon, int n_blocks /*pages*Hkv*/,
+                                  int hd) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int per_blk = kPage * hd;
+    if (idx >= (size_t)n_blocks * per_blk) return;
+    const size_t blk = idx / per_blk;
+    const int e = (int)(idx % per_blk), tok = e / hd, i = e % hd;
+    const size_t ko = blk * per_blk + kblk_offset(tok, i), vo = blk * per_blk + vblk_offset(tok, i, hd);
+    if (IMPORT) {
+        k_priv[ko] = k_canon[idx];
+        v_priv[vo] = v_canon[idx];
+    } else {
+        k_canon[idx] = k_priv[ko];
+        v_canon[idx] = v_priv[vo];
+    }
+}
+
+// ---- debug: P32 -> row-major -------------------------------------------------------------------------------
+__global__ void unpack_p32_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int rows, int K, int Kp,
+                                  const int32_t *row_map /* nullable: source row of each output row */) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)rows * K) return;
+    const int r = (int)(idx / K), k = (int)(idx % K);
+    const int sr = row_map ? row_map[r] : r;
+    dst[idx] = src[p32_offset(sr, k, Kp)];
+}
+
+// ---- CU probe: where does each workgroup of a masked stream run? -------------------------------------------
+__global__ void cu_probe_kernel(int32_t *counts) {
+    uint32_t hw_id, xcc_id;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc_id));
+    if (threadIdx.x == 0) {
+        const int cu = (hw_id >> 8) & 0xf, se = (hw_id >> 13) & 0x7;  // CU_ID and SE_ID fields of HW_ID
+        atomicAdd(&counts[(xcc_id & 7) * 128 + se * 16 + cu], 1);
+    }
+    // a little work so that workgroups spread over the CUs instead of draining through the first one
+    float acc = (float)threadIdx.x;
+    for (int i = 0; i < 2000; ++i) acc = acc * 1.0001f + 0.5f;
+    if (acc == 12345.678f) counts[0] = -1;
+}
+
+}  // namespace nexus

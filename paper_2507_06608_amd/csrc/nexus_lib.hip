@@ -1,0 +1,964 @@
+// Runtime of the partitioned prefill/decode step: context, workspace, packed weights, CU-masked stream pairs,
+// the two phase chains, the mixed step, the split profiler and the C ABI declared in include/nexus.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <new>
+#include <vector>
+
+#include "../../include/nexus.h"
+#include "attn_decode.hpp"
+#include "attn_prefill.hpp"
+#include "common.hpp"
+#include "elementwise.hpp"
+#include "gemm.hpp"
+
+using namespace nexus;
+
+// ---------------------------------------------------------------------------------------------- errors
+static thread_local char g_err[512] = "";
+static int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+#define HIP_TRY(expr)                                                                                              \
+    do {                                                                                                           \
+        hipError_t e_ = (expr);                                                                                    \
+        if (e_ != hipSuccess) return fail(NEXUS_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+#define NX_TRY(expr)             \
+    do {                         \
+        int s_ = (expr);         \
+        if (s_ != NEXUS_OK) return s_; \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------------- context
+struct LayerW {
+    bf16_t *g1 = nullptr, *g2 = nullptr, *wqkv = nullptr, *bqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdown = nullptr;
+    bool loaded = false;
+};
+
+struct PhaseWs {
+    int maxT = 0;
+    bf16_t *h = nullptr;     // P32 [maxT][hidden]   RMSNorm output (both norms)
+    bf16_t *qkv = nullptr;   // row-major [maxT][n_qkv]
+    bf16_t *q = nullptr;     // prefill: P32, request-aligned tiles; decode: row-major
+    bf16_t *attn = nullptr;  // P32 [maxT][q_dim]
+    bf16_t *x1 = nullptr;    // row-major [maxT][hidden]
+    bf16_t *act = nullptr;   // P32 [maxT][ffn]
+    bf16_t *xbuf[2] = {nullptr, nullptr};  // layer ping-pong, row-major [maxT][hidden]
+    float *partial = nullptr;
+    size_t partial_elems = 0;
+    float *part_o = nullptr, *part_ml = nullptr;  // decode attention split results
+    int max_spans = 0;
+    int q_rows = 0;
+};
+
+struct Layout {
+    int p_cus = 0, d_cus = 0;  // 0/0 = unpartitioned
+    hipStream_t sp = nullptr, sd = nullptr;
+    int p_xcd = 8, d_xcd = 8;  // XCDs each stream is spread over (tile-order hint)
+};
+
+struct TraceRec {
+    hipEvent_t a, b;
+};
+
+struct nexus_ctx {
+    nexus_model_desc m{};
+    nexus_limits lim{};
+    int device = 0, n_cus = 0, n_xcd = 8, cus_per_xcd = 32;
+    int q_dim = 0, kv_dim = 0, n_qkv = 0;
+    std::vector<LayerW> layers;
+    PhaseWs ws[2];
+    float2 *rope_tab = nullptr;
+    hipStream_t s_main = nullptr;
+    std::map<long, Layout> layouts;
+    Layout *cur = nullptr;
+    int part_mode = NEXUS_PART_SLICED;
+    bool bits_xcd_major = false;  // CU-mask bit order (see make_mask)
+    hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr, ev_sd1 = nullptr;
+    // tracing
+    int trace_phase = -1, trace_kernel = -1;
+    std::vector<TraceRec> trace_pool;
+    size_t trace_used = 0;
+    int32_t *probe_counts = nullptr;
+};
+
+struct DeviceGuard {
+    int prev = -1;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+        if (prev != dev) (void)hipSetDevice(dev);
+        else prev = -1;
+    }
+    ~DeviceGuard() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+template <typename T>
+static int dev_alloc(T **p, size_t elems, bool zero) {
+    *p = nullptr;
+    if (elems == 0) elems = 1;
+    hipError_t e = hipMalloc((void **)p, elems * sizeof(T));
+    if (e != hipSuccess) return fail(NEXUS_ENOMEM, "hipMalloc of %zu bytes failed: %s", elems * sizeof(T), hipGetErrorString(e));
+    if (zero) HIP_TRY(hipMemset(*p, 0, elems * sizeof(T)));
+    return NEXUS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------- GEMM planning
+enum GemmVariant { GV_256x256 = 0, GV_128x128, GV_SK64, GV_SK32, GV_COUNT };
+struct GemmPlan {
+    int variant, S, ksteps_per_split, FS, TS;
+};
+
+// Depends on the problem only (never on the CU share), so that results are bit-identical across layouts.
+static GemmPlan plan_gemm(int T, int n_ftiles, int Kp) {
+    const int ksteps = Kp / kGemmBK;
+    const int nt = (T + 31) / 32;
+    GemmPlan p{};
+    if (T <= 32) {
+        p.variant = GV_SK32, p.FS = 4, p.TS = 1;
+    } else if (T <= 64) {
+        p.variant = GV_SK64, p.FS = 4, p.TS = 2;
+    } else {
+        const int tiles256 = ((n_ftiles + 7) / 8) * ((nt + 7) / 8);
+        if (T > 128 && tiles256 >= 200) p.variant = GV_256x256, p.FS = 8, p.TS = 8;
+        else p.variant = GV_128x128, p.FS = 4, p.TS = 4;
+    }
+    const int blocks = ((n_ftiles + p.FS - 1) / p.FS) * ((nt + p.TS - 1) / p.TS);
+    int S = (448 + blocks - 1) / blocks;
+    const int traffic_cap = std::max(1, Kp / (8 * std::max(T, 32)));  // keep partial traffic a fraction of the weights
+    S = std::min(S, traffic_cap);
+    S = std::min(S, std::max(1, ksteps / 4));
+    S = std::max(S, 1);
+    p.ksteps_per_split = (ksteps + S - 1) / S;
+    p.S = (ksteps + p.ksteps_per_split - 1) / p.ksteps_per_split;
+    return p;
+}
+
+template <int FS, int TS, int WF, int WT, int EPI>
+static hipError_t launch_gemm_t(const GemmArgs &a, dim3 grid, hipStream_t s) {
+    constexpr int smem = 2 * (FS + TS) * kStripStage;
+    static bool attr_done = false;  // one context thread at a time (see header)
+    auto kern = gemm_p32_kernel<FS, TS, WF, WT, EPI>;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+    return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipStream_t s) {
+    switch (variant) {
+        case GV_256x256: return launch_gemm_t<8, 8, 2, 2, EPI>(a, grid, s);
+        case GV_128x128: return launch_gemm_t<4, 4, 2, 2, EPI>(a, grid, s);
+        case GV_SK64: return launch_gemm_t<4, 2, 4, 1, EPI>(a, grid, s);
+        default: return launch_gemm_t<4, 1, 4, 1, EPI>(a, grid, s);
+    }
+}
+
+static hipError_t launch_gemm(int variant, int epi, const GemmArgs &a, dim3 grid, hipStream_t s) {
+    switch (epi) {
+        case EPI_ROWMAJOR: return launch_gemm_v<EPI_ROWMAJOR>(variant, a, grid, s);
+        case EPI_RESIDUAL: return launch_gemm_v<EPI_RESIDUAL>(variant, a, grid, s);
+        case EPI_SWIGLU: return launch_gemm_v<EPI_SWIGLU>(variant, a, grid, s);
+        default: return launch_gemm_v<EPI_PARTIAL>(variant, a, grid, s);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- tracing
+struct Tracer {
+    nexus_ctx *c;
+    hipStream_t s;
+    bool on;
+    TraceRec *rec = nullptr;
+    Tracer(nexus_ctx *c_, int phase, int kernel, hipStream_t s_) : c(c_), s(s_) {
+        on = c->trace_phase == phase && c->trace_kernel == kernel && c->trace_used < c->trace_pool.size();
+        if (on) {
+            rec = &c->trace_pool[c->trace_used++];
+            (void)hipEventRecord(rec->a, s);
+        }
+    }
+    ~Tracer() {
+        if (on) (void)hipEventRecord(rec->b, s);
+    }
+};
+
+// ---------------------------------------------------------------------------------------------- phase chains
+struct PhaseRun {
+    nexus_ctx *c;
+    int phase;  // NEXUS_PHASE_*
+    hipStream_t s;
+    int n_xcd;
+    int T;
+    const nexus_prefill_batch *pb;
+    const nexus_decode_batch *db;
+    const nexus_kv_cache *kv;
+};
+
+static int run_gemm(const PhaseRun &r, int kernel_id, const bf16_t *W, int N_packed, const bf16_t *X, int K, int epi,
+                    bf16_t *out, const bf16_t *res, const bf16_t *bias, int ld_out, bf16_t *out_p32, int out_K) {
+    nexus_ctx *c = r.c;
+    PhaseWs &ws = c->ws[r.phase];
+    const int Kp = p32_kp(K);
+    const int n_ftiles = N_packed / 32;
+    const GemmPlan p = plan_gemm(r.T, n_ftiles, Kp);
+    GemmArgs a{};
+    a.W = W, a.X = X, a.n_ftiles = n_ftiles, a.n_ttiles = (r.T + 31) / 32, a.Kp = Kp;
+    a.ksteps_per_split = p.ksteps_per_split;
+    a.T = r.T, a.N = N_packed;
+    a.out = out, a.res = res, a.bias = bias, a.ld_out = ld_out;
+    a.out_p32 = out_p32, a.out_Kp = out_p32 ? p32_kp(out_K) : 0;
+    a.partial = ws.partial;
+    a.n_tblk = (a.n_ttiles + p.TS - 1) / p.TS;
+    a.n_xcd = r.n_xcd;
+    const int n_fblk = (n_ftiles + p.FS - 1) / p.FS;
+    dim3 grid(a.n_tblk * n_fblk, 1, p.S);
+    if (p.S > 1 && (size_t)p.S * r.T * N_packed > ws.partial_elems)
+        return fail(NEXUS_ESTATE, "split-K workspace too small (%d x %d x %d)", p.S, r.T, N_packed);
+    {
+        Tracer tr(c, r.phase, kernel_id, r.s);
+        HIP_TRY(launch_gemm(p.variant, p.S > 1 ? (int)EPI_PARTIAL : epi, a, grid, r.s));
+    }
+    if (p.S > 1) {
+        ReduceArgs ra{};
+        ra.partial = ws.partial, ra.S = p.S, ra.T = r.T, ra.N = N_packed;
+        ra.out = out, ra.res = res, ra.bias = bias, ra.ld_out = ld_out, ra.out_p32 = out_p32, ra.out_Kp = a.out_Kp;
+        const size_t n = (size_t)r.T * (N_packed / 4);
+        dim3 g((unsigned)((n + 255) / 256));
+        Tracer tr(c, r.phase, NEXUS_K_SPLITK_REDUCE, r.s);
+        if (epi == EPI_ROWMAJOR) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_ROWMAJOR>, g, dim3(256), 0, r.s, ra);
+        else if (epi == EPI_RESIDUAL) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_RESIDUAL>, g, dim3(256), 0, r.s, ra);
+        else hipLaunchKernelGGL(splitk_reduce_kernel<EPI_SWIGLU>, g, dim3(256), 0, r.s, ra);
+        HIP_TRY(hipGetLastError());
+    }
+    return NEXUS_OK;
+}
+
+static int run_rmsnorm(const PhaseRun &r, const bf16_t *x, const bf16_t *g, bf16_t *out_p32) {
+    nexus_ctx *c = r.c;
+    const int d = c->m.hidden;
+    Tracer tr(c, r.phase, NEXUS_K_RMSNORM, r.s);
+    if (d <= 2048) hipLaunchKernelGGL(rmsnorm_kernel<1>, dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
+    else if (d <= 4096) hipLaunchKernelGGL(rmsnorm_kernel<2>, dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
+    else hipLaunchKernelGGL(rmsnorm_kernel<4>, dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
+    HIP_TRY(hipGetLastError());
+    return NEXUS_OK;
+}
+
+template <int HD>
+static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
+    nexus_ctx *c = r.c;
+    const int G = c->m.n_q_heads / c->m.n_kv_heads;
+    AttnPrefillArgs a = base;
+    constexpr int smem = 2 * 8 * kPage * HD * 2;
+#define NX_ATTN_CASE(GG, SPB)                                                                                        \
+    case GG: {                                                                                                       \
+        auto kern = attn_prefill_kernel<HD, GG, SPB>;                                                                \
+        static bool done = false;                                                                                    \
+        if (!done) {                                                                                                 \
+            HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));      \
+            done = true;                                                                                             \
+        }                                                                                                            \
+        a.tiles_per_req = (r.pb->max_chunk + 32 * SPB - 1) / (32 * SPB);                                             \
+        hipLaunchKernelGGL(kern, dim3(r.pb->n_reqs * a.tiles_per_req, c->m.n_kv_heads), dim3(64 * GG * SPB), smem, r.s, a); \
+        break;                                                                                                       \
+    }
+    switch (G) {
+        NX_ATTN_CASE(1, 4)
+        NX_ATTN_CASE(2, 2)
+        NX_ATTN_CASE(4, 1)
+        NX_ATTN_CASE(5, 1)
+        NX_ATTN_CASE(8, 1)
+        default: return fail(NEXUS_ESHAPE, "query/kv head ratio %d has no prefill attention kernel (1, 2, 4, 5, 8)", G);
+    }
+#undef NX_ATTN_CASE
+    HIP_TRY(hipGetLastError());
+    return NEXUS_OK;
+}
+
+template <int HD>
+static int launch_attn_decode(const PhaseRun &r, const AttnDecodeArgs &a) {
+    nexus_ctx *c = r.c;
+    const int G = c->m.n_q_heads / c->m.n_kv_heads;
+    const int items = a.n_reqs * c->m.n_kv_heads * a.max_spans;
+    dim3 grid((items + 3) / 4), mgrid(a.n_reqs * c->m.n_q_heads);
+#define NX_DEC_CASE(GG)                                                                           \
+    case GG: {                                                                                    \
+        {                                                                                         \
+            Tracer tr(c, r.phase, NEXUS_K_ATTN_DECODE, r.s);                                      \
+            hipLaunchKernelGGL((attn_decode_kernel<HD, GG>), grid, dim3(256), 0, r.s, a);         \
+        }                                                                                         \
+        HIP_TRY(hipGetLastError());                                                               \
+        {                                                                                         \
+            Tracer tr(c, r.phase, NEXUS_K_ATTN_MERGE, r.s);                                       \
+            hipLaunchKernelGGL((attn_merge_kernel<HD, GG>), mgrid, dim3(64), 0, r.s, a);          \
+        }                                                                                         \
+        break;                                                                                    \
+    }
+    switch (G) {
+        NX_DEC_CASE(1)
+        NX_DEC_CASE(2)
+        NX_DEC_CASE(4)
+        NX_DEC_CASE(5)
+        NX_DEC_CASE(8)
+        default: return fail(NEXUS_ESHAPE, "query/kv head ratio %d has no decode attention kernel (1, 2, 4, 5, 8)", G);
+    }
+#undef NX_DEC_CASE
+    HIP_TRY(hipGetLastError());
+    return NEXUS_OK;
+}
+
+static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y_out) {
+    nexus_ctx *c = r.c;
+    const nexus_model_desc &m = c->m;
+    PhaseWs &ws = c->ws[r.phase];
+    const LayerW &L = c->layers[layer];
+    const bool prefill = r.phase == NEXUS_PHASE_PREFILL;
+    bf16_t *k_pool = (bf16_t *)((char *)r.kv->k_pool + (size_t)layer * r.kv->layer_stride_bytes);
+    bf16_t *v_pool = (bf16_t *)((char *)r.kv->v_pool + (size_t)layer * r.kv->layer_stride_bytes);
+
+    NX_TRY(run_rmsnorm(r, x_in, L.g1, ws.h));
+    NX_TRY(run_gemm(r, NEXUS_K_GEMM_QKV, L.wqkv, c->n_qkv, ws.h, m.hidden, EPI_ROWMAJOR, ws.qkv, nullptr, L.bqkv, c->n_qkv,
+                    nullptr, 0));
+    {
+        RopeArgs a{};
+        a.qkv = ws.qkv, a.T = r.T, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads, a.hd = m.head_dim;
+        a.rope_tab = c->rope_tab, a.n_pos = c->lim.max_positions;
+        a.cu_chunk = prefill ? r.pb->cu_chunk : nullptr;
+        a.pos_base = prefill ? r.pb->prefix_len : r.db->ctx_len;
+        a.n_reqs = prefill ? r.pb->n_reqs : r.db->n_reqs;
+        a.page_table = prefill ? r.pb->page_table : r.db->page_table;
+        a.max_pages = prefill ? r.pb->max_pages : r.db->max_pages;
+        a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.q_out = ws.q;
+        Tracer tr(c, r.phase, NEXUS_K_ROPE_APPEND, r.s);
+        if (prefill) hipLaunchKernelGGL(rope_append_kernel<true>, dim3(r.T), dim3(256), 0, r.s, a);
+        else hipLaunchKernelGGL(rope_append_kernel<false>, dim3(r.T), dim3(256), 0, r.s, a);
+        HIP_TRY(hipGetLastError());
+    }
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)m.head_dim);
+    if (prefill) {
+        AttnPrefillArgs a{};
+        a.q = ws.q, a.out = ws.attn, a.cu_chunk = r.pb->cu_chunk, a.prefix_len = r.pb->prefix_len, a.page_table = r.pb->page_table;
+        a.n_reqs = r.pb->n_reqs, a.max_pages = r.pb->max_pages;
+        a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads;
+        a.scale_log2e = scale_log2e;
+        Tracer tr(c, r.phase, NEXUS_K_ATTN_PREFILL, r.s);
+        NX_TRY(m.head_dim == 128 ? launch_attn_prefill<128>(r, a) : launch_attn_prefill<64>(r, a));
+    } else {
+        AttnDecodeArgs a{};
+        a.q = ws.q, a.ctx_len = r.db->ctx_len, a.page_table = r.db->page_table, a.n_reqs = r.db->n_reqs;
+        a.max_pages = r.db->max_pages, a.max_spans = (r.db->max_ctx + kSpan - 1) / kSpan;
+        a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads;
+        a.scale_log2e = scale_log2e, a.part_o = ws.part_o, a.part_ml = ws.part_ml, a.out = ws.attn;
+        NX_TRY(m.head_dim == 128 ? launch_attn_decode<128>(r, a) : launch_attn_decode<64>(r, a));
+    }
+    NX_TRY(run_gemm(r, NEXUS_K_GEMM_O, L.wo, m.hidden, ws.attn, c->q_dim, EPI_RESIDUAL, ws.x1, x_in, nullptr, m.hidden,
+                    nullptr, 0));
+    NX_TRY(run_rmsnorm(r, ws.x1, L.g2, ws.h));
+    NX_TRY(run_gemm(r, NEXUS_K_GEMM_GATE_UP, L.wgu, 2 * m.ffn, ws.h, m.hidden, EPI_SWIGLU, nullptr, nullptr, nullptr, 0,
+                    ws.act, m.ffn));
+    NX_TRY(run_gemm(r, NEXUS_K_GEMM_DOWN, L.wdown, m.hidden, ws.act, m.ffn, EPI_RESIDUAL, y_out, ws.x1, nullptr, m.hidden,
+                    nullptr, 0));
+    return NEXUS_OK;
+}
+
+static int run_phase(const PhaseRun &r, int layer_begin, int layer_end) {
+    PhaseWs &ws = r.c->ws[r.phase];
+    const bf16_t *x = (const bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->x : r.db->x);
+    bf16_t *y_final = (bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->y : r.db->y);
+    for (int l = layer_begin; l < layer_end; ++l) {
+        bf16_t *y = (l + 1 == layer_end) ? y_final : ws.xbuf[(l - layer_begin) & 1];
+        NX_TRY(run_layer(r, l, x, y));
+        x = y;
+    }
+    return NEXUS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------- validation
+static int check_layers(nexus_ctx *c, int lb, int le) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    if (lb < 0 || le > c->m.n_layers || lb >= le) return fail(NEXUS_EINVAL, "layer range [%d, %d) outside [0, %d)", lb, le, c->m.n_layers);
+    for (int l = lb; l < le; ++l)
+        if (!c->layers[l].loaded) return fail(NEXUS_ESTATE, "layer %d has no weights loaded", l);
+    return NEXUS_OK;
+}
+static int check_kv(nexus_ctx *c, const nexus_kv_cache *kv, int le) {
+    if (!kv || !kv->k_pool || !kv->v_pool) return fail(NEXUS_EINVAL, "null KV cache or pool");
+    if (kv->n_pages <= 0) return fail(NEXUS_EINVAL, "n_pages must be positive");
+    const int64_t need = (int64_t)kv->n_pages * c->kv_dim * kPage * 2;
+    if (le > 1 && kv->layer_stride_bytes < need) return fail(NEXUS_EINVAL, "layer_stride_bytes %lld smaller than one layer's pool (%lld)",
+                                                              (long long)kv->layer_stride_bytes, (long long)need);
+    if (((uintptr_t)kv->k_pool | (uintptr_t)kv->v_pool | (uintptr_t)kv->layer_stride_bytes) & 15) return fail(NEXUS_EINVAL, "KV pools must be 16-byte aligned");
+    return NEXUS_OK;
+}
+static int check_prefill(nexus_ctx *c, const nexus_prefill_batch *b) {
+    if (!b) return fail(NEXUS_EINVAL, "null prefill batch");
+    if (!b->x || !b->y || !b->cu_chunk || !b->prefix_len || !b->page_table) return fail(NEXUS_EINVAL, "null pointer in prefill batch");
+    if (b->n_reqs <= 0 || b->n_tokens <= 0) return fail(NEXUS_EINVAL, "prefill batch needs n_reqs > 0 and n_tokens > 0");
+    if (b->n_reqs > c->lim.max_prefill_reqs || b->n_tokens > c->lim.max_prefill_tokens)
+        return fail(NEXUS_ESHAPE, "prefill batch (%d reqs, %d tokens) exceeds context limits (%d, %d)", b->n_reqs, b->n_tokens,
+                    c->lim.max_prefill_reqs, c->lim.max_prefill_tokens);
+    if (b->max_pages <= 0 || b->max_chunk <= 0 || b->max_chunk > b->n_tokens || b->max_total_len < b->max_chunk)
+        return fail(NEXUS_EINVAL, "inconsistent prefill hints (max_pages %d, max_chunk %d, max_total_len %d)", b->max_pages, b->max_chunk,
+                    b->max_total_len);
+    if (b->max_total_len > c->lim.max_positions) return fail(NEXUS_ESHAPE, "max_total_len %d exceeds max_positions %d", b->max_total_len, c->lim.max_positions);
+    if ((int64_t)b->max_pages * kPage < b->max_total_len) return fail(NEXUS_EINVAL, "page table rows (%d pages) cannot hold max_total_len %d", b->max_pages, b->max_total_len);
+    if (((uintptr_t)b->x | (uintptr_t)b->y) & 15) return fail(NEXUS_EINVAL, "x / y must be 16-byte aligned");
+    return NEXUS_OK;
+}
+static int check_decode(nexus_ctx *c, const nexus_decode_batch *b) {
+    if (!b) return fail(NEXUS_EINVAL, "null decode batch");
+    if (!b->x || !b->y || !b->ctx_len || !b->page_table) return fail(NEXUS_EINVAL, "null pointer in decode batch");
+    if (b->n_reqs <= 0) return fail(NEXUS_EINVAL, "decode batch needs n_reqs > 0");
+    if (b->n_reqs > c->lim.max_decode_reqs) return fail(NEXUS_ESHAPE, "decode batch of %d exceeds limit %d", b->n_reqs, c->lim.max_decode_reqs);
+    if (b->max_pages <= 0 || b->max_ctx <= 0) return fail(NEXUS_EINVAL, "inconsistent decode hints (max_pages %d, max_ctx %d)", b->max_pages, b->max_ctx);
+    if (b->max_ctx > c->lim.max_positions) return fail(NEXUS_ESHAPE, "max_ctx %d exceeds max_positions %d", b->max_ctx, c->lim.max_positions);
+    if ((int64_t)b->max_pages * kPage < b->max_ctx) return fail(NEXUS_EINVAL, "page table rows (%d pages) cannot hold max_ctx %d", b->max_pages, b->max_ctx);
+    if (((uintptr_t)b->x | (uintptr_t)b->y) & 15) return fail(NEXUS_EINVAL, "x / y must be 16-byte aligned");
+    return NEXUS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------- CU masks
+// A CU mask is a bit per CU.  On a multi-die part the driver deals consecutive mask bits to the dies round-robin
+// (bit i -> die i % n_xcd, CU i / n_xcd); bits_xcd_major switches to the other order (bit i -> die i / cus_per_xcd).
+static void set_cu_bit(nexus_ctx *c, std::vector<uint32_t> &mask, int xcd, int cu) {
+    const int bit = c->bits_xcd_major ? xcd * c->cus_per_xcd + cu : cu * c->n_xcd + xcd;
+    mask[bit >> 5] |= 1u << (bit & 31);
+}
+
+static int make_layout(nexus_ctx *c, int p_cus, int d_cus, Layout *out) {
+    Layout L;
+    L.p_cus = p_cus, L.d_cus = d_cus;
+    if (p_cus == 0 && d_cus == 0) {
+        HIP_TRY(hipStreamCreateWithFlags(&L.sp, hipStreamNonBlocking));
+        L.sd = L.sp;
+        L.p_xcd = L.d_xcd = c->n_xcd;
+        *out = L;
+        return NEXUS_OK;
+    }
+    const int words = (c->n_cus + 31) / 32;
+    std::vector<uint32_t> mp(words, 0), md(words, 0);
+    if (c->part_mode == NEXUS_PART_WHOLE_XCD) {
+        const int px = p_cus / c->cus_per_xcd, dx = d_cus / c->cus_per_xcd;
+        for (int x = 0; x < px; ++x)
+            for (int u = 0; u < c->cus_per_xcd; ++u) set_cu_bit(c, mp, x, u);
+        for (int x = c->n_xcd - dx; x < c->n_xcd; ++x)
+            for (int u = 0; u < c->cus_per_xcd; ++u) set_cu_bit(c, md, x, u);
+        L.p_xcd = px, L.d_xcd = dx;
+    } else {
+        const int pu = p_cus / c->n_xcd, du = d_cus / c->n_xcd;
+        for (int x = 0; x < c->n_xcd; ++x) {
+            for (int u = 0; u < pu; ++u) set_cu_bit(c, mp, x, u);
+            for (int u = c->cus_per_xcd - du; u < c->cus_per_xcd; ++u) set_cu_bit(c, md, x, u);
+        }
+        L.p_xcd = L.d_xcd = c->n_xcd;
+    }
+    for (int i = 0; i < words; ++i)
+        if (mp[i] & md[i]) return fail(NEXUS_ESTATE, "internal: CU masks overlap");
+    HIP_TRY(hipExtStreamCreateWithCUMask(&L.sp, words, mp.data()));
+    HIP_TRY(hipExtStreamCreateWithCUMask(&L.sd, words, md.data()));
+    *out = L;
+    return NEXUS_OK;
+}
+
+static void destroy_layout(Layout &L) {
+    if (L.sd && L.sd != L.sp) (void)hipStreamDestroy(L.sd);
+    if (L.sp) (void)hipStreamDestroy(L.sp);
+    L.sp = L.sd = nullptr;
+}
+
+// ---------------------------------------------------------------------------------------------- C ABI
+extern "C" {
+
+const char *nexus_last_error(void) { return g_err; }
+
+int nexus_cu_count(nexus_ctx *c) { return c ? c->n_cus : fail(NEXUS_EINVAL, "null context"); }
+
+void nexus_destroy(nexus_ctx *c) {
+    if (!c) return;
+    DeviceGuard dg(c->device);
+    (void)hipDeviceSynchronize();
+    for (auto &kv : c->layouts) destroy_layout(kv.second);
+    if (c->s_main) (void)hipStreamDestroy(c->s_main);
+    for (auto &L : c->layers) {
+        (void)hipFree(L.g1), (void)hipFree(L.g2), (void)hipFree(L.wqkv), (void)hipFree(L.bqkv), (void)hipFree(L.wo), (void)hipFree(L.wgu),
+            (void)hipFree(L.wdown);
+    }
+    for (auto &w : c->ws) {
+        (void)hipFree(w.h), (void)hipFree(w.qkv), (void)hipFree(w.q), (void)hipFree(w.attn), (void)hipFree(w.x1), (void)hipFree(w.act);
+        (void)hipFree(w.xbuf[0]), (void)hipFree(w.xbuf[1]), (void)hipFree(w.partial), (void)hipFree(w.part_o), (void)hipFree(w.part_ml);
+    }
+    (void)hipFree(c->rope_tab);
+    (void)hipFree(c->probe_counts);
+    for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_sd1})
+        if (e) (void)hipEventDestroy(e);
+    for (auto &t : c->trace_pool) (void)hipEventDestroy(t.a), (void)hipEventDestroy(t.b);
+    delete c;
+}
+
+static int alloc_phase_ws(nexus_ctx *c, int phase, int maxT, int max_reqs) {
+    const nexus_model_desc &m = c->m;
+    PhaseWs &w = c->ws[phase];
+    w.maxT = maxT;
+    const int Tp = round_up(maxT, 32);
+    NX_TRY(dev_alloc(&w.h, p32_elems(Tp, m.hidden), true));
+    NX_TRY(dev_alloc(&w.qkv, (size_t)maxT * c->n_qkv, true));
+    if (phase == NEXUS_PHASE_PREFILL) {
+        w.q_rows = Tp + 32 * max_reqs;
+        NX_TRY(dev_alloc(&w.q, p32_elems(w.q_rows, c->q_dim), true));
+    } else {
+        NX_TRY(dev_alloc(&w.q, (size_t)maxT * c->q_dim, true));
+        w.max_spans = (c->lim.max_positions + kSpan - 1) / kSpan;
+        const int G = m.n_q_heads / m.n_kv_heads;
+        const size_t items = (size_t)maxT * m.n_kv_heads * w.max_spans * G;
+        NX_TRY(dev_alloc(&w.part_o, items * m.head_dim, false));
+        NX_TRY(dev_alloc(&w.part_ml, items * 2, false));
+    }
+    NX_TRY(dev_alloc(&w.attn, p32_elems(Tp, c->q_dim), true));
+    NX_TRY(dev_alloc(&w.x1, (size_t)maxT * m.hidden, true));
+    NX_TRY(dev_alloc(&w.act, p32_elems(Tp, m.ffn), true));
+    if (m.n_layers > 1) {
+        NX_TRY(dev_alloc(&w.xbuf[0], (size_t)maxT * m.hidden, true));
+        NX_TRY(dev_alloc(&w.xbuf[1], (size_t)maxT * m.hidden, true));
+    }
+    size_t pe = 0;
+    const int shapes[4][2] = {{c->n_qkv, m.hidden}, {m.hidden, c->q_dim}, {2 * m.ffn, m.hidden}, {m.hidden, m.ffn}};
+    for (auto &s : shapes)  // the split count depends on T, so take the worst case over every T the phase may see
+        for (int T = 1; T <= maxT; ++T) {
+            const GemmPlan p = plan_gemm(T, s[0] / 32, p32_kp(s[1]));
+            if (p.S > 1) pe = std::max(pe, (size_t)p.S * T * s[0]);
+        }
+    w.partial_elems = pe;
+    NX_TRY(dev_alloc(&w.partial, pe, false));
+    return NEXUS_OK;
+}
+
+int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int device, nexus_ctx **out) {
+    if (!desc || !limits || !out) return fail(NEXUS_EINVAL, "null argument");
+    *out = nullptr;
+    const nexus_model_desc &m = *desc;
+    if (m.hidden <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.ffn <= 0 || m.n_layers <= 0) return fail(NEXUS_EINVAL, "non-positive model dimension");
+    if (m.head_dim != 64 && m.head_dim != 128) return fail(NEXUS_ESHAPE, "head_dim %d not supported (64 or 128)", m.head_dim);
+    if (m.page_size != kPage) return fail(NEXUS_ESHAPE, "page_size %d not supported (16)", m.page_size);
+    if (m.n_q_heads % m.n_kv_heads) return fail(NEXUS_ESHAPE, "n_q_heads %d not a multiple of n_kv_heads %d", m.n_q_heads, m.n_kv_heads);
+    const int G = m.n_q_heads / m.n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 5 && G != 8) return fail(NEXUS_ESHAPE, "query/kv head ratio %d not supported (1, 2, 4, 5, 8)", G);
+    if (m.hidden % 32 || m.ffn % 32) return fail(NEXUS_ESHAPE, "hidden and ffn must be multiples of 32");
+    if (m.hidden > 8192) return fail(NEXUS_ESHAPE, "hidden %d above 8192", m.hidden);
+    if (!(m.rms_eps >= 0.f) || !(m.rope_theta > 0.f)) return fail(NEXUS_EINVAL, "bad rms_eps / rope_theta");
+    if (limits->max_prefill_tokens <= 0 || limits->max_prefill_reqs <= 0 || limits->max_decode_reqs <= 0 || limits->max_positions <= 0)
+        return fail(NEXUS_EINVAL, "limits must be positive");
+    int ndev = 0;
+    HIP_TRY(hipGetDeviceCount(&ndev));
+    if (device < 0 || device >= ndev) return fail(NEXUS_EINVAL, "device %d outside [0, %d)", device, ndev);
+
+    nexus_ctx *c = new (std::nothrow) nexus_ctx();
+    if (!c) return fail(NEXUS_ENOMEM, "out of host memory");
+    c->m = m, c->lim = *limits, c->device = device;
+    c->q_dim = m.n_q_heads * m.head_dim, c->kv_dim = m.n_kv_heads * m.head_dim, c->n_qkv = c->q_dim + 2 * c->kv_dim;
+    c->layers.resize(m.n_layers);
+    DeviceGuard dg(device);
+    int rc = NEXUS_OK;
+    do {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, device) != hipSuccess) { rc = fail(NEXUS_EHIP, "hipGetDeviceProperties failed"); break; }
+        c->n_cus = prop.multiProcessorCount;
+        c->n_xcd = 8;
+        if (c->n_cus % c->n_xcd) c->n_xcd = 1;
+        c->cus_per_xcd = c->n_cus / c->n_xcd;
+        const char *order = getenv("NEXUS_CU_BIT_ORDER");
+        c->bits_xcd_major = order && !strcmp(order, "xcd_major");
+        if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
+        for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_sd1})
+            if (hipEventCreate(e) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
+        if (rc) break;
+        if ((rc = alloc_phase_ws(c, NEXUS_PHASE_PREFILL, limits->max_prefill_tokens, limits->max_prefill_reqs))) break;
+        if ((rc = alloc_phase_ws(c, NEXUS_PHASE_DECODE, limits->max_decode_reqs, limits->max_decode_reqs))) break;
+        const int half = m.head_dim / 2;
+        if ((rc = dev_alloc(&c->rope_tab, (size_t)limits->max_positions * half, false))) break;
+        if ((rc = dev_alloc(&c->probe_counts, 8 * 128, true))) break;
+        const size_t n = (size_t)limits->max_positions * half;
+        hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->s_main, c->rope_tab, limits->max_positions, half,
+                           (double)m.rope_theta);
+        if (hipGetLastError() != hipSuccess || hipStreamSynchronize(c->s_main) != hipSuccess) { rc = fail(NEXUS_EHIP, "rotary table kernel failed"); break; }
+        Layout L;
+        if ((rc = make_layout(c, 0, 0, &L))) break;
+        c->layouts[0] = L;
+        c->cur = &c->layouts[0];
+    } while (0);
+    if (rc) {
+        nexus_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return NEXUS_OK;
+}
+
+int nexus_sync(nexus_ctx *c) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    DeviceGuard dg(c->device);
+    HIP_TRY(hipStreamSynchronize(c->s_main));
+    for (auto &kv : c->layouts) {
+        HIP_TRY(hipStreamSynchronize(kv.second.sp));
+        if (kv.second.sd != kv.second.sp) HIP_TRY(hipStreamSynchronize(kv.second.sd));
+    }
+    return NEXUS_OK;
+}
+
+static int pack_one(nexus_ctx *c, const void *src, int N, int K, int interleave_F, bf16_t **dst) {
+    const int Kp = p32_kp(K), Np = round_up(N, 32);
+    if (!*dst) NX_TRY(dev_alloc(dst, (size_t)Np * Kp, false));
+    const size_t n = (size_t)Np * (Kp / 8);
+    hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->s_main, (const bf16_t *)src, *dst, N, K, Kp,
+                       interleave_F);
+    HIP_TRY(hipGetLastError());
+    return NEXUS_OK;
+}
+
+int nexus_load_layer(nexus_ctx *c, int layer, const nexus_layer_weights *w) {
+    if (!c || !w) return fail(NEXUS_EINVAL, "null argument");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(NEXUS_EINVAL, "layer %d outside [0, %d)", layer, c->m.n_layers);
+    if (!w->attn_norm_g || !w->w_qkv || !w->w_o || !w->ffn_norm_g || !w->w_gate_up || !w->w_down) return fail(NEXUS_EINVAL, "null weight pointer");
+    DeviceGuard dg(c->device);
+    const nexus_model_desc &m = c->m;
+    LayerW &L = c->layers[layer];
+    L.loaded = false;
+    if (!L.g1) NX_TRY(dev_alloc(&L.g1, m.hidden, false));
+    if (!L.g2) NX_TRY(dev_alloc(&L.g2, m.hidden, false));
+    HIP_TRY(hipMemcpyAsync(L.g1, w->attn_norm_g, (size_t)m.hidden * 2, hipMemcpyDeviceToDevice, c->s_main));
+    HIP_TRY(hipMemcpyAsync(L.g2, w->ffn_norm_g, (size_t)m.hidden * 2, hipMemcpyDeviceToDevice, c->s_main));
+    if (w->b_qkv) {
+        if (!L.bqkv) NX_TRY(dev_alloc(&L.bqkv, c->n_qkv, false));
+        HIP_TRY(hipMemcpyAsync(L.bqkv, w->b_qkv, (size_t)c->n_qkv * 2, hipMemcpyDeviceToDevice, c->s_main));
+    } else if (L.bqkv) {
+        (void)hipFree(L.bqkv);
+        L.bqkv = nullptr;
+    }
+    NX_TRY(pack_one(c, w->w_qkv, c->n_qkv, m.hidden, 0, &L.wqkv));
+    NX_TRY(pack_one(c, w->w_o, m.hidden, c->q_dim, 0, &L.wo));
+    NX_TRY(pack_one(c, w->w_gate_up, 2 * m.ffn, m.hidden, m.ffn, &L.wgu));
+    NX_TRY(pack_one(c, w->w_down, m.hidden, m.ffn, 0, &L.wdown));
+    HIP_TRY(hipStreamSynchronize(c->s_main));
+    L.loaded = true;
+    return NEXUS_OK;
+}
+
+static int kv_convert(nexus_ctx *c, const nexus_kv_cache *kv, int layer, void *k_canon, void *v_canon, int32_t page_begin, int32_t page_count,
+                      bool import) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    NX_TRY(check_kv(c, kv, layer + 1));
+    if (!k_canon || !v_canon) return fail(NEXUS_EINVAL, "null canonical buffer");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(NEXUS_EINVAL, "layer %d outside [0, %d)", layer, c->m.n_layers);
+    if (page_begin < 0 || page_count < 0 || (int64_t)page_begin + page_count > kv->n_pages) return fail(NEXUS_EINVAL, "page range [%d, +%d) outside the pool of %d", page_begin, page_count, kv->n_pages);
+    if (page_count == 0) return NEXUS_OK;
+    DeviceGuard dg(c->device);
+    const size_t blk = (size_t)kPage * c->m.head_dim;
+    const size_t off = (size_t)page_begin * c->m.n_kv_heads * blk;
+    bf16_t *kp = (bf16_t *)((char *)kv->k_pool + (size_t)layer * kv->layer_stride_bytes) + off;
+    bf16_t *vp = (bf16_t *)((char *)kv->v_pool + (size_t)layer * kv->layer_stride_bytes) + off;
+    const int n_blocks = page_count * c->m.n_kv_heads;
+    const size_t n = (size_t)n_blocks * blk;
+    dim3 grid((unsigned)((n + 255) / 256));
+    if (import) hipLaunchKernelGGL(kv_convert_kernel<true>, grid, dim3(256), 0, c->s_main, kp, vp, (bf16_t *)k_canon, (bf16_t *)v_canon, n_blocks, c->m.head_dim);
+    else hipLaunchKernelGGL(kv_convert_kernel<false>, grid, dim3(256), 0, c->s_main, kp, vp, (bf16_t *)k_canon, (bf16_t *)v_canon, n_blocks, c->m.head_dim);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(c->s_main));
+    return NEXUS_OK;
+}
+
+int nexus_kv_import(nexus_ctx *c, const nexus_kv_cache *kv, int layer, const void *k_canon, const void *v_canon, int32_t page_begin,
+                    int32_t page_count) {
+    return kv_convert(c, kv, layer, (void *)k_canon, (void *)v_canon, page_begin, page_count, true);
+}
+int nexus_kv_export(nexus_ctx *c, const nexus_kv_cache *kv, int layer, void *k_canon, void *v_canon, int32_t page_begin, int32_t page_count) {
+    return kv_convert(c, kv, layer, k_canon, v_canon, page_begin, page_count, false);
+}
+
+int nexus_set_partition_mode(nexus_ctx *c, int mode) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    if (mode != NEXUS_PART_SLICED && mode != NEXUS_PART_WHOLE_XCD) return fail(NEXUS_EINVAL, "unknown partition mode %d", mode);
+    c->part_mode = mode;
+    return NEXUS_OK;
+}
+
+int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    DeviceGuard dg(c->device);
+    long key = 0;
+    if (prefill_cus == NEXUS_CUS_ALL && decode_cus == NEXUS_CUS_ALL) {
+        prefill_cus = decode_cus = 0;
+    } else {
+        const int gran = c->part_mode == NEXUS_PART_WHOLE_XCD ? c->cus_per_xcd : c->n_xcd;
+        if (prefill_cus <= 0 || decode_cus <= 0) return fail(NEXUS_EINVAL, "CU shares must be positive (or both NEXUS_CUS_ALL)");
+        if (prefill_cus % gran || decode_cus % gran) return fail(NEXUS_EINVAL, "CU shares must be multiples of %d in this partition mode", gran);
+        if (prefill_cus + decode_cus > c->n_cus) return fail(NEXUS_EINVAL, "CU shares %d + %d exceed the device's %d CUs", prefill_cus, decode_cus, c->n_cus);
+        key = ((long)c->part_mode << 40) | ((long)prefill_cus << 20) | decode_cus;
+    }
+    auto it = c->layouts.find(key);
+    if (it == c->layouts.end()) {
+        Layout L;
+        NX_TRY(make_layout(c, prefill_cus, decode_cus, &L));
+        it = c->layouts.emplace(key, L).first;
+    }
+    c->cur = &it->second;
+    return NEXUS_OK;
+}
+
+static PhaseRun make_run(nexus_ctx *c, int phase, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv) {
+    PhaseRun r{};
+    r.c = c, r.phase = phase, r.pb = pb, r.db = db, r.kv = kv;
+    r.s = phase == NEXUS_PHASE_PREFILL ? c->cur->sp : c->cur->sd;
+    r.n_xcd = phase == NEXUS_PHASE_PREFILL ? c->cur->p_xcd : c->cur->d_xcd;
+    r.T = phase == NEXUS_PHASE_PREFILL ? pb->n_tokens : db->n_reqs;
+    return r;
+}
+
+int nexus_prefill_chunk(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_kv_cache *kv) {
+    NX_TRY(check_layers(c, lb, le));
+    NX_TRY(check_kv(c, kv, le));
+    NX_TRY(check_prefill(c, pb));
+    DeviceGuard dg(c->device);
+    return run_phase(make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le);
+}
+
+int nexus_decode_step(nexus_ctx *c, int lb, int le, const nexus_decode_batch *db, const nexus_kv_cache *kv) {
+    NX_TRY(check_layers(c, lb, le));
+    NX_TRY(check_kv(c, kv, le));
+    NX_TRY(check_decode(c, db));
+    DeviceGuard dg(c->device);
+    return run_phase(make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le);
+}
+
+int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
+                     void *caller_stream, nexus_step_timing *timing) {
+    NX_TRY(check_layers(c, lb, le));
+    NX_TRY(check_kv(c, kv, le));
+    NX_TRY(check_prefill(c, pb));
+    NX_TRY(check_decode(c, db));
+    DeviceGuard dg(c->device);
+    Layout *L = c->cur;
+    hipStream_t cs = (hipStream_t)caller_stream;
+    const bool split = L->sd != L->sp;
+    if (cs) {
+        HIP_TRY(hipEventRecord(c->ev_caller, cs));
+        HIP_TRY(hipStreamWaitEvent(L->sp, c->ev_caller, 0));
+        if (split) HIP_TRY(hipStreamWaitEvent(L->sd, c->ev_caller, 0));
+    }
+    if (split) {
+        // fork: the decode stream starts when the prefill stream reaches this point
+        HIP_TRY(hipEventRecord(c->ev_fork, L->sp));
+        HIP_TRY(hipStreamWaitEvent(L->sd, c->ev_fork, 0));
+    }
+    if (timing) {
+        HIP_TRY(hipEventRecord(c->ev_sp0, L->sp));
+        if (split) HIP_TRY(hipEventRecord(c->ev_sd0, L->sd));
+    }
+    NX_TRY(run_phase(make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le));
+    if (timing) HIP_TRY(hipEventRecord(c->ev_sp1, L->sp));
+    NX_TRY(run_phase(make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le));
+    if (timing || (cs && split)) HIP_TRY(hipEventRecord(c->ev_sd1, L->sd));
+    if (cs) {
+        if (split) {
+            if (!timing) HIP_TRY(hipEventRecord(c->ev_sp1, L->sp));
+            HIP_TRY(hipStreamWaitEvent(cs, c->ev_sp1, 0));
+            HIP_TRY(hipStreamWaitEvent(cs, c->ev_sd1, 0));
+        } else {
+            HIP_TRY(hipEventRecord(c->ev_fork, L->sp));
+            HIP_TRY(hipStreamWaitEvent(cs, c->ev_fork, 0));
+        }
+    }
+    if (timing) {
+        HIP_TRY(hipStreamSynchronize(L->sp));
+        if (split) HIP_TRY(hipStreamSynchronize(L->sd));
+        float tp = 0, td = 0;
+        HIP_TRY(hipEventElapsedTime(&tp, c->ev_sp0, c->ev_sp1));
+        if (split) {
+            float d0 = 0, pd = 0;
+            HIP_TRY(hipEventElapsedTime(&td, c->ev_sd0, c->ev_sd1));
+            HIP_TRY(hipEventElapsedTime(&pd, c->ev_sp0, c->ev_sd1));  // prefill start -> decode end
+            HIP_TRY(hipEventElapsedTime(&d0, c->ev_sp0, c->ev_sd0));  // start skew (may be negative)
+            const float start = std::min(0.f, d0);
+            timing->t_prefill_ms = tp, timing->t_decode_ms = td;
+            timing->t_step_ms = std::max(tp, pd) - start;
+        } else {
+            HIP_TRY(hipEventElapsedTime(&td, c->ev_sp0, c->ev_sd1));  // decode waits for prefill: its latency includes it
+            timing->t_prefill_ms = tp, timing->t_decode_ms = td, timing->t_step_ms = td;
+        }
+    }
+    return NEXUS_OK;
+}
+
+static float median(std::vector<float> v) {
+    std::sort(v.begin(), v.end());
+    return v[v.size() / 2];
+}
+
+static int time_phase(nexus_ctx *c, int phase, int lb, int le, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
+                      int repeats, float *out_ms) {
+    std::vector<float> t;
+    hipStream_t s = phase == NEXUS_PHASE_PREFILL ? c->cur->sp : c->cur->sd;
+    for (int i = 0; i < repeats + 1; ++i) {
+        HIP_TRY(hipEventRecord(c->ev_sp0, s));
+        NX_TRY(run_phase(make_run(c, phase, pb, db, kv), lb, le));
+        HIP_TRY(hipEventRecord(c->ev_sp1, s));
+        HIP_TRY(hipStreamSynchronize(s));
+        float ms = 0;
+        HIP_TRY(hipEventElapsedTime(&ms, c->ev_sp0, c->ev_sp1));
+        if (i) t.push_back(ms);  // first run is the warm-up
+    }
+    *out_ms = median(t);
+    return NEXUS_OK;
+}
+
+// The selection rule; kept free of HIP so that the host tests can drive it with synthetic curves.
+int nexus_choose_split(int n, const float *t_p, const float *t_d, const float *t_step, float t_p_all, float t_d_all, int policy, float alpha,
+                       float beta) {
+    if (n <= 0 || !t_p || !t_d || !t_step) return fail(NEXUS_EINVAL, "bad curve arguments");
+    if (policy < 0 || policy > 2) return fail(NEXUS_EINVAL, "unknown policy %d", policy);
+    int best = -1;
+    if (policy == NEXUS_POLICY_MIN_STEP) {
+        for (int i = 0; i < n; ++i)
+            if (best < 0 || t_step[i] < t_step[best]) best = i;
+        return best;
+    }
+    const bool pp = policy == NEXUS_POLICY_PREFILL_PRIORITIZED;
+    const float *obj = pp ? t_p : t_d, *con = pp ? t_d : t_p;
+    const double bound = pp ? (double)beta * t_d_all : (double)alpha * t_p_all;
+    for (int i = 0; i < n; ++i)
+        if ((double)con[i] <= bound && (best < 0 || obj[i] < obj[best])) best = i;
+    if (best < 0)  // nothing meets the slack: take the candidate that violates it least
+        for (int i = 0; i < n; ++i)
+            if (best < 0 || con[i] < con[best]) best = i;
+    return best;
+}
+
+int nexus_profile_split(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
+                        const int32_t *cand, int n_cand, int policy, float alpha, float beta, int repeats, float *t_p, float *t_d, float *t_s,
+                        float *t_all, int32_t *chosen) {
+    NX_TRY(check_layers(c, lb, le));
+    NX_TRY(check_kv(c, kv, le));
+    NX_TRY(check_prefill(c, pb));
+    NX_TRY(check_decode(c, db));
+    if (!cand || n_cand <= 0 || !t_p || !t_d || !t_s || !t_all || !chosen) return fail(NEXUS_EINVAL, "null output or no candidates");
+    if (policy < 0 || policy > 2) return fail(NEXUS_EINVAL, "unknown policy %d", policy);
+    if (repeats <= 0) return fail(NEXUS_EINVAL, "repeats must be positive");
+    const int gran = c->part_mode == NEXUS_PART_WHOLE_XCD ? c->cus_per_xcd : c->n_xcd;
+    for (int i = 0; i < n_cand; ++i)
+        if (cand[i] <= 0 || cand[i] >= c->n_cus || cand[i] % gran || (c->n_cus - cand[i]) % gran)
+            return fail(NEXUS_EINVAL, "candidate %d (%d prefill CUs) is not a valid split of %d CUs at granularity %d", i, cand[i], c->n_cus, gran);
+    DeviceGuard dg(c->device);
+    NX_TRY(nexus_sync(c));
+    NX_TRY(nexus_set_cu_split(c, NEXUS_CUS_ALL, NEXUS_CUS_ALL));
+    NX_TRY(time_phase(c, NEXUS_PHASE_PREFILL, lb, le, pb, nullptr, kv, repeats, &t_all[0]));
+    NX_TRY(time_phase(c, NEXUS_PHASE_DECODE, lb, le, nullptr, db, kv, repeats, &t_all[1]));
+    for (int i = 0; i < n_cand; ++i) {
+        NX_TRY(nexus_set_cu_split(c, cand[i], c->n_cus - cand[i]));
+        NX_TRY(time_phase(c, NEXUS_PHASE_PREFILL, lb, le, pb, nullptr, kv, repeats, &t_p[i]));
+        NX_TRY(time_phase(c, NEXUS_PHASE_DECODE, lb, le, nullptr, db, kv, repeats, &t_d[i]));
+        std::vector<float> ts;
+        for (int k = 0; k < repeats + 1; ++k) {
+            nexus_step_timing tm;
+            NX_TRY(nexus_mixed_step(c, lb, le, pb, db, kv, nullptr, &tm));
+            if (k) ts.push_back(tm.t_step_ms);
+        }
+        t_s[i] = median(ts);
+    }
+    const int best = nexus_choose_split(n_cand, t_p, t_d, t_s, t_all[0], t_all[1], policy, alpha, beta);
+    if (best < 0) return best;
+    *chosen = cand[best];
+    return nexus_set_cu_split(c, cand[best], c->n_cus - cand[best]);
+}
+
+int nexus_trace_begin(nexus_ctx *c, int phase, int kernel) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    if (phase < 0 || phase > 1 || kernel < 0 || kernel >= NEXUS_K_COUNT) return fail(NEXUS_EINVAL, "bad phase / kernel id");
+    DeviceGuard dg(c->device);
+    if (c->trace_pool.empty()) {
+        c->trace_pool.resize(4096);
+        for (auto &t : c->trace_pool) {
+            HIP_TRY(hipEventCreate(&t.a));
+            HIP_TRY(hipEventCreate(&t.b));
+        }
+    }
+    c->trace_used = 0;
+    c->trace_phase = phase, c->trace_kernel = kernel;
+    return NEXUS_OK;
+}
+
+int nexus_trace_read(nexus_ctx *c, float *mean_ms, int32_t *launches) {
+    if (!c || !mean_ms || !launches) return fail(NEXUS_EINVAL, "null argument");
+    DeviceGuard dg(c->device);
+    c->trace_phase = c->trace_kernel = -1;
+    NX_TRY(nexus_sync(c));
+    double sum = 0;
+    for (size_t i = 0; i < c->trace_used; ++i) {
+        float ms = 0;
+        HIP_TRY(hipEventElapsedTime(&ms, c->trace_pool[i].a, c->trace_pool[i].b));
+        sum += ms;
+    }
+    *launches = (int32_t)c->trace_used;
+    *mean_ms = c->trace_used ? (float)(sum / c->trace_used) : 0.f;
+    c->trace_used = 0;
+    return NEXUS_OK;
+}
+
+int nexus_debug_fetch(nexus_ctx *c, int phase, int which, int32_t n_tokens, void *out) {
+    if (!c || !out) return fail(NEXUS_EINVAL, "null argument");
+    if (phase < 0 || phase > 1) return fail(NEXUS_EINVAL, "bad phase");
+    PhaseWs &w = c->ws[phase];
+    if (n_tokens <= 0 || n_tokens > w.maxT) return fail(NEXUS_EINVAL, "n_tokens outside the workspace");
+    DeviceGuard dg(c->device);
+    NX_TRY(nexus_sync(c));
+    const bf16_t *src = nullptr;
+    int K = 0;
+    bool p32 = true;
+    switch (which) {
+        case NEXUS_BUF_NORM1: return fail(NEXUS_ESTATE, "the first norm's output is overwritten by the second norm within a layer");
+        case NEXUS_BUF_Q: src = w.q, K = c->q_dim, p32 = phase == NEXUS_PHASE_PREFILL; break;
+        case NEXUS_BUF_ATTN: src = w.attn, K = c->q_dim; break;
+        case NEXUS_BUF_X1: src = w.x1, K = c->m.hidden, p32 = false; break;
+        case NEXUS_BUF_ACT: src = w.act, K = c->m.ffn; break;
+        default: return fail(NEXUS_EINVAL, "unknown buffer id %d", which);
+    }
+    if (!p32) {
+        HIP_TRY(hipMemcpyAsync(out, src, (size_t)n_tokens * K * 2, hipMemcpyDeviceToDevice, c->s_main));
+    } else {
+        // prefill queries sit in request-aligned tiles; callers with one request (or 32-aligned chunks) see rows in order
+        const size_t n = (size_t)n_tokens * K;
+        hipLaunchKernelGGL(unpack_p32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->s_main, src, (bf16_t *)out, n_tokens, K, p32_kp(K),
+                           (const int32_t *)nullptr);
+        HIP_TRY(hipGetLastError());
+    }
+    HIP_TRY(hipStreamSynchronize(c->s_main));
+    return NEXUS_OK;
+}
+
+int nexus_debug_cu_probe(nexus_ctx *c, int phase, int n_blocks, int32_t *out_counts) {
+    if (!c || !out_counts) return fail(NEXUS_EINVAL, "null argument");
+    if (phase < 0 || phase > 1 || n_blocks <= 0 || n_blocks > (1 << 20)) return fail(NEXUS_EINVAL, "bad phase or block count");
+    DeviceGuard dg(c->device);
+    hipStream_t s = phase == NEXUS_PHASE_PREFILL ? c->cur->sp : c->cur->sd;
+    HIP_TRY(hipMemsetAsync(c->probe_counts, 0, 8 * 128 * sizeof(int32_t), s));
+    hipLaunchKernelGGL(cu_probe_kernel, dim3(n_blocks), dim3(64), 0, s, c->probe_counts);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipMemcpy(out_counts, c->probe_counts, 8 * 128 * sizeof(int32_t), hipMemcpyDeviceToHost));
+    return NEXUS_OK;
+}
+
+}  // extern "C"
