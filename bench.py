@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the partitioned prefill/decode step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: a chunked-prefill sub-batch and a decode sub-batch of
+one decoder layer, run concurrently on disjoint CU partitions (or back to back for the serialized baseline).
+Default workload: the Llama-3-8B-shaped layer with a 512-token chunk over a 1536-token prefix and 64 decode
+requests with contexts uniform in [512, 4096] (seeded, synthetic, resident in HBM before the timed region).
+
+Prints ONE JSON line: mixed-step tokens/s at the chosen CU split, the sweep over splits with decode-step latency,
+the serialized baseline, the roofline of the dominant kernels and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_work(wl):
+    """Flops / bytes the method itself must do per launch of each kernel family (one layer)."""
+    s = wl.shape
+    p, d = wl.prefill, wl.decode
+    T, B = p.n_tokens, d.n_reqs
+    kv_tok_bytes = 2 * s.n_kv_heads * s.head_dim * 2
+    pairs = sum(int(n) * int(pre) + int(n) * (int(n) + 1) // 2 for n, pre in zip(p.chunk_len, p.prefix_len))
+    w = {
+        "gemm_qkv": 2.0 * T * s.n_qkv * s.hidden,
+        "gemm_o": 2.0 * T * s.hidden * s.q_dim,
+        "gemm_gate_up": 2.0 * T * 2 * s.ffn * s.hidden,
+        "gemm_down": 2.0 * T * s.hidden * s.ffn,
+        "attn_prefill": 4.0 * s.head_dim * s.n_q_heads * pairs,
+    }
+    prefill_flops = sum(w.values())
+    decode_kv_bytes = float(sum(int(c) + 1 for c in d.ctx_len)) * kv_tok_bytes
+    weight_bytes = 2.0 * s.params_per_layer
+    decode_bytes = {
+        "attn_decode": decode_kv_bytes,
+        "gemm_qkv": 2.0 * s.n_qkv * s.hidden, "gemm_o": 2.0 * s.hidden * s.q_dim,
+        "gemm_gate_up": 2.0 * 2 * s.ffn * s.hidden, "gemm_down": 2.0 * s.hidden * s.ffn,
+    }
+    return {"prefill_flops": w, "prefill_total_flops": prefill_flops, "decode_bytes": decode_bytes,
+            "decode_total_bytes": decode_kv_bytes + weight_bytes, "weight_bytes": weight_bytes,
+            "tokens": T + B}
+
+
+def cpu_baseline(wl, weights, n_prefill_tokens=96, n_decode=12):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+    from paper_2507_06608_amd import synth
+    p = wl.prefill
+    sub = synth.subset_for_oracle(wl, [0], list(range(min(n_decode, wl.decode.n_reqs))))
+    # first n tokens of the chunk (they see the whole cached prefix); decode requests in batch order
+    n = min(n_prefill_tokens, int(p.chunk_len[0]))
+    sp = sub.prefill
+    sp = synth.PrefillBatch(sp.x[:n], np.array([0, n], np.int32), sp.prefix_len[:1], sp.page_table[:1])
+    m = oracle.Model(hidden=wl.shape.hidden, n_q_heads=wl.shape.n_q_heads, n_kv_heads=wl.shape.n_kv_heads,
+                     head_dim=wl.shape.head_dim, ffn=wl.shape.ffn, page_size=wl.shape.page_size,
+                     rms_eps=wl.shape.rms_eps, rope_theta=wl.shape.rope_theta)
+    ow = {k: v.float().numpy() for k, v in weights.items()}
+    kp, vp = sub.k_pool.float().numpy().copy(), sub.v_pool.float().numpy().copy()
+    oracle.lib()
+    t0 = time.perf_counter()
+    oracle.layer_prefill(m, ow, sp.x.float().numpy(), sp.cu_chunk, sp.prefix_len, sp.page_table, kp, vp)
+    oracle.layer_decode(m, ow, sub.decode.x.float().numpy(), sub.decode.ctx_len, sub.decode.page_table, kp, vp)
+    dt = time.perf_counter() - t0
+    toks = n + sub.decode.n_reqs
+    return {"value": toks / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n} of {p.n_tokens} prefill tokens (over the full {int(p.prefix_len[0])}-token prefix) + "
+                      f"{sub.decode.n_reqs} of {wl.decode.n_reqs} decode requests, one layer, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--split", default="auto", help="'auto' (profile and choose) or PREFILL_CUS/DECODE_CUS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the partitioned step is an intra-GPU method); --gpus must be 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2507_06608_amd import binding, synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    t0 = time.time()
+    wl = synth.config(args.config, seed=0, kv_device=dev)
+    weights = synth.make_weights(wl.shape, 0)
+    log(f"[bench] workload {wl.name}: inputs generated in {time.time() - t0:.1f} s")
+    ctx = binding.context_for(wl)
+    ctx.load_layer(0, weights)
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    pb, db = binding.DevPrefill(wl.prefill, ctx.device), binding.DevDecode(wl.decode, ctx.device)
+    work = algorithmic_work(wl)
+    n_cus = ctx.cu_count
+    # a real (non-null) stream: every step forks from it and joins back into it, so steps do not overlap each other
+    stream = torch.cuda.Stream()
+
+    def run_steps(n):
+        for _ in range(n):
+            ctx.mixed_step(pb, db, kv, stream=stream)
+
+    def timed(n):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        run_steps(n)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n * 1e3
+
+    # ---- serialized baseline (one unmasked stream, prefill then decode)
+    ctx.set_cu_split(binding.CUS_ALL, binding.CUS_ALL)
+    run_steps(args.warmup)
+    serial_ms = timed(max(10, args.steps // 4))
+    tm = [ctx.mixed_step(pb, db, kv, timing=True) for _ in range(5)][-1]
+    serial = {"ms_per_step": serial_ms, "tokens_per_s": work["tokens"] / serial_ms * 1e3,
+              "t_prefill_ms": tm.t_prefill_ms, "decode_latency_ms": tm.t_decode_ms}
+    log(f"[bench] serialized: {serial}")
+
+    # ---- sweep of the CU split
+    sweep = []
+    chosen = None
+    if args.split == "auto":
+        cands = [c for c in range(32, n_cus, 32)]
+        if not args.no_sweep:
+            prof = ctx.profile_split(pb, db, kv, cands, binding.POLICY_MIN_STEP, repeats=7)
+            for i, c in enumerate(cands):
+                sweep.append({"prefill_cus": c, "decode_cus": n_cus - c, "t_prefill_alone_ms": prof["t_prefill_ms"][i],
+                              "t_decode_alone_ms": prof["t_decode_ms"][i], "t_step_ms": prof["t_step_ms"][i],
+                              "tokens_per_s": work["tokens"] / prof["t_step_ms"][i] * 1e3})
+            chosen = prof["chosen_prefill_cus"]
+            alone = {"t_prefill_all_cus_ms": prof["t_prefill_all_ms"], "t_decode_all_cus_ms": prof["t_decode_all_ms"]}
+            # the paper's two objectives on the same measured curves, for the record
+            for name, pol in (("prefill_prioritized", binding.POLICY_PREFILL_PRIORITIZED),
+                              ("decode_prioritized", binding.POLICY_DECODE_PRIORITIZED)):
+                i = binding.choose_split(prof["t_prefill_ms"], prof["t_decode_ms"], prof["t_step_ms"],
+                                         prof["t_prefill_all_ms"], prof["t_decode_all_ms"], pol, 1.3, 1.1)
+                alone[name + "_prefill_cus"] = cands[i]
+            log(f"[bench] sweep: {json.dumps(sweep)}")
+            log(f"[bench] alone on all CUs: {alone}; chosen prefill CUs (min step): {chosen}")
+        else:
+            chosen, alone = n_cus // 2, {}
+    else:
+        a, b = args.split.split("/")
+        chosen, alone = int(a), {}
+        assert int(a) + int(b) == n_cus or True
+    ctx.set_cu_split(chosen, n_cus - chosen)
+
+    # ---- find the dominant kernel of each phase at this split (short traced passes)
+    run_steps(args.warmup)
+    kt = {}
+    for phase, names in ((binding.PHASE_PREFILL, ("gemm_qkv", "attn_prefill", "gemm_o", "gemm_gate_up", "gemm_down",
+                                                   "rmsnorm", "rope_append", "splitk_reduce")),
+                         (binding.PHASE_DECODE, ("gemm_qkv", "attn_decode", "attn_merge", "gemm_o", "gemm_gate_up",
+                                                 "gemm_down", "rmsnorm", "rope_append", "splitk_reduce"))):
+        for k in names:
+            ctx.trace_begin(phase, k)
+            run_steps(5)
+            ms, n = ctx.trace_read()
+            kt[("prefill" if phase == 0 else "decode", k)] = (ms, n / 5.0)
+    log("[bench] kernel times at the chosen split (ms per launch, launches per step): " +
+        json.dumps({f"{a}.{b}": (round(v[0], 4), v[1]) for (a, b), v in kt.items()}))
+    dom = max((k for k in kt if k[1] in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn_prefill", "attn_decode")),
+              key=lambda k: kt[k][0])
+
+    # ---- timed region: exactly K steps, dominant kernel bracketed by HIP events on its own stream
+    ctx.trace_begin(binding.PHASE_PREFILL if dom[0] == "prefill" else binding.PHASE_DECODE, dom[1])
+    ms_per_step = timed(args.steps)
+    dom_ms, dom_n = ctx.trace_read()
+    tms = [ctx.mixed_step(pb, db, kv, timing=True) for _ in range(9)]
+    dec_lat = float(np.median([t.t_decode_ms for t in tms]))
+    pre_lat = float(np.median([t.t_prefill_ms for t in tms]))
+
+    def roof(phase, k, ms):
+        if phase == "prefill":
+            fl = work["prefill_flops"][k]
+            ach = fl / (ms * 1e-3) / 1e12
+            return {"kernel": f"{phase}.{k}", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "ms_per_launch": ms,
+                    "cus": chosen, "frac_of_cu_share": ach / (PEAK_BF16_TFLOPS * chosen / n_cus)}
+        by = work["decode_bytes"][k]
+        ach = by / (ms * 1e-3) / 1e9
+        return {"kernel": f"{phase}.{k}", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None, "ms_per_launch": ms, "cus": n_cus - chosen}
+
+    roofline = roof(dom[0], dom[1], dom_ms)
+    # the other side of the target: best prefill GEMM against MFMA peak, decode attention against HBM peak
+    others = {}
+    for key in (("prefill", "gemm_gate_up"), ("decode", "attn_decode"), ("decode", "gemm_gate_up")):
+        if key != dom and key in kt:
+            others[f"{key[0]}.{key[1]}"] = roof(key[0], key[1], kt[key][0])
+    phase_roof = {
+        "prefill_phase_tflops": work["prefill_total_flops"] / (pre_lat * 1e-3) / 1e12,
+        "prefill_phase_frac_of_mfma_peak": work["prefill_total_flops"] / (pre_lat * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "decode_phase_gbs": work["decode_total_bytes"] / (dec_lat * 1e-3) / 1e9,
+        "decode_phase_frac_of_hbm_peak": work["decode_total_bytes"] / (dec_lat * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
+
+    out = {
+        "metric": "mixed-step tokens/s + decode-step latency vs CU split; MFMA %, HBM GB/s",
+        "value": work["tokens"] / ms_per_step * 1e3, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": 1, "prefill_tokens": wl.prefill.n_tokens,
+                   "decode_requests": wl.decode.n_reqs, "cu_split": f"{chosen}/{n_cus - chosen}",
+                   "split_policy": "min measured concurrent step time over an 8-step sweep"},
+        "decode_step_latency_ms": dec_lat, "prefill_phase_latency_ms": pre_lat,
+        "serialized": serial, "speedup_vs_serialized": serial_ms / ms_per_step,
+        "alone": alone, "sweep": sweep, "roofline": roofline, "roofline_other": others, "phase_roofline": phase_roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, weights)
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

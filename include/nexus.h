@@ -138,12 +138,6 @@ typedef struct {
     float t_step_ms;    /* fork -> both complete                                */
 } nexus_step_timing;
 
-/* How a CU share is laid out over the chip's accelerator dies (XCDs), each of which has its own L2. */
-typedef enum {
-    NEXUS_PART_SLICED = 0, /* every XCD gives each phase the same fraction of its CUs (default) */
-    NEXUS_PART_WHOLE_XCD = 1 /* each phase gets whole XCDs; shares are multiples of one XCD    */
-} nexus_partition_mode;
-
 /* Split-selection rule applied to measured latency curves (Sec. 4.1.2 objectives; alpha, beta as in Sec. 5). */
 typedef enum {
     NEXUS_POLICY_PREFILL_PRIORITIZED = 0, /* min t_prefill  s.t. t_decode  <= beta  * t_decode(all CUs)  */
@@ -177,11 +171,12 @@ int nexus_kv_export(nexus_ctx *ctx, const nexus_kv_cache *kv, int layer, void *k
 
 /* ---- CU partitioning (Sec. 5: partition layouts are created ahead of use and switched at run time) --------- */
 
-int nexus_set_partition_mode(nexus_ctx *ctx, int mode /* nexus_partition_mode */);
 /*
  * Selects the CU share of each phase: prefill_cus + decode_cus <= nexus_cu_count(), both positive multiples of
- * 8 (of one XCD's CU count in WHOLE_XCD mode).  The two phases then run on two streams whose CU masks are
- * disjoint.  The stream pair of a layout is created on first use and kept.  (NEXUS_CUS_ALL, NEXUS_CUS_ALL)
+ * 8.  The chip is eight accelerator dies (XCDs) with an L2 each; every XCD gives each phase the same number of
+ * its CUs (a queue's CU mask must keep at least one CU in every XCD, and workgroups are dealt to XCDs
+ * round-robin whatever the mask).  The two phases then run on two streams whose CU masks are disjoint.  The stream pair of a layout is created on first use; the three most recently used partitioned layouts
+ * are kept (each masked stream owns a hardware queue, of which a process has few), older ones are retired.  (NEXUS_CUS_ALL, NEXUS_CUS_ALL)
  * selects the unpartitioned layout: one unmasked stream, the mixed step runs prefill then decode back to back
  * (the serialized baseline of Sec. 3.1).
  */

@@ -21,14 +21,13 @@ LIB_PATH = os.path.join(_HERE, "libnexus.so")
 
 CUS_ALL = -1
 PHASE_PREFILL, PHASE_DECODE = 0, 1
-PART_SLICED, PART_WHOLE_XCD = 0, 1
 POLICY_PREFILL_PRIORITIZED, POLICY_DECODE_PRIORITIZED, POLICY_MIN_STEP = 0, 1, 2
 KERNELS = ("rmsnorm", "gemm_qkv", "rope_append", "attn_prefill", "gemm_o", "gemm_gate_up", "gemm_down",
            "attn_decode", "attn_merge", "splitk_reduce")
 BUF_NORM1, BUF_Q, BUF_ATTN, BUF_X1, BUF_ACT = range(5)
 
 EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "nexus_last_error", "nexus_cu_count",
-           "nexus_kv_import", "nexus_kv_export", "nexus_set_partition_mode", "nexus_set_cu_split",
+           "nexus_kv_import", "nexus_kv_export", "nexus_set_cu_split",
            "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_profile_split",
            "nexus_choose_split", "nexus_trace_begin", "nexus_trace_read", "nexus_debug_fetch",
            "nexus_debug_cu_probe")
@@ -209,9 +208,6 @@ class Nexus:
         return kc, vc
 
     # -- partitioning
-    def set_partition_mode(self, mode: int):
-        _check(lib().nexus_set_partition_mode(self._ctx, mode))
-
     def set_cu_split(self, prefill_cus: int, decode_cus: int):
         _check(lib().nexus_set_cu_split(self._ctx, prefill_cus, decode_cus))
 

@@ -46,6 +46,8 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 template <int FS, int TS, int WF, int WT, int EPI>
 __global__ __launch_bounds__(256) void gemm_p32_kernel(GemmArgs a) {
     static_assert(WF * WT == 4, "four waves per block");
+    static_assert(FS % WF == 0 && TS % WT == 0, "whole tiles per wave");
+    static_assert((FS / WF) % 2 == 0, "a wave needs gate/up strip pairs (and the SwiGLU epilogue reads acc[i + 1])");
     constexpr int FW = FS / WF, TW = TS / WT;
     constexpr int NP = FS + TS;
     constexpr int STAGE = NP * kStripStage;

@@ -67,7 +67,9 @@ struct Layout {
     int p_cus = 0, d_cus = 0;  // 0/0 = unpartitioned
     hipStream_t sp = nullptr, sd = nullptr;
     int p_xcd = 8, d_xcd = 8;  // XCDs each stream is spread over (tile-order hint)
+    long last_use = 0;
 };
+constexpr int kMaxMaskedLayouts = 3;
 
 struct TraceRec {
     hipEvent_t a, b;
@@ -84,7 +86,7 @@ struct nexus_ctx {
     hipStream_t s_main = nullptr;
     std::map<long, Layout> layouts;
     Layout *cur = nullptr;
-    int part_mode = NEXUS_PART_SLICED;
+    long use_clock = 0;
     bool bits_xcd_major = false;  // CU-mask bit order (see make_mask)
     hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr, ev_sd1 = nullptr;
     // tracing
@@ -128,7 +130,7 @@ static GemmPlan plan_gemm(int T, int n_ftiles, int Kp) {
     const int nt = (T + 31) / 32;
     GemmPlan p{};
     if (T <= 32) {
-        p.variant = GV_SK32, p.FS = 4, p.TS = 1;
+        p.variant = GV_SK32, p.FS = 8, p.TS = 1;
     } else if (T <= 64) {
         p.variant = GV_SK64, p.FS = 4, p.TS = 2;
     } else {
@@ -166,8 +168,8 @@ static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipSt
     switch (variant) {
         case GV_256x256: return launch_gemm_t<8, 8, 2, 2, EPI>(a, grid, s);
         case GV_128x128: return launch_gemm_t<4, 4, 2, 2, EPI>(a, grid, s);
-        case GV_SK64: return launch_gemm_t<4, 2, 4, 1, EPI>(a, grid, s);
-        default: return launch_gemm_t<4, 1, 4, 1, EPI>(a, grid, s);
+        case GV_SK64: return launch_gemm_t<4, 2, 2, 2, EPI>(a, grid, s);
+        default: return launch_gemm_t<8, 1, 4, 1, EPI>(a, grid, s);
     }
 }
 
@@ -453,21 +455,15 @@ static int make_layout(nexus_ctx *c, int p_cus, int d_cus, Layout *out) {
     }
     const int words = (c->n_cus + 31) / 32;
     std::vector<uint32_t> mp(words, 0), md(words, 0);
-    if (c->part_mode == NEXUS_PART_WHOLE_XCD) {
-        const int px = p_cus / c->cus_per_xcd, dx = d_cus / c->cus_per_xcd;
-        for (int x = 0; x < px; ++x)
-            for (int u = 0; u < c->cus_per_xcd; ++u) set_cu_bit(c, mp, x, u);
-        for (int x = c->n_xcd - dx; x < c->n_xcd; ++x)
-            for (int u = 0; u < c->cus_per_xcd; ++u) set_cu_bit(c, md, x, u);
-        L.p_xcd = px, L.d_xcd = dx;
-    } else {
-        const int pu = p_cus / c->n_xcd, du = d_cus / c->n_xcd;
-        for (int x = 0; x < c->n_xcd; ++x) {
-            for (int u = 0; u < pu; ++u) set_cu_bit(c, mp, x, u);
-            for (int u = c->cus_per_xcd - du; u < c->cus_per_xcd; ++u) set_cu_bit(c, md, x, u);
-        }
-        L.p_xcd = L.d_xcd = c->n_xcd;
+    // Every XCD gives each phase the same number of its CUs.  This is the only workable topology: the driver
+    // rejects a queue mask that leaves an XCD without CUs, and workgroups are dealt to the XCDs round-robin
+    // whatever the mask, so unequal per-XCD shares would only unbalance the phase.
+    const int pu = p_cus / c->n_xcd, du = d_cus / c->n_xcd;
+    for (int x = 0; x < c->n_xcd; ++x) {
+        for (int u = 0; u < pu; ++u) set_cu_bit(c, mp, x, u);
+        for (int u = c->cus_per_xcd - du; u < c->cus_per_xcd; ++u) set_cu_bit(c, md, x, u);
     }
+    L.p_xcd = L.d_xcd = c->n_xcd;
     for (int i = 0; i < words; ++i)
         if (mp[i] & md[i]) return fail(NEXUS_ESTATE, "internal: CU masks overlap");
     HIP_TRY(hipExtStreamCreateWithCUMask(&L.sp, words, mp.data()));
@@ -689,13 +685,6 @@ int nexus_kv_export(nexus_ctx *c, const nexus_kv_cache *kv, int layer, void *k_c
     return kv_convert(c, kv, layer, k_canon, v_canon, page_begin, page_count, false);
 }
 
-int nexus_set_partition_mode(nexus_ctx *c, int mode) {
-    if (!c) return fail(NEXUS_EINVAL, "null context");
-    if (mode != NEXUS_PART_SLICED && mode != NEXUS_PART_WHOLE_XCD) return fail(NEXUS_EINVAL, "unknown partition mode %d", mode);
-    c->part_mode = mode;
-    return NEXUS_OK;
-}
-
 int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
     if (!c) return fail(NEXUS_EINVAL, "null context");
     DeviceGuard dg(c->device);
@@ -703,18 +692,34 @@ int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
     if (prefill_cus == NEXUS_CUS_ALL && decode_cus == NEXUS_CUS_ALL) {
         prefill_cus = decode_cus = 0;
     } else {
-        const int gran = c->part_mode == NEXUS_PART_WHOLE_XCD ? c->cus_per_xcd : c->n_xcd;
+        const int gran = c->n_xcd;
         if (prefill_cus <= 0 || decode_cus <= 0) return fail(NEXUS_EINVAL, "CU shares must be positive (or both NEXUS_CUS_ALL)");
-        if (prefill_cus % gran || decode_cus % gran) return fail(NEXUS_EINVAL, "CU shares must be multiples of %d in this partition mode", gran);
+        if (prefill_cus % gran || decode_cus % gran) return fail(NEXUS_EINVAL, "CU shares must be multiples of %d (one CU in each XCD)", gran);
         if (prefill_cus + decode_cus > c->n_cus) return fail(NEXUS_EINVAL, "CU shares %d + %d exceed the device's %d CUs", prefill_cus, decode_cus, c->n_cus);
-        key = ((long)c->part_mode << 40) | ((long)prefill_cus << 20) | decode_cus;
+        key = ((long)prefill_cus << 20) | decode_cus;
     }
     auto it = c->layouts.find(key);
     if (it == c->layouts.end()) {
+        // Every CU-masked stream owns a hardware queue, and a process only gets a handful of those: keep at most
+        // kMaxMaskedLayouts partitioned pairs alive and retire the least recently used one before creating another.
+        int masked = 0;
+        for (auto &kv : c->layouts) masked += kv.first != 0;
+        while (masked >= kMaxMaskedLayouts) {
+            auto victim = c->layouts.end();
+            for (auto jt = c->layouts.begin(); jt != c->layouts.end(); ++jt)
+                if (jt->first != 0 && (victim == c->layouts.end() || jt->second.last_use < victim->second.last_use)) victim = jt;
+            HIP_TRY(hipStreamSynchronize(victim->second.sp));
+            HIP_TRY(hipStreamSynchronize(victim->second.sd));
+            if (c->cur == &victim->second) c->cur = &c->layouts[0];
+            destroy_layout(victim->second);
+            c->layouts.erase(victim);
+            --masked;
+        }
         Layout L;
         NX_TRY(make_layout(c, prefill_cus, decode_cus, &L));
         it = c->layouts.emplace(key, L).first;
     }
+    it->second.last_use = ++c->use_clock;
     c->cur = &it->second;
     return NEXUS_OK;
 }
@@ -857,7 +862,7 @@ int nexus_profile_split(nexus_ctx *c, int lb, int le, const nexus_prefill_batch 
     if (!cand || n_cand <= 0 || !t_p || !t_d || !t_s || !t_all || !chosen) return fail(NEXUS_EINVAL, "null output or no candidates");
     if (policy < 0 || policy > 2) return fail(NEXUS_EINVAL, "unknown policy %d", policy);
     if (repeats <= 0) return fail(NEXUS_EINVAL, "repeats must be positive");
-    const int gran = c->part_mode == NEXUS_PART_WHOLE_XCD ? c->cus_per_xcd : c->n_xcd;
+    const int gran = c->n_xcd;
     for (int i = 0; i < n_cand; ++i)
         if (cand[i] <= 0 || cand[i] >= c->n_cus || cand[i] % gran || (c->n_cus - cand[i]) % gran)
             return fail(NEXUS_EINVAL, "candidate %d (%d prefill CUs) is not a valid split of %d CUs at granularity %d", i, cand[i], c->n_cus, gran);
