@@ -119,57 +119,69 @@ static int dev_alloc(T **p, size_t elems, bool zero) {
 }
 
 // ---------------------------------------------------------------------------------------------- GEMM planning
-enum GemmVariant { GV_256x256 = 0, GV_128x128, GV_SK64, GV_SK32, GV_COUNT };
+// Tile shapes (features x tokens), wavefronts, k per stage, ring depth.  Measured on MI355X: 128x128 tiles with
+// more workgroups per CU beat 256x256 at the token counts of a prefill chunk; a decode batch (<= 64 tokens) streams
+// the weights once and wants many small workgroups with deep rings to keep HBM busy.
+enum GemmVariant {
+    GV_P128_BK32 = 0,  // 128 x 128, 4 waves, 64 KiB LDS: several workgroups per CU
+    GV_P128_BK64,      // 128 x 128, 4 waves, 128 KiB LDS: deeper ring for launches that cannot fill the chip anyway
+    GV_D128,           // 128 x 64 tokens, 4 waves: wide decode GEMMs (gate/up)
+    GV_D64,            // 64 x 64 tokens, 2 waves: narrow decode GEMMs, split along K
+    GV_D256_T32,       // 256 x 32 tokens, 4 waves: decode batches of at most 32
+    GV_COUNT
+};
 struct GemmPlan {
     int variant, S, ksteps_per_split, FS, TS;
 };
+constexpr int kChipCUs = 256;  // the plan is sized for the whole chip, whatever share the phase runs on
 
 // Depends on the problem only (never on the CU share), so that results are bit-identical across layouts.
 static GemmPlan plan_gemm(int T, int n_ftiles, int Kp) {
     const int ksteps = Kp / kGemmBK;
     const int nt = (T + 31) / 32;
     GemmPlan p{};
+    int min_ksteps;
     if (T <= 32) {
-        p.variant = GV_SK32, p.FS = 8, p.TS = 1;
+        p.variant = GV_D256_T32, p.FS = 8, p.TS = 1, min_ksteps = 8;
     } else if (T <= 64) {
-        p.variant = GV_SK64, p.FS = 4, p.TS = 2;
+        if (n_ftiles >= 512) p.variant = GV_D128, p.FS = 4, p.TS = 2;
+        else p.variant = GV_D64, p.FS = 2, p.TS = 2;
+        min_ksteps = 8;
     } else {
-        const int tiles256 = ((n_ftiles + 7) / 8) * ((nt + 7) / 8);
-        if (T > 128 && tiles256 >= 200) p.variant = GV_256x256, p.FS = 8, p.TS = 8;
-        else p.variant = GV_128x128, p.FS = 4, p.TS = 4;
+        p.FS = 4, p.TS = 4, min_ksteps = 16;
     }
     const int blocks = ((n_ftiles + p.FS - 1) / p.FS) * ((nt + p.TS - 1) / p.TS);
-    int S = (448 + blocks - 1) / blocks;
-    const int traffic_cap = std::max(1, Kp / (8 * std::max(T, 32)));  // keep partial traffic a fraction of the weights
-    S = std::min(S, traffic_cap);
-    S = std::min(S, std::max(1, ksteps / 4));
-    S = std::max(S, 1);
+    int S = 1;
+    if (blocks < (3 * kChipCUs) / 4) S = std::min(T <= 64 ? 8 : 4, (kChipCUs + blocks / 2) / blocks);
+    while (S > 1 && ksteps / S < min_ksteps) --S;
     p.ksteps_per_split = (ksteps + S - 1) / S;
     p.S = (ksteps + p.ksteps_per_split - 1) / p.ksteps_per_split;
+    if (T > 64) p.variant = blocks * p.S <= kChipCUs + kChipCUs / 4 ? GV_P128_BK64 : GV_P128_BK32;
     return p;
 }
 
-template <int FS, int TS, int WF, int WT, int EPI>
+template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI>
 static hipError_t launch_gemm_t(const GemmArgs &a, dim3 grid, hipStream_t s) {
-    constexpr int smem = 2 * (FS + TS) * kStripStage;
+    constexpr int smem = NST * (FS + TS) * BKT * 1024;
     static bool attr_done = false;  // one context thread at a time (see header)
-    auto kern = gemm_p32_kernel<FS, TS, WF, WT, EPI>;
+    auto kern = gemm_dl_kernel<FS, TS, WF, WT, BKT, NST, EPI>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), smem, s, a);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * WF * WT), smem, s, a);
     return hipGetLastError();
 }
 
 template <int EPI>
 static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipStream_t s) {
     switch (variant) {
-        case GV_256x256: return launch_gemm_t<8, 8, 2, 2, EPI>(a, grid, s);
-        case GV_128x128: return launch_gemm_t<4, 4, 2, 2, EPI>(a, grid, s);
-        case GV_SK64: return launch_gemm_t<4, 2, 2, 2, EPI>(a, grid, s);
-        default: return launch_gemm_t<8, 1, 4, 1, EPI>(a, grid, s);
+        case GV_P128_BK32: return launch_gemm_t<4, 4, 2, 2, 2, 4, EPI>(a, grid, s);
+        case GV_P128_BK64: return launch_gemm_t<4, 4, 2, 2, 4, 4, EPI>(a, grid, s);
+        case GV_D128: return launch_gemm_t<4, 2, 2, 2, 4, 4, EPI>(a, grid, s);
+        case GV_D64: return launch_gemm_t<2, 2, 1, 2, 4, 4, EPI>(a, grid, s);
+        default: return launch_gemm_t<8, 1, 4, 1, 4, 3, EPI>(a, grid, s);
     }
 }
 
@@ -262,12 +274,22 @@ static int run_rmsnorm(const PhaseRun &r, const bf16_t *x, const bf16_t *g, bf16
     return NEXUS_OK;
 }
 
+// Key-range splits of the prefill attention: a short chunk has too few (32-token strip, query head) pairs to fill
+// the chip's 1024 SIMDs, so its key range is cut into runs handled by separate workgroups.  Problem-only.
+static int plan_attn_splits(int n_tokens, int n_q_heads, int max_total_len) {
+    const int wave_tasks = ((n_tokens + 31) / 32) * n_q_heads;
+    int S = (2048 + wave_tasks / 2) / wave_tasks;
+    const int tiles = (max_total_len + 63) / 64;
+    S = std::min(S, tiles / 4);  // at least 4 key tiles per split
+    return std::max(1, std::min(S, 8));
+}
+
 template <int HD>
 static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
     nexus_ctx *c = r.c;
     const int G = c->m.n_q_heads / c->m.n_kv_heads;
     AttnPrefillArgs a = base;
-    constexpr int smem = 2 * 8 * kPage * HD * 2;
+    constexpr int smem = 2 * 8 * kPage * HD * 2 + kAttnMaxPages * 4;
 #define NX_ATTN_CASE(GG, SPB)                                                                                        \
     case GG: {                                                                                                       \
         auto kern = attn_prefill_kernel<HD, GG, SPB>;                                                                \
@@ -277,7 +299,15 @@ static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
             done = true;                                                                                             \
         }                                                                                                            \
         a.tiles_per_req = (r.pb->max_chunk + 32 * SPB - 1) / (32 * SPB);                                             \
-        hipLaunchKernelGGL(kern, dim3(r.pb->n_reqs * a.tiles_per_req, c->m.n_kv_heads), dim3(64 * GG * SPB), smem, r.s, a); \
+        {                                                                                                            \
+            Tracer tr(c, r.phase, NEXUS_K_ATTN_PREFILL, r.s);                                                        \
+            hipLaunchKernelGGL(kern, dim3(r.pb->n_reqs * a.tiles_per_req, c->m.n_kv_heads, a.n_splits), dim3(64 * GG * SPB), smem, r.s, a); \
+        }                                                                                                            \
+        HIP_TRY(hipGetLastError());                                                                                  \
+        if (a.n_splits > 1) {                                                                                        \
+            Tracer tr(c, r.phase, NEXUS_K_ATTN_MERGE, r.s);                                                          \
+            hipLaunchKernelGGL((attn_prefill_merge_kernel<HD, SPB>), dim3(r.T * c->m.n_q_heads), dim3(64), 0, r.s, a); \
+        }                                                                                                            \
         break;                                                                                                       \
     }
     switch (G) {
@@ -359,7 +389,8 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
         a.n_reqs = r.pb->n_reqs, a.max_pages = r.pb->max_pages;
         a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads;
         a.scale_log2e = scale_log2e;
-        Tracer tr(c, r.phase, NEXUS_K_ATTN_PREFILL, r.s);
+        a.n_splits = plan_attn_splits(r.T, m.n_q_heads, r.pb->max_total_len);
+        a.part_o = ws.part_o, a.part_ml = ws.part_ml, a.T = r.T;
         NX_TRY(m.head_dim == 128 ? launch_attn_prefill<128>(r, a) : launch_attn_prefill<64>(r, a));
     } else {
         AttnDecodeArgs a{};
@@ -419,6 +450,7 @@ static int check_prefill(nexus_ctx *c, const nexus_prefill_batch *b) {
         return fail(NEXUS_EINVAL, "inconsistent prefill hints (max_pages %d, max_chunk %d, max_total_len %d)", b->max_pages, b->max_chunk,
                     b->max_total_len);
     if (b->max_total_len > c->lim.max_positions) return fail(NEXUS_ESHAPE, "max_total_len %d exceeds max_positions %d", b->max_total_len, c->lim.max_positions);
+    if (b->max_total_len > kAttnMaxPages * kPage) return fail(NEXUS_ESHAPE, "max_total_len %d exceeds the %d tokens a prefill workgroup can address", b->max_total_len, kAttnMaxPages * kPage);
     if ((int64_t)b->max_pages * kPage < b->max_total_len) return fail(NEXUS_EINVAL, "page table rows (%d pages) cannot hold max_total_len %d", b->max_pages, b->max_total_len);
     if (((uintptr_t)b->x | (uintptr_t)b->y) & 15) return fail(NEXUS_EINVAL, "x / y must be 16-byte aligned");
     return NEXUS_OK;
@@ -517,6 +549,13 @@ static int alloc_phase_ws(nexus_ctx *c, int phase, int maxT, int max_reqs) {
     if (phase == NEXUS_PHASE_PREFILL) {
         w.q_rows = Tp + 32 * max_reqs;
         NX_TRY(dev_alloc(&w.q, p32_elems(w.q_rows, c->q_dim), true));
+        size_t items = 0;  // split results of the attention: worst case over the token counts the phase may see
+        for (int T = 1; T <= maxT; ++T) {
+            const int S = plan_attn_splits(T, m.n_q_heads, c->lim.max_positions);
+            if (S > 1) items = std::max(items, (size_t)S * T * m.n_q_heads);
+        }
+        NX_TRY(dev_alloc(&w.part_o, items * m.head_dim, false));
+        NX_TRY(dev_alloc(&w.part_ml, items * 2, false));
     } else {
         NX_TRY(dev_alloc(&w.q, (size_t)maxT * c->q_dim, true));
         w.max_spans = (c->lim.max_positions + kSpan - 1) / kSpan;
