@@ -32,10 +32,11 @@ struct AttnDecodeArgs {
 };
 
 template <int HD, int G>
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeArgs a) {
+__global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnDecodeArgs a) {
     constexpr int KK = HD / 32;   // k-steps of QK^T per page
     constexpr int RT = HD / 32;   // 32-row groups of O^T (two 16-row MFMA tiles each)
     constexpr int BLK = kPage * HD;  // elements per (page, kv head) block
+    constexpr int NPAIR = kSpan / 32;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wi = blockIdx.x * 4 + w;
     const int span = wi % a.max_spans;
@@ -47,7 +48,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeArgs a) {
     if (k_begin >= len) return;
     const int k_end = min(len, k_begin + kSpan);
     const int col = lane & 15, g4 = lane >> 4;
-    const int32_t *pt = a.page_table + (size_t)j * a.max_pages;
+
+    // the span's 16 page ids, one per lane, fetched once: no key/value load waits on a page-table read
+    int my_page = -1;
+    {
+        const int lp = (k_begin >> 4) + col;
+        if (lp * 16 < k_end && lp < a.max_pages) my_page = a.page_table[(size_t)j * a.max_pages + lp];
+        if ((unsigned)my_page >= (unsigned)a.n_pages) my_page = -1;
+    }
 
     bf16x8 qf[KK];
 #pragma unroll
@@ -65,40 +73,38 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeArgs a) {
             for (int e = 0; e < 4; ++e) o_acc[i][p][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    const int n_pairs = (k_end - k_begin + 31) >> 5;
-    for (int pp = 0; pp < n_pairs; ++pp) {
-        const int lpA = (k_begin >> 4) + 2 * pp, lpB = lpA + 1;
-        int pageA = -1, pageB = -1;
-        if (lpA < a.max_pages) pageA = pt[lpA];
-        if (lpB * 16 < k_end && lpB < a.max_pages) pageB = pt[lpB];
-        const bool okA = (unsigned)pageA < (unsigned)a.n_pages, okB = (unsigned)pageB < (unsigned)a.n_pages;
-        const bf16_t *kA = a.k_pool + ((size_t)(okA ? pageA : 0) * a.Hkv + kvh) * BLK;
-        const bf16_t *kB = a.k_pool + ((size_t)(okB ? pageB : 0) * a.Hkv + kvh) * BLK;
-        const bf16_t *vA = a.v_pool + ((size_t)(okA ? pageA : 0) * a.Hkv + kvh) * BLK;
-        const bf16_t *vB = a.v_pool + ((size_t)(okB ? pageB : 0) * a.Hkv + kvh) * BLK;
-
-        // issue every load of the pair up front: 2 * KK key loads and 2 * RT value loads of 16 B per lane
-        uint4 kfa[KK], kfb[KK], vfa[RT], vfb[RT];
+    // One pair = two pages = 32 keys: 2 * KK key loads and 2 * RT value loads of 16 B per lane, all issued together.
+    // V block [4 token groups][hd][4]: a lane reads hd rows 32i + 2*col, +1 of token group g4 (16 B).
+    struct PairRegs {
+        u32x4 ka[KK], kb[KK], va[RT], vb[RT];
+    };
+    auto load_pair = [&](PairRegs &r, int pp) {
+        const int pageA = __builtin_amdgcn_readlane(my_page, 2 * pp), pageB = __builtin_amdgcn_readlane(my_page, 2 * pp + 1);
+        const u32x4 zero = {0, 0, 0, 0};
+        const bf16_t *kA = a.k_pool + ((size_t)(pageA < 0 ? 0 : pageA) * a.Hkv + kvh) * BLK;
+        const bf16_t *kB = a.k_pool + ((size_t)(pageB < 0 ? 0 : pageB) * a.Hkv + kvh) * BLK;
+        const bf16_t *vA = a.v_pool + ((size_t)(pageA < 0 ? 0 : pageA) * a.Hkv + kvh) * BLK;
+        const bf16_t *vB = a.v_pool + ((size_t)(pageB < 0 ? 0 : pageB) * a.Hkv + kvh) * BLK;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            kfa[kk] = okA ? *(const uint4 *)(kA + kk * 512 + lane * 8) : make_uint4(0, 0, 0, 0);
-            kfb[kk] = okB ? *(const uint4 *)(kB + kk * 512 + lane * 8) : make_uint4(0, 0, 0, 0);
+            r.ka[kk] = pageA >= 0 ? *(const u32x4 *)(kA + kk * 512 + lane * 8) : zero;
+            r.kb[kk] = pageB >= 0 ? *(const u32x4 *)(kB + kk * 512 + lane * 8) : zero;
         }
-        // V block [4 token groups][hd][4]: lane reads hd rows 32i + 2*col, +1 of token group g4 (16 B)
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
-            vfa[i] = okA ? *(const uint4 *)(vA + (g4 * HD + 32 * i + 2 * col) * 4) : make_uint4(0, 0, 0, 0);
-            vfb[i] = okB ? *(const uint4 *)(vB + (g4 * HD + 32 * i + 2 * col) * 4) : make_uint4(0, 0, 0, 0);
+            r.va[i] = pageA >= 0 ? *(const u32x4 *)(vA + (g4 * HD + 32 * i + 2 * col) * 4) : zero;
+            r.vb[i] = pageB >= 0 ? *(const u32x4 *)(vB + (g4 * HD + 32 * i + 2 * col) * 4) : zero;
         }
-
+    };
+    auto compute_pair = [&](PairRegs &r, int pp) {
         f32x4 sA = {0, 0, 0, 0}, sB = {0, 0, 0, 0};
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&kfa[kk], qf[kk], sA, 0, 0, 0);
-            sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&kfb[kk], qf[kk], sB, 0, 0, 0);
+            sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&r.ka[kk], qf[kk], sA, 0, 0, 0);
+            sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&r.kb[kk], qf[kk], sB, 0, 0, 0);
         }
-        // lane (col = query head, g4): register e of sA is key lpA*16 + 4*g4 + e
-        const int keyA = lpA * 16 + 4 * g4, keyB = keyA + 16;
+        // lane (col = query head, g4): register e of sA is key keyA + e, of sB key keyA + 16 + e
+        const int keyA = k_begin + 32 * pp + 4 * g4, keyB = keyA + 16;
         float mx = m_run;
         float sv[8];
 #pragma unroll
@@ -123,24 +129,20 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeArgs a) {
         }
         l_run = l_run * alpha + rs;
         // values past the end of the context may hold anything; their weight is 0 but 0 * NaN is not
-        if (keyA + 4 > k_end || keyB + 4 > k_end || lpA * 16 + 32 > k_end) {
+        if (keyB + 4 > k_end) {
 #pragma unroll
-            for (int i = 0; i < RT; ++i) {
-                uint32_t wa[4] = {vfa[i].x, vfa[i].y, vfa[i].z, vfa[i].w}, wb[4] = {vfb[i].x, vfb[i].y, vfb[i].z, vfb[i].w};
+            for (int i = 0; i < RT; ++i)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const uint32_t keep = (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    if (keyA + (e & 3) >= k_end) wa[e >> 1] &= keep;
-                    if (keyB + (e & 3) >= k_end) wb[e >> 1] &= keep;
+                    if (keyA + (e & 3) >= k_end) r.va[i][e >> 1] &= keep;
+                    if (keyB + (e & 3) >= k_end) r.vb[i][e >> 1] &= keep;
                 }
-                vfa[i] = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                vfb[i] = make_uint4(wb[0], wb[1], wb[2], wb[3]);
-            }
         }
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
             // 16 B = [hd row even: 4 tokens][hd row odd: 4 tokens]; operand A k-slots 0..3 from page A, 4..7 from page B
-            uint4 ev = make_uint4(vfa[i].x, vfa[i].y, vfb[i].x, vfb[i].y), od = make_uint4(vfa[i].z, vfa[i].w, vfb[i].z, vfb[i].w);
+            u32x4 ev = {r.va[i][0], r.va[i][1], r.vb[i][0], r.vb[i][1]}, od = {r.va[i][2], r.va[i][3], r.vb[i][2], r.vb[i][3]};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 o_acc[i][0][e] *= alpha;
@@ -149,6 +151,20 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnDecodeArgs a) {
             o_acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&ev, pf, o_acc[i][0], 0, 0, 0);
             o_acc[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&od, pf, o_acc[i][1], 0, 0, 0);
         }
+    };
+
+    // two register sets: the loads of the next pair are in flight while the current pair is computed
+    const int n_pairs = (k_end - k_begin + 31) >> 5;
+    PairRegs r0, r1;
+    load_pair(r0, 0);
+#pragma unroll
+    for (int pp = 0; pp < NPAIR; pp += 2) {
+        if (pp >= n_pairs) break;
+        if (pp + 1 < n_pairs) load_pair(r1, pp + 1);
+        compute_pair(r0, pp);
+        if (pp + 1 >= n_pairs) break;
+        if (pp + 2 < n_pairs) load_pair(r0, pp + 2);
+        compute_pair(r1, pp + 1);
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
@@ -178,19 +194,36 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnDecodeArgs a) {
     const int len = a.ctx_len[j] + 1;
     const int n_spans = (len + kSpan - 1) / kSpan;
     const size_t item0 = ((size_t)j * a.Hkv + kvh) * a.max_spans;
-    float m = -INFINITY;
-    for (int s = 0; s < n_spans; ++s) m = fmaxf(m, a.part_ml[((item0 + s) * G + col) * 2]);
     constexpr int EPL = HD / 64;
-    float acc[EPL], denom = 0.f;
+    float acc[EPL], m = -INFINITY, denom = 0.f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    for (int s = 0; s < n_spans; ++s) {
-        const float2 ml = *(const float2 *)(a.part_ml + ((item0 + s) * G + col) * 2);
-        const float wgt = exp2f(ml.x - m);
-        denom += wgt * ml.y;
-        const float *po = a.part_o + ((item0 + s) * G + col) * HD + lane * EPL;
+    // spans are taken 64 at a time: lane s holds the statistics of span base + s, so the loads of the partial
+    // outputs do not wait on one another
+    for (int base = 0; base < n_spans; base += 64) {
+        const int s = base + lane;
+        float2 ml = {-INFINITY, 0.f};
+        if (s < n_spans) ml = *(const float2 *)(a.part_ml + ((item0 + s) * G + col) * 2);
+        float cm = ml.x;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] += wgt * po[e];
+        for (int o = 32; o > 0; o >>= 1) cm = fmaxf(cm, __shfl_xor(cm, o));
+        const float m_new = fmaxf(m, cm);
+        const float rescale = exp2f(m - m_new);  // 0 on the first chunk (m = -inf), spans are never empty
+        const float wgt = s < n_spans ? exp2f(ml.x - m_new) : 0.f;
+        float part = wgt * ml.y;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+        denom = denom * rescale + part;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] *= rescale;
+        const int cnt = min(64, n_spans - base);
+        for (int k = 0; k < cnt; ++k) {
+            const float wk = __shfl(wgt, k);
+            const float *po = a.part_o + ((item0 + base + k) * G + col) * HD + lane * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] += wk * po[e];
+        }
+        m = m_new;
     }
     const float inv = 1.0f / denom;
     const int QKp = a.Hq * HD;
