@@ -55,6 +55,14 @@ typedef struct {
     int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers, page_size;
     float rms_eps, rope_theta;
 } nexus_model_desc;
+/*
+ * Precision inside the library: the layer input x, the output y, the rotated queries and the KV cache are bf16;
+ * the operands of the four projection GEMMs (normalised activations, attention output, SwiGLU activation and
+ * the packed weights) are IEEE half, which the matrix unit runs at the bf16 rate with 8x smaller operand
+ * rounding (half holds every bf16 weight of magnitude >= 2^-14 exactly); accumulators, softmax and norm
+ * statistics and the residual stream between attention and feed-forward are fp32.  Activations feeding a GEMM
+ * must stay inside half's range (|v| < 65504).
+ */
 
 /* Upper bounds that size the context's workspace; step calls beyond them fail with NEXUS_ESHAPE. */
 typedef struct {
@@ -237,7 +245,7 @@ typedef enum { NEXUS_PHASE_PREFILL = 0, NEXUS_PHASE_DECODE = 1 } nexus_phase;
 int nexus_trace_begin(nexus_ctx *ctx, int phase, int kernel);
 int nexus_trace_read(nexus_ctx *ctx, float *mean_ms, int32_t *launches);
 
-/* Intermediate buffers of the last step of a phase, converted to row-major bf16 (device out pointer). */
+/* Intermediate buffers of the last step of a phase, converted to row-major fp32 (device out pointer). */
 typedef enum {
     NEXUS_BUF_NORM1 = 0, /* [T][hidden]   RMSNorm output feeding the QKV projection */
     NEXUS_BUF_Q,         /* [T][Hq*hd]    rotated queries                           */

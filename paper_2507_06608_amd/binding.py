@@ -251,7 +251,7 @@ class Nexus:
     def debug_fetch(self, phase: int, which: int, n_tokens: int) -> torch.Tensor:
         s = self.shape
         width = {BUF_Q: s.q_dim, BUF_ATTN: s.q_dim, BUF_X1: s.hidden, BUF_ACT: s.ffn}[which]
-        out = torch.empty((n_tokens, width), dtype=torch.bfloat16, device=self.device)
+        out = torch.empty((n_tokens, width), dtype=torch.float32, device=self.device)
         _check(lib().nexus_debug_fetch(self._ctx, phase, which, n_tokens, _ptr(out)))
         return out
 

@@ -28,7 +28,7 @@ struct AttnDecodeArgs {
     float scale_log2e;
     float *part_o;   // [B][Hkv][max_spans][G][hd]
     float *part_ml;  // [B][Hkv][max_spans][G][2]  (running max in the log2 domain, sum)
-    bf16_t *out;     // merge output: P32 [B rows][Hq*hd]
+    f16_t *out;      // merge output: half, P32 [B rows][Hq*hd]
 };
 
 template <int HD, int G>
@@ -227,11 +227,11 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnDecodeArgs a) {
     }
     const float inv = 1.0f / denom;
     const int QKp = a.Hq * HD;
-    bf16_t *dst = a.out + p32_offset(j, hq * HD + lane * EPL, QKp);
+    f16_t *dst = a.out + p32_offset(j, hq * HD + lane * EPL, QKp);
     if (EPL == 2) {
-        *(uint32_t *)dst = pack2(acc[0] * inv, acc[EPL - 1] * inv);
+        *(uint32_t *)dst = packh2(acc[0] * inv, acc[EPL - 1] * inv);
     } else {
-        dst[0] = f2bf(acc[0] * inv);
+        dst[0] = f2h(acc[0] * inv);
     }
 }
 

@@ -25,7 +25,7 @@ constexpr int kAttnMaxPages = 2048;  // page ids staged in LDS per workgroup (32
 
 struct AttnPrefillArgs {
     const bf16_t *q;  // P32 [request-aligned rows][Hq*hd]
-    bf16_t *out;      // P32 [global token rows][Hq*hd]
+    f16_t *out;       // half, P32 [global token rows][Hq*hd] (operand of the output projection)
     const int32_t *cu_chunk, *prefix_len, *page_table;
     int n_reqs, max_pages, tiles_per_req;  // tiles of 32*SPB tokens sized from the max_chunk hint
     const bf16_t *k_pool, *v_pool;
@@ -264,10 +264,10 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             const int hd0 = 64 * i + 16 * b + 8 * g;
-            uint4 o = make_uint4(pack2(o_acc[i][0][4 * b + 0] * inv, o_acc[i][1][4 * b + 0] * inv),
-                                 pack2(o_acc[i][0][4 * b + 1] * inv, o_acc[i][1][4 * b + 1] * inv),
-                                 pack2(o_acc[i][0][4 * b + 2] * inv, o_acc[i][1][4 * b + 2] * inv),
-                                 pack2(o_acc[i][0][4 * b + 3] * inv, o_acc[i][1][4 * b + 3] * inv));
+            uint4 o = make_uint4(packh2(o_acc[i][0][4 * b + 0] * inv, o_acc[i][1][4 * b + 0] * inv),
+                                 packh2(o_acc[i][0][4 * b + 1] * inv, o_acc[i][1][4 * b + 1] * inv),
+                                 packh2(o_acc[i][0][4 * b + 2] * inv, o_acc[i][1][4 * b + 2] * inv),
+                                 packh2(o_acc[i][0][4 * b + 3] * inv, o_acc[i][1][4 * b + 3] * inv));
             *(uint4 *)(a.out + p32_offset(trow, hq * HD + hd0, QKp)) = o;
         }
 }
@@ -307,9 +307,9 @@ __global__ __launch_bounds__(64) void attn_prefill_merge_kernel(AttnPrefillArgs 
         for (int i = 0; i < EPL; ++i) acc[i] += wgt * po[i];
     }
     const float inv = 1.0f / denom;
-    bf16_t *dst = a.out + p32_offset(t, hq * HD + lane * EPL, a.Hq * HD);
-    if (EPL == 2) *(uint32_t *)dst = pack2(acc[0] * inv, acc[EPL - 1] * inv);
-    else dst[0] = f2bf(acc[0] * inv);
+    f16_t *dst = a.out + p32_offset(t, hq * HD + lane * EPL, a.Hq * HD);
+    if (EPL == 2) *(uint32_t *)dst = packh2(acc[0] * inv, acc[EPL - 1] * inv);
+    else dst[0] = f2h(acc[0] * inv);
 }
 
 }  // namespace nexus

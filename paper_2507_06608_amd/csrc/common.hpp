@@ -7,11 +7,13 @@
 namespace nexus {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // 16-byte staging register
-typedef unsigned short bf16_t;  // raw storage
+typedef unsigned short bf16_t;  // raw storage of a bfloat16
+typedef unsigned short f16_t;   // raw storage of an IEEE half
 
 constexpr int kWave = 64;
 constexpr int kPage = 16;  // tokens per KV page
@@ -25,6 +27,24 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
     return (bf16_t)(u >> 16);
 }
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+
+// ---- fp16 <-> fp32 (round to nearest even) ------------------------------------------------------------------
+// GEMM operands (normalised activations, attention output, SwiGLU activation, packed weights) are IEEE half, not
+// bfloat16: the matrix unit runs both at the same rate, and the three extra mantissa bits cut the operand
+// rounding error by 8x, which the elementwise parity bar needs once the hidden size reaches the thousands.
+// The KV cache, the rotated queries and the layer's input and output stay bfloat16.
+__device__ __forceinline__ float h2f(f16_t v) {
+    _Float16 h;
+    __builtin_memcpy(&h, &v, 2);
+    return (float)h;
+}
+__device__ __forceinline__ f16_t f2h(float f) {
+    _Float16 h = (_Float16)f;
+    f16_t v;
+    __builtin_memcpy(&v, &h, 2);
+    return v;
+}
+__device__ __forceinline__ uint32_t packh2(float lo, float hi) { return (uint32_t)f2h(lo) | ((uint32_t)f2h(hi) << 16); }
 
 // ---- P32: MFMA-operand tile order of a [rows][K] matrix ----------------------------------------------------
 // The matrix is cut into tiles of 32 rows x 16 k (1 KiB).  Inside a tile the 64 lanes of a wavefront each own

@@ -6,26 +6,34 @@
 namespace nexus {
 
 // ---- RMSNorm: h = x * rsqrt(mean(x^2) + eps) * g, one workgroup per token, fp32 statistics -----------------
-// Input row-major [T][d]; output in P32 tile order (operand of the following GEMM).
-template <int MAXC>  // 8-element chunks per thread, d <= MAXC * 256 * 8
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ g,
-                                                      bf16_t *__restrict__ out_p32, int d, int Kp, float eps) {
+// Input row-major [T][d], bf16 (the layer input) or fp32 (the residual stream after attention); output half, in
+// P32 tile order (operand of the following GEMM).
+template <int MAXC, bool IN_F32>  // 8-element chunks per thread, d <= MAXC * 256 * 8
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x, const bf16_t *__restrict__ g,
+                                                      f16_t *__restrict__ out_p32, int d, int Kp, float eps) {
     __shared__ float red[4];
     const int t = blockIdx.x, tid = threadIdx.x;
     const int nchunk = d >> 3;
-    const uint4 *row = (const uint4 *)(x + (size_t)t * d);
     float v[MAXC][8];
     float ss = 0.f;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int ci = tid + c * 256;
         if (ci < nchunk) {
-            uint4 u = row[ci];
-            uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+            if (IN_F32) {
+                const float4 *row = (const float4 *)((const float *)x + (size_t)t * d);
+                float4 a0 = row[2 * ci], a1 = row[2 * ci + 1];
+                v[c][0] = a0.x, v[c][1] = a0.y, v[c][2] = a0.z, v[c][3] = a0.w;
+                v[c][4] = a1.x, v[c][5] = a1.y, v[c][6] = a1.z, v[c][7] = a1.w;
+            } else {
+                const uint4 *row = (const uint4 *)((const bf16_t *)x + (size_t)t * d);
+                uint4 u = row[ci];
+                uint32_t wds[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                v[c][2 * e] = bf2f(wds[e] & 0xffff);
-                v[c][2 * e + 1] = bf2f(wds[e] >> 16);
+                for (int e = 0; e < 4; ++e) {
+                    v[c][2 * e] = bf2f(wds[e] & 0xffff);
+                    v[c][2 * e + 1] = bf2f(wds[e] >> 16);
+                }
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss += v[c][e] * v[c][e];
@@ -46,7 +54,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16_t *__restrict__
             uint32_t o[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                o[e] = pack2(v[c][2 * e] * inv * bf2f(gw[e] & 0xffff), v[c][2 * e + 1] * inv * bf2f(gw[e] >> 16));
+                o[e] = packh2(v[c][2 * e] * inv * bf2f(gw[e] & 0xffff), v[c][2 * e + 1] * inv * bf2f(gw[e] >> 16));
             *(uint4 *)(out_p32 + p32_offset(t, ci * 8, Kp)) = make_uint4(o[0], o[1], o[2], o[3]);
         }
     }
@@ -63,10 +71,10 @@ __global__ void rope_table_kernel(float2 *tab, int n_pos, int half, double theta
 }
 
 // ---- rotary embedding + KV append ---------------------------------------------------------------------------
-// Reads the QKV projection output (row-major [T][(Hq+2Hkv)*hd]); rotates q and k at the token's absolute
+// Reads the QKV projection output (half, row-major [T][(Hq+2Hkv)*hd]); rotates q and k at the token's absolute
 // position; writes q for the attention kernel and k, v into the token's (page, slot) of the pools.
 struct RopeArgs {
-    const bf16_t *qkv;
+    const f16_t *qkv;
     int T, Hq, Hkv, hd;
     const float2 *rope_tab;
     int n_pos;
@@ -102,7 +110,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
         qrow = t;
     }
     const int qd = a.Hq * hd, kvd = a.Hkv * hd;
-    const bf16_t *row = a.qkv + (size_t)t * (qd + 2 * kvd);
+    const f16_t *row = a.qkv + (size_t)t * (qd + 2 * kvd);
     int page = -1;
     const int lp = pos >> 4, slot = pos & 15;
     if (lp < a.max_pages) page = a.page_table[(size_t)r * a.max_pages + lp];
@@ -115,14 +123,14 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
     for (int u = threadIdx.x; u < rope_units + v_units; u += 256) {
         if (u < rope_units) {
             const int h = u / cph, c = u % cph;  // head (q heads first, then k heads), pair chunk
-            const bf16_t *src = row + (size_t)h * hd + c * 8;
+            const f16_t *src = row + (size_t)h * hd + c * 8;
             uint4 lo = *(const uint4 *)src, hi = *(const uint4 *)(src + half);
             uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
             float ol[8], oh[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float x0 = bf2f((lw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
-                const float x1 = bf2f((hw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+                const float x0 = h2f((f16_t)((lw[e >> 1] >> ((e & 1) * 16)) & 0xffff));
+                const float x1 = h2f((f16_t)((hw[e >> 1] >> ((e & 1) * 16)) & 0xffff));
                 const float2 cs = tab[c * 8 + e];
                 ol[e] = x0 * cs.x - x1 * cs.y;
                 oh[e] = x1 * cs.x + x0 * cs.y;
@@ -151,15 +159,16 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
             bf16_t *blk = a.v_pool + ((size_t)page * a.Hkv + kvh) * (kPage * hd);
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                blk[vblk_offset(slot, c * 8 + e, hd)] = (bf16_t)((vw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+                blk[vblk_offset(slot, c * 8 + e, hd)] = f2bf(h2f((f16_t)((vw[e >> 1] >> ((e & 1) * 16)) & 0xffff)));
         }
     }
 }
 
-// ---- weight packing: row-major [N][K] -> P32 [round_up(N,32)][Kp], zero padded ----------------------------
+// ---- weight packing: bf16 row-major [N][K] -> half P32 [round_up(N,32)][Kp], zero padded -----------------------
+// bf16 -> half is exact for |w| >= 2^-14 and off by at most 2^-25 below that.
 // interleave_F > 0 reorders gate/up rows so that 32-row strips alternate: strip 2s = gate rows [32s, 32s+32),
 // strip 2s+1 = up rows [32s, 32s+32) (a lane of the GEMM then holds a gate value and its up value).
-__global__ void pack_weight_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int N, int K, int Kp,
+__global__ void pack_weight_kernel(const bf16_t *__restrict__ src, f16_t *__restrict__ dst, int N, int K, int Kp,
                                    int interleave_F) {
     const int Np = round_up(N, 32);
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -181,7 +190,10 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, bf16_t *__res
             v = *(uint4 *)tmp;
         }
     }
-    *(uint4 *)(dst + p32_offset(n, k, Kp)) = v;
+    uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) wds[e] = packh2(bf2f(wds[e] & 0xffff), bf2f(wds[e] >> 16));
+    *(uint4 *)(dst + p32_offset(n, k, Kp)) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
 }
 
 // ---- KV page layout conversion (canonical [pages][Hkv][16][hd] <-> private blocks) -------------------------
@@ -203,14 +215,14 @@ __global__ void kv_convert_kernel(bf16_t *k_priv, bf16_t *v_priv, bf16_t *k_cano
     }
 }
 
-// ---- debug: P32 -> row-major -------------------------------------------------------------------------------
-__global__ void unpack_p32_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, int rows, int K, int Kp,
-                                  const int32_t *row_map /* nullable: source row of each output row */) {
+// ---- debug: 16-bit P32 or row-major buffer -> fp32 row-major ----------------------------------------------------
+// kind: 0 = half P32, 1 = bf16 P32, 2 = half row-major, 3 = bf16 row-major
+__global__ void debug_to_f32_kernel(const unsigned short *__restrict__ src, float *__restrict__ dst, int rows, int K, int Kp, int kind) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)rows * K) return;
     const int r = (int)(idx / K), k = (int)(idx % K);
-    const int sr = row_map ? row_map[r] : r;
-    dst[idx] = src[p32_offset(sr, k, Kp)];
+    const unsigned short v = kind < 2 ? src[p32_offset(r, k, Kp)] : src[idx];
+    dst[idx] = (kind & 1) ? bf2f(v) : h2f(v);
 }
 
 // ---- CU probe: where does each workgroup of a masked stream run? -------------------------------------------

@@ -1,4 +1,5 @@
-// bf16 MFMA projection GEMMs of the layer (Eq. 1-3): Y[T][N] = X[T][K] * W[N][K]^T with fused epilogues.
+// MFMA projection GEMMs of the layer (Eq. 1-3): Y[T][N] = X[T][K] * W[N][K]^T with fused epilogues.  Operands are
+// IEEE half (same matrix-unit rate as bfloat16, 8x smaller operand rounding), accumulation is fp32.
 //
 // Both operands are stored in P32 tile order (common.hpp), so every global access of the main loop is a
 // contiguous 16 B per lane and the LDS image of a tile is the MFMA register image.  The kernel computes the
@@ -17,23 +18,24 @@
 namespace nexus {
 
 enum GemmEpi : int {
-    EPI_ROWMAJOR = 0,  // out[t][f] = bf16(acc (+ bias[f]))
-    EPI_RESIDUAL = 1,  // out[t][f] = bf16(res[t][f] + acc)
-    EPI_SWIGLU = 2,    // weight strips alternate gate/up; out_p32[t][f] = bf16(silu(gate) * up)
-    EPI_PARTIAL = 3    // partial[z][t][n] = acc (fp32), finished by splitk_reduce
+    EPI_ROWMAJOR = 0,  // out[t][f] = half(acc (+ bias[f]))                      (QKV projection)
+    EPI_RES_IN = 1,    // out_f32[t][f] = bf16 res[t][f] + acc                   (x1 = x + attention projection)
+    EPI_SWIGLU = 2,    // weight strips alternate gate/up; out_p32[t][f] = half(silu(gate) * up)
+    EPI_PARTIAL = 3,   // partial[z][t][n] = acc (fp32), finished by splitk_reduce
+    EPI_RES_OUT = 4    // out[t][f] = bf16(res_f32[t][f] + acc)                  (y = x1 + down projection)
 };
 
 struct GemmArgs {
-    const bf16_t *W;   // P32 [n_ftiles*32][Kp]
-    const bf16_t *X;   // P32 [n_ttiles*32][Kp]
+    const f16_t *W;    // P32 [n_ftiles*32][Kp]
+    const f16_t *X;    // P32 [n_ttiles*32][Kp]
     int n_ftiles, n_ttiles, Kp;
     int ksteps_per_split;  // K steps of 64 handled by one z-slice
     int T, N;              // valid tokens; N = n_ftiles * 32 (packed row count)
-    bf16_t *out;           // row-major [T][ld_out]
-    const bf16_t *res;     // row-major [T][ld_out]
+    void *out;             // row-major [T][ld_out]: half (ROWMAJOR), fp32 (RES_IN) or bf16 (RES_OUT)
+    const void *res;       // row-major [T][ld_out]: bf16 (RES_IN) or fp32 (RES_OUT)
     const bf16_t *bias;    // [N] or null
     int ld_out;
-    bf16_t *out_p32;       // EPI_SWIGLU destination, P32 with out_Kp
+    f16_t *out_p32;        // EPI_SWIGLU destination, P32 with out_Kp
     int out_Kp;
     float *partial;        // [S][T][N]
     int n_tblk;            // token blocks in the grid
@@ -65,7 +67,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[F
                     float v[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] = silu_f(acc[i][j][4 * b + e]) * acc[i + 1][j][4 * b + e];
-                    uint2 o = {pack2(v[0], v[1]), pack2(v[2], v[3])};
+                    uint2 o = {packh2(v[0], v[1]), packh2(v[2], v[3])};
                     *(uint2 *)(a.out_p32 + p32_offset(t, f, a.out_Kp)) = o;
                 }
             }
@@ -83,20 +85,22 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[F
                     if constexpr (EPI == EPI_PARTIAL) {
                         float4 o = {v[0], v[1], v[2], v[3]};
                         *(float4 *)(a.partial + ((size_t)z * a.T + t) * a.N + f) = o;
-                    } else {
-                        if constexpr (EPI == EPI_ROWMAJOR) {
-                            if (a.bias) {
-                                uint2 bb = *(const uint2 *)(a.bias + f);
-                                v[0] += bf2f(bb.x & 0xffff), v[1] += bf2f(bb.x >> 16);
-                                v[2] += bf2f(bb.y & 0xffff), v[3] += bf2f(bb.y >> 16);
-                            }
-                        } else {
-                            uint2 rr = *(const uint2 *)(a.res + (size_t)t * a.ld_out + f);
-                            v[0] += bf2f(rr.x & 0xffff), v[1] += bf2f(rr.x >> 16);
-                            v[2] += bf2f(rr.y & 0xffff), v[3] += bf2f(rr.y >> 16);
+                    } else if constexpr (EPI == EPI_ROWMAJOR) {
+                        if (a.bias) {
+                            uint2 bb = *(const uint2 *)(a.bias + f);
+                            v[0] += bf2f(bb.x & 0xffff), v[1] += bf2f(bb.x >> 16);
+                            v[2] += bf2f(bb.y & 0xffff), v[3] += bf2f(bb.y >> 16);
                         }
-                        uint2 o = {pack2(v[0], v[1]), pack2(v[2], v[3])};
-                        *(uint2 *)(a.out + (size_t)t * a.ld_out + f) = o;
+                        uint2 o = {packh2(v[0], v[1]), packh2(v[2], v[3])};
+                        *(uint2 *)((f16_t *)a.out + (size_t)t * a.ld_out + f) = o;
+                    } else if constexpr (EPI == EPI_RES_IN) {
+                        uint2 rr = *(const uint2 *)((const bf16_t *)a.res + (size_t)t * a.ld_out + f);
+                        float4 o = {v[0] + bf2f(rr.x & 0xffff), v[1] + bf2f(rr.x >> 16), v[2] + bf2f(rr.y & 0xffff), v[3] + bf2f(rr.y >> 16)};
+                        *(float4 *)((float *)a.out + (size_t)t * a.ld_out + f) = o;
+                    } else {
+                        float4 rr = *(const float4 *)((const float *)a.res + (size_t)t * a.ld_out + f);
+                        uint2 o = {pack2(v[0] + rr.x, v[1] + rr.y), pack2(v[2] + rr.z, v[3] + rr.w)};
+                        *(uint2 *)((bf16_t *)a.out + (size_t)t * a.ld_out + f) = o;
                     }
                 }
             }
@@ -187,14 +191,14 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     // Software pipeline: operand fragments are read from LDS one k-tile ahead of the MFMAs that use them, also
     // across the stage boundary, so the matrix unit never waits on LDS latency.  The barrier that publishes stage
     // ks + 1 therefore sits before the LAST k-tile of stage ks.
-    bf16x8 fa[2][FW], fb_[2][TW];
+    f16x8 fa[2][FW], fb_[2][TW];
     auto read_frags = [&](int buf, int ks, int kt) {
         const char *sW = smem + (ks % NST) * STAGE + (wf * FW) * (BKT * 1024) + kt * 1024 + lane * 16;
         const char *sX = smem + (ks % NST) * STAGE + (FS + wt * TW) * (BKT * 1024) + kt * 1024 + lane * 16;
 #pragma unroll
-        for (int i = 0; i < FW; ++i) fa[buf][i] = *(const bf16x8 *)(sW + i * (BKT * 1024));
+        for (int i = 0; i < FW; ++i) fa[buf][i] = *(const f16x8 *)(sW + i * (BKT * 1024));
 #pragma unroll
-        for (int j = 0; j < TW; ++j) fb_[buf][j] = *(const bf16x8 *)(sX + j * (BKT * 1024));
+        for (int j = 0; j < TW; ++j) fb_[buf][j] = *(const f16x8 *)(sX + j * (BKT * 1024));
     };
     auto publish_next = [&](int ks) {
         // loads issued after those of step ks + 1 (and still allowed in flight): steps ks + 2 .. ks + NST - 2
@@ -230,7 +234,7 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
             for (int i = 0; i < FW; ++i)
 #pragma unroll
                 for (int j = 0; j < TW; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         // The fragments of the next stage's first k-tile were requested a whole k-tile of MFMAs ago: settle the
@@ -248,11 +252,11 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
 struct ReduceArgs {
     const float *partial;  // [S][T][N]
     int S, T, N;
-    bf16_t *out;
-    const bf16_t *res;
+    void *out;
+    const void *res;
     const bf16_t *bias;
     int ld_out;
-    bf16_t *out_p32;
+    f16_t *out_p32;
     int out_Kp;
 };
 
@@ -274,8 +278,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceArgs a) {
             usum[0] += uv.x, usum[1] += uv.y, usum[2] += uv.z, usum[3] += uv.w;
         }
         const int f = (strip >> 1) * 32 + (n & 31);
-        uint2 o = {pack2(silu_f(gsum[0]) * usum[0], silu_f(gsum[1]) * usum[1]),
-                   pack2(silu_f(gsum[2]) * usum[2], silu_f(gsum[3]) * usum[3])};
+        uint2 o = {packh2(silu_f(gsum[0]) * usum[0], silu_f(gsum[1]) * usum[1]),
+                   packh2(silu_f(gsum[2]) * usum[2], silu_f(gsum[3]) * usum[3])};
         *(uint2 *)(a.out_p32 + p32_offset(t, f, a.out_Kp)) = o;
     } else {
         float v[4] = {0, 0, 0, 0};
@@ -288,12 +292,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceArgs a) {
                 uint2 bb = *(const uint2 *)(a.bias + n);
                 v[0] += bf2f(bb.x & 0xffff), v[1] += bf2f(bb.x >> 16), v[2] += bf2f(bb.y & 0xffff), v[3] += bf2f(bb.y >> 16);
             }
+            uint2 o = {packh2(v[0], v[1]), packh2(v[2], v[3])};
+            *(uint2 *)((f16_t *)a.out + (size_t)t * a.ld_out + n) = o;
+        } else if constexpr (EPI == EPI_RES_IN) {
+            uint2 rr = *(const uint2 *)((const bf16_t *)a.res + (size_t)t * a.ld_out + n);
+            float4 o = {v[0] + bf2f(rr.x & 0xffff), v[1] + bf2f(rr.x >> 16), v[2] + bf2f(rr.y & 0xffff), v[3] + bf2f(rr.y >> 16)};
+            *(float4 *)((float *)a.out + (size_t)t * a.ld_out + n) = o;
         } else {
-            uint2 rr = *(const uint2 *)(a.res + (size_t)t * a.ld_out + n);
-            v[0] += bf2f(rr.x & 0xffff), v[1] += bf2f(rr.x >> 16), v[2] += bf2f(rr.y & 0xffff), v[3] += bf2f(rr.y >> 16);
+            float4 rr = *(const float4 *)((const float *)a.res + (size_t)t * a.ld_out + n);
+            uint2 o = {pack2(v[0] + rr.x, v[1] + rr.y), pack2(v[2] + rr.z, v[3] + rr.w)};
+            *(uint2 *)((bf16_t *)a.out + (size_t)t * a.ld_out + n) = o;
         }
-        uint2 o = {pack2(v[0], v[1]), pack2(v[2], v[3])};
-        *(uint2 *)(a.out + (size_t)t * a.ld_out + n) = o;
     }
 }
 

@@ -43,18 +43,19 @@ static int fail(int code, const char *fmt, ...) {
 
 // ---------------------------------------------------------------------------------------------- context
 struct LayerW {
-    bf16_t *g1 = nullptr, *g2 = nullptr, *wqkv = nullptr, *bqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdown = nullptr;
+    bf16_t *g1 = nullptr, *g2 = nullptr, *bqkv = nullptr;
+    f16_t *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdown = nullptr;  // half, P32
     bool loaded = false;
 };
 
 struct PhaseWs {
     int maxT = 0;
-    bf16_t *h = nullptr;     // P32 [maxT][hidden]   RMSNorm output (both norms)
-    bf16_t *qkv = nullptr;   // row-major [maxT][n_qkv]
-    bf16_t *q = nullptr;     // prefill: P32, request-aligned tiles; decode: row-major
-    bf16_t *attn = nullptr;  // P32 [maxT][q_dim]
-    bf16_t *x1 = nullptr;    // row-major [maxT][hidden]
-    bf16_t *act = nullptr;   // P32 [maxT][ffn]
+    f16_t *h = nullptr;      // half P32 [maxT][hidden]   RMSNorm output (both norms)
+    f16_t *qkv = nullptr;    // half row-major [maxT][n_qkv]
+    bf16_t *q = nullptr;     // bf16, rotated; prefill: P32, request-aligned tiles; decode: row-major
+    f16_t *attn = nullptr;   // half P32 [maxT][q_dim]
+    float *x1 = nullptr;     // fp32 row-major [maxT][hidden]: residual stream after attention
+    f16_t *act = nullptr;    // half P32 [maxT][ffn]
     bf16_t *xbuf[2] = {nullptr, nullptr};  // layer ping-pong, row-major [maxT][hidden]
     float *partial = nullptr;
     size_t partial_elems = 0;
@@ -188,7 +189,8 @@ static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipSt
 static hipError_t launch_gemm(int variant, int epi, const GemmArgs &a, dim3 grid, hipStream_t s) {
     switch (epi) {
         case EPI_ROWMAJOR: return launch_gemm_v<EPI_ROWMAJOR>(variant, a, grid, s);
-        case EPI_RESIDUAL: return launch_gemm_v<EPI_RESIDUAL>(variant, a, grid, s);
+        case EPI_RES_IN: return launch_gemm_v<EPI_RES_IN>(variant, a, grid, s);
+        case EPI_RES_OUT: return launch_gemm_v<EPI_RES_OUT>(variant, a, grid, s);
         case EPI_SWIGLU: return launch_gemm_v<EPI_SWIGLU>(variant, a, grid, s);
         default: return launch_gemm_v<EPI_PARTIAL>(variant, a, grid, s);
     }
@@ -224,8 +226,8 @@ struct PhaseRun {
     const nexus_kv_cache *kv;
 };
 
-static int run_gemm(const PhaseRun &r, int kernel_id, const bf16_t *W, int N_packed, const bf16_t *X, int K, int epi,
-                    bf16_t *out, const bf16_t *res, const bf16_t *bias, int ld_out, bf16_t *out_p32, int out_K) {
+static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_packed, const f16_t *X, int K, int epi,
+                    void *out, const void *res, const bf16_t *bias, int ld_out, f16_t *out_p32, int out_K) {
     nexus_ctx *c = r.c;
     PhaseWs &ws = c->ws[r.phase];
     const int Kp = p32_kp(K);
@@ -256,20 +258,22 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const bf16_t *W, int N_pac
         dim3 g((unsigned)((n + 255) / 256));
         Tracer tr(c, r.phase, NEXUS_K_SPLITK_REDUCE, r.s);
         if (epi == EPI_ROWMAJOR) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_ROWMAJOR>, g, dim3(256), 0, r.s, ra);
-        else if (epi == EPI_RESIDUAL) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_RESIDUAL>, g, dim3(256), 0, r.s, ra);
+        else if (epi == EPI_RES_IN) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_RES_IN>, g, dim3(256), 0, r.s, ra);
+        else if (epi == EPI_RES_OUT) hipLaunchKernelGGL(splitk_reduce_kernel<EPI_RES_OUT>, g, dim3(256), 0, r.s, ra);
         else hipLaunchKernelGGL(splitk_reduce_kernel<EPI_SWIGLU>, g, dim3(256), 0, r.s, ra);
         HIP_TRY(hipGetLastError());
     }
     return NEXUS_OK;
 }
 
-static int run_rmsnorm(const PhaseRun &r, const bf16_t *x, const bf16_t *g, bf16_t *out_p32) {
+template <bool IN_F32>
+static int run_rmsnorm(const PhaseRun &r, const void *x, const bf16_t *g, f16_t *out_p32) {
     nexus_ctx *c = r.c;
     const int d = c->m.hidden;
     Tracer tr(c, r.phase, NEXUS_K_RMSNORM, r.s);
-    if (d <= 2048) hipLaunchKernelGGL(rmsnorm_kernel<1>, dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
-    else if (d <= 4096) hipLaunchKernelGGL(rmsnorm_kernel<2>, dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
-    else hipLaunchKernelGGL(rmsnorm_kernel<4>, dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
+    if (d <= 2048) hipLaunchKernelGGL((rmsnorm_kernel<1, IN_F32>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
+    else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_kernel<2, IN_F32>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
+    else hipLaunchKernelGGL((rmsnorm_kernel<4, IN_F32>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
     HIP_TRY(hipGetLastError());
     return NEXUS_OK;
 }
@@ -364,7 +368,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
     bf16_t *k_pool = (bf16_t *)((char *)r.kv->k_pool + (size_t)layer * r.kv->layer_stride_bytes);
     bf16_t *v_pool = (bf16_t *)((char *)r.kv->v_pool + (size_t)layer * r.kv->layer_stride_bytes);
 
-    NX_TRY(run_rmsnorm(r, x_in, L.g1, ws.h));
+    NX_TRY(run_rmsnorm<false>(r, x_in, L.g1, ws.h));
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_QKV, L.wqkv, c->n_qkv, ws.h, m.hidden, EPI_ROWMAJOR, ws.qkv, nullptr, L.bqkv, c->n_qkv,
                     nullptr, 0));
     {
@@ -400,12 +404,12 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
         a.scale_log2e = scale_log2e, a.part_o = ws.part_o, a.part_ml = ws.part_ml, a.out = ws.attn;
         NX_TRY(m.head_dim == 128 ? launch_attn_decode<128>(r, a) : launch_attn_decode<64>(r, a));
     }
-    NX_TRY(run_gemm(r, NEXUS_K_GEMM_O, L.wo, m.hidden, ws.attn, c->q_dim, EPI_RESIDUAL, ws.x1, x_in, nullptr, m.hidden,
+    NX_TRY(run_gemm(r, NEXUS_K_GEMM_O, L.wo, m.hidden, ws.attn, c->q_dim, EPI_RES_IN, ws.x1, x_in, nullptr, m.hidden,
                     nullptr, 0));
-    NX_TRY(run_rmsnorm(r, ws.x1, L.g2, ws.h));
+    NX_TRY(run_rmsnorm<true>(r, ws.x1, L.g2, ws.h));
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_GATE_UP, L.wgu, 2 * m.ffn, ws.h, m.hidden, EPI_SWIGLU, nullptr, nullptr, nullptr, 0,
                     ws.act, m.ffn));
-    NX_TRY(run_gemm(r, NEXUS_K_GEMM_DOWN, L.wdown, m.hidden, ws.act, m.ffn, EPI_RESIDUAL, y_out, ws.x1, nullptr, m.hidden,
+    NX_TRY(run_gemm(r, NEXUS_K_GEMM_DOWN, L.wdown, m.hidden, ws.act, m.ffn, EPI_RES_OUT, y_out, ws.x1, nullptr, m.hidden,
                     nullptr, 0));
     return NEXUS_OK;
 }
@@ -655,7 +659,7 @@ int nexus_sync(nexus_ctx *c) {
     return NEXUS_OK;
 }
 
-static int pack_one(nexus_ctx *c, const void *src, int N, int K, int interleave_F, bf16_t **dst) {
+static int pack_one(nexus_ctx *c, const void *src, int N, int K, int interleave_F, f16_t **dst) {
     const int Kp = p32_kp(K), Np = round_up(N, 32);
     if (!*dst) NX_TRY(dev_alloc(dst, (size_t)Np * Kp, false));
     const size_t n = (size_t)Np * (Kp / 8);
@@ -968,24 +972,23 @@ int nexus_debug_fetch(nexus_ctx *c, int phase, int which, int32_t n_tokens, void
     if (n_tokens <= 0 || n_tokens > w.maxT) return fail(NEXUS_EINVAL, "n_tokens outside the workspace");
     DeviceGuard dg(c->device);
     NX_TRY(nexus_sync(c));
-    const bf16_t *src = nullptr;
-    int K = 0;
-    bool p32 = true;
+    const void *src = nullptr;
+    int K = 0, kind = 0;  // 0 half P32, 1 bf16 P32, 2 half row-major, 3 bf16 row-major
     switch (which) {
         case NEXUS_BUF_NORM1: return fail(NEXUS_ESTATE, "the first norm's output is overwritten by the second norm within a layer");
-        case NEXUS_BUF_Q: src = w.q, K = c->q_dim, p32 = phase == NEXUS_PHASE_PREFILL; break;
-        case NEXUS_BUF_ATTN: src = w.attn, K = c->q_dim; break;
-        case NEXUS_BUF_X1: src = w.x1, K = c->m.hidden, p32 = false; break;
-        case NEXUS_BUF_ACT: src = w.act, K = c->m.ffn; break;
+        case NEXUS_BUF_Q: src = w.q, K = c->q_dim, kind = phase == NEXUS_PHASE_PREFILL ? 1 : 3; break;
+        case NEXUS_BUF_ATTN: src = w.attn, K = c->q_dim, kind = 0; break;
+        case NEXUS_BUF_X1: src = w.x1, K = c->m.hidden, kind = -1; break;
+        case NEXUS_BUF_ACT: src = w.act, K = c->m.ffn, kind = 0; break;
         default: return fail(NEXUS_EINVAL, "unknown buffer id %d", which);
     }
-    if (!p32) {
-        HIP_TRY(hipMemcpyAsync(out, src, (size_t)n_tokens * K * 2, hipMemcpyDeviceToDevice, c->s_main));
+    if (kind < 0) {
+        HIP_TRY(hipMemcpyAsync(out, src, (size_t)n_tokens * K * 4, hipMemcpyDeviceToDevice, c->s_main));
     } else {
         // prefill queries sit in request-aligned tiles; callers with one request (or 32-aligned chunks) see rows in order
         const size_t n = (size_t)n_tokens * K;
-        hipLaunchKernelGGL(unpack_p32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->s_main, src, (bf16_t *)out, n_tokens, K, p32_kp(K),
-                           (const int32_t *)nullptr);
+        hipLaunchKernelGGL(debug_to_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->s_main, (const unsigned short *)src, (float *)out,
+                           n_tokens, K, p32_kp(K), kind);
         HIP_TRY(hipGetLastError());
     }
     HIP_TRY(hipStreamSynchronize(c->s_main));

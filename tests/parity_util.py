@@ -70,6 +70,7 @@ def assert_close(name, got: np.ndarray, ref: np.ndarray):
                                   f"(err {err[worst]:.4g} > {bound[worst]:.4g}); {int((err > bound).sum())} of {err.size} fail")
     rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
     assert rel <= REL_L2, f"{name}: relative L2 {rel:.4g} > {REL_L2}"
+    print(f"[parity] {name}: worst err/bound {float((err / bound).max()):.3f}, rel L2 {rel:.2e}, n {err.size}", flush=True)
     return rel
 
 

@@ -250,3 +250,60 @@ def test_argument_errors_launch_nothing(nx):
     ctx.mixed_step(pb, db, kv)                 # and the context still works afterwards
     ctx.sync()
     ctx.close()
+
+
+def test_cfg2_full_size_sampled_outputs_in_bench_launch_configuration(nx, oracle):
+    """The benchmark workload at full size, run the way bench.py runs it (mixed step on a partitioned layout,
+    KV generated on the device).  The oracle evaluates a sample it can afford: the first 40 tokens of the chunk
+    (they attend to the whole 1536-token prefix) and 6 decode requests including the shortest and longest context.
+    Whole-output properties that hold at any size are checked on everything: finiteness, and bit-identity of the
+    concurrent step with the serialized one."""
+    _announce("cfg2 full size, sampled")
+    wl = synth.config(2, seed=0, kv_device="cuda:0")
+    w = synth.make_weights(wl.shape, 0)
+    ctx = nx.context_for(wl)
+    ctx.load_layer(0, w)
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+    ctx.set_cu_split(160, 96)
+    ctx.mixed_step(pb, db, kv, stream=torch.cuda.Stream())
+    ctx.sync()
+    torch.cuda.synchronize()
+    yp, yd = pb.y.clone(), db.y.clone()
+    kv_after = ctx.kv_export(kv)
+    assert torch.isfinite(yp.float()).all() and torch.isfinite(yd.float()).all()
+
+    # serialized run on a fresh cache: identical bits
+    kv2 = ctx.make_kv(wl.k_pool, wl.v_pool)
+    ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
+    ctx.mixed_step(pb, db, kv2)
+    ctx.sync()
+    assert torch.equal(pb.y.view(torch.int16), yp.view(torch.int16))
+    assert torch.equal(db.y.view(torch.int16), yd.view(torch.int16))
+    for a, b in zip(ctx.kv_export(kv2), kv_after):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+    # sampled oracle comparison
+    d = wl.decode
+    order = np.argsort(d.ctx_len)
+    dec_sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 0, 17, 63})
+    n_pre = 40
+    sub = synth.subset_for_oracle(wl, [0], dec_sample)
+    sp = sub.prefill
+    sub.prefill = synth.PrefillBatch(sp.x[:n_pre], np.array([0, n_pre], np.int32), sp.prefix_len[:1], sp.page_table[:1])
+    ref = run_oracle(oracle, sub, w)
+    assert_close("cfg2 prefill rows 0..39", f32(yp[:n_pre]), ref["y_p"])
+    assert_close("cfg2 decode sample", f32(yd[dec_sample]), ref["y_d"])
+    # appended K/V of the sampled tokens: page ids of the sub-pool map back through notes["pages"]
+    pages = sub.notes["pages"]
+    ps = wl.shape.page_size
+    kg, vg = kv_after
+    for name, req_row, positions in (
+            [("prefill", sub.prefill.page_table[0], range(int(sp.prefix_len[0]), int(sp.prefix_len[0]) + n_pre))] +
+            [(f"decode {j}", sub.decode.page_table[i], [int(sub.decode.ctx_len[i])]) for i, j in enumerate(dec_sample)]):
+        for pos in positions:
+            sp_page = int(req_row[pos // ps])
+            full_page = pages[sp_page]
+            assert_close(f"K {name} pos {pos}", f32(kg[full_page, :, pos % ps]), ref["k_pool"][sp_page, :, pos % ps])
+            assert_close(f"V {name} pos {pos}", f32(vg[full_page, :, pos % ps]), ref["v_pool"][sp_page, :, pos % ps])
+    ctx.close()
