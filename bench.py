@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--split", default="auto", help="'auto' (profile and choose) or PREFILL_CUS/DECODE_CUS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) to calibrate rocprofv3 byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the partitioned step is an intra-GPU method); --gpus must be 1")
@@ -126,6 +128,14 @@ def main():
         run_steps(n)
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / n * 1e3
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- serialized baseline (one unmasked stream, prefill then decode)
     ctx.set_cu_split(binding.CUS_ALL, binding.CUS_ALL)
