@@ -10,14 +10,16 @@
 // padded to the 16 columns of the tile; on this memory-bound sweep the matrix unit is otherwise idle, while the
 // same work on the vector ALUs would cost about G+1 instructions per KV element and bind before HBM does once
 // the phase only owns a fraction of the CUs.  As in the prefill kernel the transposed orientation
-// (S^T = K Q^T, O^T = V^T P^T) keeps softmax statistics per lane and lets the S^T accumulators of two pages
-// serve directly as the P^T operand (k-slots 0..3 = page A tokens 4g..4g+3, k-slots 4..7 = page B).
+// (S^T = K Q^T, O^T = V^T P^T) keeps softmax statistics per lane and lets the S^T accumulators serve directly as
+// the P^T operand.  The loop is kept lean on purpose (no per-load predicates, raw v_exp_f32): with a dozen VALU
+// instructions per key the sweep would be instruction-bound, not memory-bound.
 #pragma once
 #include "common.hpp"
 
 namespace nexus {
 
 constexpr int kSpan = 256;  // keys per work item (16 pages)
+constexpr int kDecWaves = 1;  // work items (wavefronts) per workgroup
 
 struct AttnDecodeArgs {
     const bf16_t *q;  // row-major [B][Hq*hd], rotated
@@ -32,13 +34,12 @@ struct AttnDecodeArgs {
 };
 
 template <int HD, int G>
-__global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnDecodeArgs a) {
-    constexpr int KK = HD / 32;   // k-steps of QK^T per page
-    constexpr int RT = HD / 32;   // 32-row groups of O^T (two 16-row MFMA tiles each)
+__global__ __launch_bounds__(kDecWaves * 64, 2) void attn_decode_kernel(AttnDecodeArgs a) {
+    constexpr int KK = HD / 32;   // k-steps of QK^T
+    constexpr int RT = HD / 16;   // 16-row tiles of O^T
     constexpr int BLK = kPage * HD;  // elements per (page, kv head) block
-    constexpr int NPAIR = kSpan / 32;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int wi = blockIdx.x * 4 + w;
+    const int wi = blockIdx.x * kDecWaves + w;
     const int span = wi % a.max_spans;
     const int kvh = (wi / a.max_spans) % a.Hkv;
     const int j = wi / (a.max_spans * a.Hkv);
@@ -49,135 +50,133 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnDecodeArgs a) {
     const int k_end = min(len, k_begin + kSpan);
     const int col = lane & 15, g4 = lane >> 4;
 
-    // the span's 16 page ids, one per lane, fetched once: no key/value load waits on a page-table read
-    int my_page = -1;
+    // The span's 16 page ids, one per lane, fetched once: no key/value load waits on a page-table read.  Ids that
+    // are out of range or belong to pages past the end of the context are replaced by page 0: every load below
+    // then has a valid address and no branch, and what it fetches for such a page is masked out.
+    int my_page = 0;
     {
         const int lp = (k_begin >> 4) + col;
         if (lp * 16 < k_end && lp < a.max_pages) my_page = a.page_table[(size_t)j * a.max_pages + lp];
-        if ((unsigned)my_page >= (unsigned)a.n_pages) my_page = -1;
+        if ((unsigned)my_page >= (unsigned)a.n_pages) my_page = 0;
     }
 
     bf16x8 qf[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (col < G) v = *(const uint4 *)(a.q + (size_t)j * a.Hq * HD + (size_t)(kvh * G + col) * HD + (kk * 4 + g4) * 8);
+        u32x4 v = {0, 0, 0, 0};
+        if (col < G) v = *(const u32x4 *)(a.q + (size_t)j * a.Hq * HD + (size_t)(kvh * G + col) * HD + (kk * 4 + g4) * 8);
         qf[kk] = *(bf16x8 *)&v;
     }
-    f32x4 o_acc[RT][2];
+    f32x4 o_acc[RT];
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o_acc[i][p][e] = 0.f;
+        for (int e = 0; e < 4; ++e) o_acc[i][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // One pair = two pages = 32 keys: 2 * KK key loads and 2 * RT value loads of 16 B per lane, all issued together.
-    // V block [4 token groups][hd][4]: a lane reads hd rows 32i + 2*col, +1 of token group g4 (16 B).
+    // One pair = two pages (A, B) = 32 keys.  S^T is computed as two 16-row tiles: tile 1 takes slots 0..7 of page
+    // A and of page B (tokens {0..3, 8..11}), tile 2 slots 8..15 (tokens {4..7, 12..15}); lane (col = query head,
+    // g4) then holds the scores of tokens 8*(g4 % 2) .. +7 of page g4 / 2, exactly the 8 tokens of the V^T operand
+    // it reads with one 16-byte load.
     struct PairRegs {
-        u32x4 ka[KK], kb[KK], va[RT], vb[RT];
+        u32x4 k1[KK], k2[KK], v[RT];
     };
+    const int half_off = (col & 7) * 8 + g4 * 128;  // elements: slot (col % 8) of a tile's half, k-group g4
     auto load_pair = [&](PairRegs &r, int pp) {
         const int pageA = __builtin_amdgcn_readlane(my_page, 2 * pp), pageB = __builtin_amdgcn_readlane(my_page, 2 * pp + 1);
-        const u32x4 zero = {0, 0, 0, 0};
-        const bf16_t *kA = a.k_pool + ((size_t)(pageA < 0 ? 0 : pageA) * a.Hkv + kvh) * BLK;
-        const bf16_t *kB = a.k_pool + ((size_t)(pageB < 0 ? 0 : pageB) * a.Hkv + kvh) * BLK;
-        const bf16_t *vA = a.v_pool + ((size_t)(pageA < 0 ? 0 : pageA) * a.Hkv + kvh) * BLK;
-        const bf16_t *vB = a.v_pool + ((size_t)(pageB < 0 ? 0 : pageB) * a.Hkv + kvh) * BLK;
+        // K operand row (lane % 16): rows 0..7 from page A, 8..15 from page B
+        const bf16_t *kp = a.k_pool + ((size_t)(col < 8 ? pageA : pageB) * a.Hkv + kvh) * BLK + half_off;
+        // V operand: lane group g4 reads page g4 / 2, token group g4 % 2, hd rows 16 i + col
+        const bf16_t *vp = a.v_pool + ((size_t)(g4 < 2 ? pageA : pageB) * a.Hkv + kvh) * BLK + ((g4 & 1) * HD + col) * 8;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            r.ka[kk] = pageA >= 0 ? *(const u32x4 *)(kA + kk * 512 + lane * 8) : zero;
-            r.kb[kk] = pageB >= 0 ? *(const u32x4 *)(kB + kk * 512 + lane * 8) : zero;
+            r.k1[kk] = *(const u32x4 *)(kp + kk * 512);
+            r.k2[kk] = *(const u32x4 *)(kp + kk * 512 + 64);
         }
 #pragma unroll
-        for (int i = 0; i < RT; ++i) {
-            r.va[i] = pageA >= 0 ? *(const u32x4 *)(vA + (g4 * HD + 32 * i + 2 * col) * 4) : zero;
-            r.vb[i] = pageB >= 0 ? *(const u32x4 *)(vB + (g4 * HD + 32 * i + 2 * col) * 4) : zero;
-        }
+        for (int i = 0; i < RT; ++i) r.v[i] = *(const u32x4 *)(vp + i * 128);
     };
     auto compute_pair = [&](PairRegs &r, int pp) {
-        f32x4 sA = {0, 0, 0, 0}, sB = {0, 0, 0, 0};
+        f32x4 s1 = {0, 0, 0, 0}, s2 = {0, 0, 0, 0};
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&r.ka[kk], qf[kk], sA, 0, 0, 0);
-            sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&r.kb[kk], qf[kk], sB, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&r.k1[kk], qf[kk], s1, 0, 0, 0);
+            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&r.k2[kk], qf[kk], s2, 0, 0, 0);
         }
-        // lane (col = query head, g4): register e of sA is key keyA + e, of sB key keyA + 16 + e
-        const int keyA = k_begin + 32 * pp + 4 * g4, keyB = keyA + 16;
-        float mx = m_run;
+        // register e of s1 is key key0 + e, of s2 key key0 + 4 + e
+        const int key0 = k_begin + 32 * pp + 16 * (g4 >> 1) + 8 * (g4 & 1);
         float sv[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            sv[e] = (keyA + e < k_end) ? sA[e] * a.scale_log2e : -INFINITY;
-            sv[4 + e] = (keyB + e < k_end) ? sB[e] * a.scale_log2e : -INFINITY;
+            sv[e] = s1[e] * a.scale_log2e;
+            sv[4 + e] = s2[e] * a.scale_log2e;
         }
+        const bool tail = k_begin + 32 * pp + 32 > k_end;  // uniform: only the last pair of a context
+        if (tail) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sv[e] = key0 + e < k_end ? sv[e] : -INFINITY;
+            // values past the end of the context may hold anything; their weight is 0 but 0 * NaN is not
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (key0 + e >= k_end) r.v[i][e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+        }
+        float mx = m_run;
 #pragma unroll
         for (int e = 0; e < 8; ++e) mx = fmaxf(mx, sv[e]);
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         // the first key of the span is always valid, so mx is finite
-        const float alpha = exp2f(m_run - mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - mx);
         m_run = mx;
         float rs = 0.f;
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float p = exp2f(sv[e] - mx);
+            const float p = __builtin_amdgcn_exp2f(sv[e] - mx);
             rs += p;
             pf[e] = (__bf16)p;
         }
         l_run = l_run * alpha + rs;
-        // values past the end of the context may hold anything; their weight is 0 but 0 * NaN is not
-        if (keyB + 4 > k_end) {
-#pragma unroll
-            for (int i = 0; i < RT; ++i)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const uint32_t keep = (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    if (keyA + (e & 3) >= k_end) r.va[i][e >> 1] &= keep;
-                    if (keyB + (e & 3) >= k_end) r.vb[i][e >> 1] &= keep;
-                }
-        }
 #pragma unroll
         for (int i = 0; i < RT; ++i) {
-            // 16 B = [hd row even: 4 tokens][hd row odd: 4 tokens]; operand A k-slots 0..3 from page A, 4..7 from page B
-            u32x4 ev = {r.va[i][0], r.va[i][1], r.vb[i][0], r.vb[i][1]}, od = {r.va[i][2], r.va[i][3], r.vb[i][2], r.vb[i][3]};
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                o_acc[i][0][e] *= alpha;
-                o_acc[i][1][e] *= alpha;
-            }
-            o_acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&ev, pf, o_acc[i][0], 0, 0, 0);
-            o_acc[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&od, pf, o_acc[i][1], 0, 0, 0);
+            for (int e = 0; e < 4; ++e) o_acc[i][e] *= alpha;
+            o_acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(bf16x8 *)&r.v[i], pf, o_acc[i], 0, 0, 0);
         }
     };
 
-    // two register sets: the loads of the next pair are in flight while the current pair is computed
+    // Two register sets: the loads of the next pair are in flight while the current pair is computed.  The steady
+    // state loop has no branch around a prefetch: with one, the paths with and without the extra loads in flight
+    // merge, and the compiler can only wait as if they had not been issued, i.e. for the prefetch itself.
     const int n_pairs = (k_end - k_begin + 31) >> 5;
     PairRegs r0, r1;
     load_pair(r0, 0);
-#pragma unroll
-    for (int pp = 0; pp < NPAIR; pp += 2) {
-        if (pp >= n_pairs) break;
-        if (pp + 1 < n_pairs) load_pair(r1, pp + 1);
+    int pp = 0;
+    for (; pp + 2 < n_pairs; pp += 2) {
+        load_pair(r1, pp + 1);
         compute_pair(r0, pp);
-        if (pp + 1 >= n_pairs) break;
-        if (pp + 2 < n_pairs) load_pair(r0, pp + 2);
+        load_pair(r0, pp + 2);
         compute_pair(r1, pp + 1);
+    }
+    if (pp + 1 < n_pairs) {
+        load_pair(r1, pp + 1);
+        compute_pair(r0, pp);
+        compute_pair(r1, pp + 1);
+    } else {
+        compute_pair(r0, pp);
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     if (col >= G) return;
-    // o_acc[i][par][e] is hd = 32i + 2*(4*g4 + e) + par  ->  8 consecutive floats from hd0 = 32i + 8*g4
+    // register e of o_acc[i] is hd = 16 i + 4 g4 + e
     const size_t item = ((size_t)j * a.Hkv + kvh) * a.max_spans + span;
     float *po = a.part_o + (item * G + col) * HD;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-        float4 lo = {o_acc[i][0][0], o_acc[i][1][0], o_acc[i][0][1], o_acc[i][1][1]};
-        float4 hi = {o_acc[i][0][2], o_acc[i][1][2], o_acc[i][0][3], o_acc[i][1][3]};
-        *(float4 *)(po + 32 * i + 8 * g4) = lo;
-        *(float4 *)(po + 32 * i + 8 * g4 + 4) = hi;
+        float4 o = {o_acc[i][0], o_acc[i][1], o_acc[i][2], o_acc[i][3]};
+        *(float4 *)(po + 16 * i + 4 * g4) = o;
     }
     if (g4 == 0) {
         float2 ml = {m_run, l_run};

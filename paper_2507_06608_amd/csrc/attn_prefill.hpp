@@ -7,13 +7,13 @@
 //     S^T[keys][tokens] = K * Q^T          (v_mfma_f32_32x32x16_bf16; K tile is operand A, Q^T operand B)
 //     O^T[hd][tokens]  += V^T * P^T        (V^T operand A, P^T operand B)
 // In that orientation a lane owns one token column: the softmax running max / sum are per-lane scalars, and the
-// S^T accumulator registers of a lane are, as they stand, the P^T operand of the second product (the register
-// holding key 8b+4g+j of a 32-key group feeds k-slot 4(b%2)+j of the PV instruction of 16-key page b/2), so the
+// S^T accumulator registers of a lane are, as they stand, the P^T operand of the second product (registers
+// 8p .. 8p+7 are tokens 8g .. 8g+7 of page p, the eight k-slots of that page's PV instruction), so the
 // probabilities never leave registers.  The private page layouts make both LDS reads conflict-free 16-byte reads.
 //
-// K/V tiles of 64 keys (4 pages of K, 4 of V) move global->LDS asynchronously (global_load_lds_dwordx4, 1 KiB per
-// wavefront instruction, page blocks copied verbatim) into a two-stage ring; the request's page ids are staged in
-// LDS once so that no load waits on a page-table read.  A short chunk has too few (strip, head) pairs to fill the
+// K/V tiles of 32 keys (2 pages of K, 2 of V) move global->LDS asynchronously (global_load_lds_dwordx4, 1 KiB per
+// wavefront instruction, page blocks copied verbatim) into a four-stage ring, three tiles in flight while one is
+// consumed; the request's page ids are staged in LDS once so that no load waits on a page-table read.  A short chunk has too few (strip, head) pairs to fill the
 // chip, so the key range can be split over gridDim.z workgroups whose partial (max, sum, O) results are merged by
 // attn_prefill_merge_kernel; the split count depends on the problem only.
 #pragma once
@@ -37,6 +37,11 @@ struct AttnPrefillArgs {
     int T;
 };
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_attn() {  // s_waitcnt vmcnt(N) alone (gfx9 encoding)
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+
 // key tiles [begin, end) of split z when n_tiles tiles are dealt to n_splits splits in contiguous runs
 __device__ __forceinline__ void attn_split_range(int n_tiles, int n_splits, int z, int &begin, int &end) {
     const int per = (n_tiles + n_splits - 1) / n_splits;
@@ -44,18 +49,24 @@ __device__ __forceinline__ void attn_split_range(int n_tiles, int n_splits, int 
     end = begin + per < n_tiles ? begin + per : n_tiles;
 }
 
+constexpr int kAttnTile = 32;   // keys per LDS stage (2 pages of K and of V)
+constexpr int kAttnStages = 4;  // ring depth: three tiles in flight while one is consumed
+
 template <int HD, int G, int SPB>
 __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefillArgs a) {  // two wavefronts per SIMD
     constexpr int NW = G * SPB;
     constexpr int BLK = kPage * HD * 2;      // bytes of one (page, kv head) block
     constexpr int UPB = BLK / 1024;          // 1 KiB units per block
-    constexpr int STAGE = 8 * BLK;           // 4 K pages + 4 V pages = 64 keys
-    constexpr int UNITS = 8 * UPB;
-    constexpr int LPW = (UNITS + NW - 1) / NW;
+    constexpr int STAGE = 4 * BLK;           // 2 K pages + 2 V pages = 32 keys
+    constexpr int UNITS = 4 * UPB;
+    constexpr int LW = NW >= 8 ? 8 : NW >= 4 ? 4 : NW;  // wavefronts that issue loads: UNITS / LW each
+    static_assert(UNITS % LW == 0, "uniform load count per loading wavefront (the vmcnt waits rely on it)");
+    constexpr int LPW = UNITS / LW;
+    constexpr int NST = kAttnStages;
     constexpr int KK = HD / 16;              // k-steps of the QK^T product
-    constexpr int RT = HD / 64;              // pairs of 32-row tiles of O^T
+    constexpr int RT = HD / 32;              // 32-row tiles of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    int32_t *s_pt = (int32_t *)(smem + 2 * STAGE);
+    int32_t *s_pt = (int32_t *)(smem + NST * STAGE);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int hg = w % G, strip = w / G;
@@ -73,7 +84,7 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     int blk_last = (lt + 1) * 32 * SPB;
     if (blk_last > n_r) blk_last = n_r;
     const int kmax = prefix + blk_last;            // keys [0, kmax) are visible to some row of this block
-    const int n_kv_tiles = (kmax + 63) >> 6;
+    const int n_kv_tiles = (kmax + kAttnTile - 1) / kAttnTile;
     int pages_valid = (kmax + 15) >> 4;
     if (pages_valid > a.max_pages) pages_valid = a.max_pages;
     if (pages_valid > kAttnMaxPages) pages_valid = kAttnMaxPages;
@@ -81,9 +92,11 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     attn_split_range(n_kv_tiles, a.n_splits, z, t_begin, t_end);
     if (t_begin >= t_end) return;  // the merge kernel applies the same rule and never reads this split
 
+    // Page ids of the request, staged once.  Ids out of range become page 0: every load then has a valid address
+    // (and every wavefront issues the same number of loads per tile); what such a page delivers is masked out.
     for (int i = tid; i < pages_valid; i += 64 * NW) {
         const int page = pt[i];
-        s_pt[i] = (unsigned)page < (unsigned)a.n_pages ? page : -1;
+        s_pt[i] = (unsigned)page < (unsigned)a.n_pages ? page : 0;
     }
     __syncthreads();
 
@@ -108,130 +121,107 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
             for (int e = 0; e < 8; ++e) qf[kk][e] = (__bf16)0.f;
     }
 
-    f32x16 o_acc[RT][2];
+    f32x16 o_acc[RT];
 #pragma unroll
     for (int i = 0; i < RT; ++i)
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) o_acc[i][p][e] = 0.f;
+        for (int e = 0; e < 16; ++e) o_acc[i][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // unit u of a stage: block u / UPB (0..3 K pages, 4..7 V pages of the tile), KiB u % UPB of that block
+    // unit u of a stage: block u / UPB (0, 1: K pages; 2, 3: V pages of the tile), KiB u % UPB of that block
     auto issue = [&](int tile) {
-        char *dst = smem + (tile & 1) * STAGE;
+        if (w >= LW) return;
+        char *dst = smem + (tile % NST) * STAGE;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int u = w + NW * i;
-            if (u < UNITS) {
-                const int which = u / UPB;
-                const int lp = tile * 4 + (which & 3);
-                if (lp < pages_valid) {
-                    const int page = s_pt[lp];
-                    if (page >= 0) {
-                        const char *src = (const char *)((which < 4 ? a.k_pool : a.v_pool) + ((size_t)page * a.Hkv + kvh) * (kPage * HD)) +
-                                          (u % UPB) * 1024 + lane * 16;
-                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                                         (__attribute__((address_space(3))) void *)(dst + u * 1024), 16, 0, 0);
-                    }
-                }
-            }
+            const int u = w + LW * i;
+            const int which = u / UPB;
+            const int lp = tile * 2 + (which & 1);
+            const int page = lp < pages_valid ? s_pt[lp] : 0;
+            const char *src = (const char *)((which < 2 ? a.k_pool : a.v_pool) + ((size_t)page * a.Hkv + kvh) * (kPage * HD)) +
+                              (u % UPB) * 1024 + lane * 16;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(dst + u * 1024), 16, 0, 0);
         }
     };
 
-    issue(t_begin);
+#pragma unroll
+    for (int i = 0; i < NST - 1; ++i)
+        if (t_begin + i < t_end) issue(t_begin + i);
     for (int tile = t_begin; tile < t_end; ++tile) {
-        const int cur = tile & 1;
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wavefront's part of the tile has landed
-        __syncthreads();                     // everyone's part has landed; everyone is done with the other stage
-        if (tile + 1 < t_end) issue(tile + 1);
-        const int key0 = tile * 64;
+        // loads issued after those of this tile and allowed to stay in flight: min(NST - 2, tiles left after it)
+        const int later = t_end - 1 - tile;
+        if (later >= NST - 2) wait_vmcnt_attn<(NST - 2) * LPW>();
+        else if (later == 1) wait_vmcnt_attn<LPW>();
+        else wait_vmcnt_attn<0>();
+        __builtin_amdgcn_s_barrier();  // everyone's part of this tile has landed; everyone is done with tile - 1
+        if (tile + NST - 1 < t_end) issue(tile + NST - 1);
+        const int key0 = tile * kAttnTile;
         // rows of this wave see keys up to prefix + st*32 + 31; tiles entirely past that contribute nothing
         if (wave_active && key0 <= wave_min_pos + 31) {
-            const char *sK = smem + cur * STAGE;
-            const char *sV = sK + 4 * BLK;
-            f32x16 s[2];
+            const char *sK = smem + (tile % NST) * STAGE;
+            const char *sV = sK + 2 * BLK;
+            f32x16 s;
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2) {
+            for (int e = 0; e < 16; ++e) s[e] = 0.f;
+            // operand A row (lane % 32): page row / 16, slot row % 16 (slots are rows as they stand); k-slot group g
+            const char *kp = sK + (col >> 4) * BLK + (col & 15) * 16 + g * 256;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) s[h2][e] = 0.f;
-                // operand A row (lane % 32) = key 32*h2 + row: page 2*h2 + row/16, token row%16; k-slot group g
-                const char *kp = sK + (2 * h2 + (col >> 4)) * BLK + (col & 15) * 16 + g * 256;
-#pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    bf16x8 kf = *(const bf16x8 *)(kp + kk * 512);
-                    s[h2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[h2], 0, 0, 0);
-                }
+            for (int kk = 0; kk < KK; ++kk) {
+                bf16x8 kf = *(const bf16x8 *)(kp + kk * 512);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
             }
-            // scale, causal mask (register 4b+j of group h2 is key key0 + 32*h2 + 8b + 4g + j), running max
-            const bool need_mask = key0 + 63 > wave_min_pos;
+            // Register 4b + j is row 8b + 4g + j: page b / 2, slot 8(b%2) + 4g + j, which holds token
+            // 8g + 4(b%2) + j.  So registers 8p .. 8p+7 are tokens 8g .. 8g+7 of page p, in order.
+            const bool need_mask = key0 + kAttnTile - 1 > wave_min_pos;
             float mx = m_run;
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float v = s[h2][e] * a.scale_log2e;
-                    if (need_mask) {
-                        const int key = key0 + 32 * h2 + 8 * (e >> 2) + 4 * g + (e & 3);
-                        v = key <= pos ? v : -INFINITY;
-                    }
-                    s[h2][e] = v;
-                    mx = fmaxf(mx, v);
+            for (int e = 0; e < 16; ++e) {
+                float v = s[e] * a.scale_log2e;
+                if (need_mask) {
+                    const int key = key0 + 16 * (e >> 3) + 8 * g + (e & 7);
+                    v = key <= pos ? v : -INFINITY;
                 }
+                s[e] = v;
+                mx = fmaxf(mx, v);
+            }
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             // a row may see no key at all in this split's range yet: keep the arithmetic finite
             const float mref = mx == -INFINITY ? 0.f : mx;
-            const float alpha = exp2f(m_run - mref);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - mref);
             m_run = mx;
             float rs = 0.f;
 #pragma unroll
-            for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = exp2f(s[h2][e] - mref);
-                    s[h2][e] = p;
-                    rs += p;
-                }
+            for (int e = 0; e < 16; ++e) {
+                const float p = __builtin_amdgcn_exp2f(s[e] - mref);
+                s[e] = p;
+                rs += p;
+            }
             l_run = l_run * alpha + rs;
 #pragma unroll
             for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int p = 0; p < 2; ++p)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) o_acc[i][p][e] *= alpha;
+                for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
             // V slots at or past kmax may hold anything (even NaN): their probability is exactly 0, but 0 * NaN is
             // not, so the last tile zeroes them as it reads them.
-            const bool v_tail = key0 + 64 > kmax;
-            // PV: page pg of the tile uses registers 8*(pg%2) .. +7 of group pg/2 as its 8 k-slots
+            const bool v_tail = key0 + kAttnTile > kmax;
 #pragma unroll
-            for (int pg = 0; pg < 4; ++pg) {
+            for (int pg = 0; pg < 2; ++pg) {
                 bf16x8 pf;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[pg >> 1][8 * (pg & 1) + e];
-                // k-slot e<4 is token 4g+e, e>=4 is token 8+4g+(e-4): token groups g and g+2 of the page
-                const char *vp = sV + pg * BLK + col * 16;
-                uint32_t keep_lo = 0xffffffffu, keep_hi = 0xffffffffu, keep_lo2 = 0xffffffffu, keep_hi2 = 0xffffffffu;
-                if (v_tail) {
-                    // tokens of group g: key0 + 16 pg + 4 g + {0..3}; of group g + 2: eight further on
-                    const int left = kmax - (key0 + 16 * pg + 4 * g);  // tokens of group g that are valid
-                    const int left2 = left - 8;
-                    keep_lo = left >= 2 ? 0xffffffffu : left == 1 ? 0x0000ffffu : 0u;   // tokens 0, 1
-                    keep_hi = left >= 4 ? 0xffffffffu : left == 3 ? 0x0000ffffu : 0u;   // tokens 2, 3
-                    keep_lo2 = left2 >= 2 ? 0xffffffffu : left2 == 1 ? 0x0000ffffu : 0u;
-                    keep_hi2 = left2 >= 4 ? 0xffffffffu : left2 == 3 ? 0x0000ffffu : 0u;
-                }
+                for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[8 * pg + e];
+                // V block [2 token groups][hd][8]: lane (col, g) reads hd row 32 i + col of token group g
+                const char *vp = sV + pg * BLK + (g * HD + col) * 16;
+                const int left = kmax - (key0 + 16 * pg + 8 * g);  // tokens of this group that are valid
 #pragma unroll
                 for (int i = 0; i < RT; ++i) {
-                    uint4 lo = *(const uint4 *)(vp + ((g)*HD + 64 * i) * 8);
-                    uint4 hi = *(const uint4 *)(vp + ((g + 2) * HD + 64 * i) * 8);
+                    u32x4 vf = *(const u32x4 *)(vp + i * 512);
                     if (v_tail) {
-                        lo.x &= keep_lo, lo.y &= keep_hi, lo.z &= keep_lo, lo.w &= keep_hi;
-                        hi.x &= keep_lo2, hi.y &= keep_hi2, hi.z &= keep_lo2, hi.w &= keep_hi2;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (e >= left) vf[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
                     }
-                    // each 16 B holds hd rows (64i + 2*col) and (64i + 2*col + 1), 4 tokens each
-                    uint4 ev = make_uint4(lo.x, lo.y, hi.x, hi.y), od = make_uint4(lo.z, lo.w, hi.z, hi.w);
-                    o_acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&ev, pf, o_acc[i][0], 0, 0, 0);
-                    o_acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&od, pf, o_acc[i][1], 0, 0, 0);
+                    o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf, pf, o_acc[i], 0, 0, 0);
                 }
             }
         }
@@ -240,17 +230,15 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     if (!tok_ok) return;
     l_run += __shfl_xor(l_run, 32);  // both lanes of a column are valid together
     const int trow = c0 + local;
+    // o_acc[i][4b + j] is hd = 32 i + 8 b + 4 g + j
     if (a.n_splits > 1) {
-        // o_acc[i][par][4b+j] is hd = 64i + 16b + 8g + 2j + par: 8 consecutive floats per (i, b)
         float *po = a.part_o + (((size_t)z * a.T + trow) * a.Hq + hq) * HD;
 #pragma unroll
         for (int i = 0; i < RT; ++i)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                float4 x0 = {o_acc[i][0][4 * b + 0], o_acc[i][1][4 * b + 0], o_acc[i][0][4 * b + 1], o_acc[i][1][4 * b + 1]};
-                float4 x1 = {o_acc[i][0][4 * b + 2], o_acc[i][1][4 * b + 2], o_acc[i][0][4 * b + 3], o_acc[i][1][4 * b + 3]};
-                *(float4 *)(po + 64 * i + 16 * b + 8 * g) = x0;
-                *(float4 *)(po + 64 * i + 16 * b + 8 * g + 4) = x1;
+                float4 x = {o_acc[i][4 * b + 0], o_acc[i][4 * b + 1], o_acc[i][4 * b + 2], o_acc[i][4 * b + 3]};
+                *(float4 *)(po + 32 * i + 8 * b + 4 * g) = x;
             }
         if (g == 0) {
             float2 ml = {m_run, l_run};
@@ -263,12 +251,8 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            const int hd0 = 64 * i + 16 * b + 8 * g;
-            uint4 o = make_uint4(packh2(o_acc[i][0][4 * b + 0] * inv, o_acc[i][1][4 * b + 0] * inv),
-                                 packh2(o_acc[i][0][4 * b + 1] * inv, o_acc[i][1][4 * b + 1] * inv),
-                                 packh2(o_acc[i][0][4 * b + 2] * inv, o_acc[i][1][4 * b + 2] * inv),
-                                 packh2(o_acc[i][0][4 * b + 3] * inv, o_acc[i][1][4 * b + 3] * inv));
-            *(uint4 *)(a.out + p32_offset(trow, hq * HD + hd0, QKp)) = o;
+            uint2 o = {packh2(o_acc[i][4 * b + 0] * inv, o_acc[i][4 * b + 1] * inv), packh2(o_acc[i][4 * b + 2] * inv, o_acc[i][4 * b + 3] * inv)};
+            *(uint2 *)(a.out + p32_offset(trow, hq * HD + 32 * i + 8 * b + 4 * g, QKp)) = o;
         }
 }
 
@@ -283,7 +267,7 @@ __global__ __launch_bounds__(64) void attn_prefill_merge_kernel(AttnPrefillArgs 
     const int lt = local / (32 * SPB);
     int blk_last = (lt + 1) * 32 * SPB;
     if (blk_last > n_r) blk_last = n_r;
-    const int n_kv_tiles = (a.prefix_len[r] + blk_last + 63) >> 6;
+    const int n_kv_tiles = (a.prefix_len[r] + blk_last + kAttnTile - 1) / kAttnTile;
     float m = -INFINITY;
     for (int z = 0; z < a.n_splits; ++z) {
         int b, e;

@@ -61,9 +61,15 @@ __host__ __device__ __forceinline__ size_t p32_offset(int r, int k, int Kp) {
 __host__ __device__ __forceinline__ size_t p32_elems(int rows, int K) { return (size_t)round_up(rows, 32) * p32_kp(K); }
 
 // ---- private KV page layouts (one (page, kv head) block = 16 tokens x hd) ---------------------------------
-// K block: [hd / 8][16 tokens][8]   -> a wave reads 16 tokens x 32 hd (one 16x16x32 operand) as 1 KiB contiguous.
-// V block: [4 token groups][hd][4]  -> lanes own hd rows and read 4 consecutive tokens of a group.
-__host__ __device__ __forceinline__ int kblk_offset(int tok, int i) { return ((i >> 3) * kPage + tok) * 8 + (i & 7); }
-__host__ __device__ __forceinline__ int vblk_offset(int tok, int i, int hd) { return ((tok >> 2) * hd + i) * 4 + (tok & 3); }
+// Both attention kernels compute S^T = K Q^T and then feed the S^T accumulators, as they stand, into O^T = V^T P^T.
+// The accumulator layout of the MFMA gives a lane 4 consecutive rows of each S^T tile; two tiles give it 8
+// probabilities, which must be 8 consecutive tokens so that the matching V^T operand is one 16-byte read.
+//   K block: [hd / 8][16 slots][8], token t in slot kslot(t) = t with bits 2 and 3 swapped: slots 0..7 hold
+//            tokens {0..3, 8..11}, slots 8..15 tokens {4..7, 12..15}; an MFMA operand row is a slot, 16 B per lane,
+//            and 8 consecutive slots (one tile's share of a page) are 128 contiguous bytes.
+//   V block: [2 token groups][hd][8 tokens]: a lane reads hd row r of token group g as one 16-byte operand.
+__host__ __device__ __forceinline__ int kslot(int tok) { return (tok & 3) | ((tok & 8) >> 1) | ((tok & 4) << 1); }
+__host__ __device__ __forceinline__ int kblk_offset(int tok, int i) { return ((i >> 3) * kPage + kslot(tok)) * 8 + (i & 7); }
+__host__ __device__ __forceinline__ int vblk_offset(int tok, int i, int hd) { return ((tok >> 3) * hd + i) * 8 + (tok & 7); }
 
 }  // namespace nexus

@@ -116,6 +116,12 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
 
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt() {  // s_waitcnt lgkmcnt(N) alone (LDS / scalar-memory counter, 4 bits)
+    static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+    __builtin_amdgcn_s_waitcnt(0xc07f | (N << 8));
+}
+
 // ---- main GEMM: asynchronous global->LDS tile loads, NST-stage ring --------------------------------------------
 // A stage holds BKT k-tiles (16 k each) of FS weight strips and TS token strips, as 1 KiB units in P32 order.
 // The units of a stage are dealt round-robin to the wavefronts; a wavefront moves a unit with one
@@ -124,6 +130,19 @@ __device__ __forceinline__ void wait_vmcnt() {
 // One s_barrier per stage: a wavefront passes it after its own loads of the stage about to be consumed have
 // landed (vmcnt) and, having passed it, knows that every wavefront is done with the stage consumed before, which
 // is the one the next loads overwrite.
+// LDS read of one MFMA operand fragment with a compile-time offset (no address arithmetic in the main loop).
+template <int OFF>
+__device__ __forceinline__ void lds_read_frag(f16x8 &dst, unsigned base) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(base), "n"(OFF));
+}
+template <int N, int STRIDE, int KOFF, int I = 0>
+__device__ __forceinline__ void lds_read_frags(f16x8 (&dst)[N], unsigned base) {
+    if constexpr (I < N) {
+        lds_read_frag<I * STRIDE + KOFF>(dst[I], base);
+        lds_read_frags<N, STRIDE, KOFF, I + 1>(dst, base);
+    }
+}
+
 template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI>
 __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     constexpr int NW = WF * WT;
@@ -137,9 +156,15 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     constexpr int LPW = UNITS / NW;
     constexpr int STAGE = UNITS * 1024;
     static_assert((NST - 1) * LPW < 64, "vmcnt range");
+    static_assert(FW + TW < 16, "lgkmcnt range");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // Everything that depends on the wavefront index is kept in scalar registers (readfirstlane makes the index
+    // provably uniform): the main loop then spends its vector-ALU slots on MFMAs, not on address arithmetic.  The
+    // matrix unit only runs ahead while the wavefront keeps issuing MFMAs, so every VALU instruction between two
+    // groups of MFMAs is matrix-unit idle time.
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wf = w % WF, wt = w / WF;
     int nblk = gridDim.x, bid = blockIdx.x;
     if (a.n_xcd > 1 && nblk % a.n_xcd == 0) bid = (bid % a.n_xcd) * (nblk / a.n_xcd) + bid / a.n_xcd;
@@ -152,7 +177,7 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     const int nsteps = ktiles / BKT;  // Kp is a multiple of 64 and BKT divides 4
 
     const size_t strip_bytes = (size_t)(a.Kp >> 4) * 1024;
-    const char *ub[LPW];  // this wavefront's units: global address of k-step 0, this lane
+    const char *ub[LPW];  // this wavefront's units: uniform global address of k-step 0 (lane offset added at the load)
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
         const int u = w + NW * i, p = u / BKT, kt = u % BKT;
@@ -166,13 +191,15 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
             if (s >= a.n_ttiles) s = a.n_ttiles - 1;
             base = (const char *)a.X + (size_t)s * strip_bytes;
         }
-        ub[i] = base + (size_t)(ktile0 + kt) * 1024 + lane * 16;
+        ub[i] = base + (size_t)(ktile0 + kt) * 1024;
     }
+    const unsigned lane_off = lane * 16;
     auto issue = [&](int ks) {
         char *dst = smem + (ks % NST) * STAGE + w * 1024;
+        const size_t koff = (size_t)ks * (BKT * 1024);
 #pragma unroll
         for (int i = 0; i < LPW; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ub[i] + (size_t)ks * (BKT * 1024)),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ub[i] + koff + lane_off),
                                              (__attribute__((address_space(3))) void *)(dst + i * (NW * 1024)), 16, 0, 0);
     };
 
@@ -191,14 +218,36 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     // Software pipeline: operand fragments are read from LDS one k-tile ahead of the MFMAs that use them, also
     // across the stage boundary, so the matrix unit never waits on LDS latency.  The barrier that publishes stage
     // ks + 1 therefore sits before the LAST k-tile of stage ks.
+    //
+    // The LDS reads are issued with inline assembly and waited for by hand.  Left to the compiler, the wait before
+    // each group of MFMAs becomes lgkmcnt(0) wherever control flow merges (loop entry, the branch around the tail
+    // prefetch), which also waits for the reads that were issued one instruction earlier and stalls the matrix
+    // unit for a full LDS latency per k-tile.  The hand-placed wait is lgkmcnt(FW + TW): LDS reads return in
+    // order, so "at most the FW + TW newest outstanding" means the previous group has landed.  (A scalar load in
+    // flight can only make that wait more conservative.)
     f16x8 fa[2][FW], fb_[2][TW];
-    auto read_frags = [&](int buf, int ks, int kt) {
-        const char *sW = smem + (ks % NST) * STAGE + (wf * FW) * (BKT * 1024) + kt * 1024 + lane * 16;
-        const char *sX = smem + (ks % NST) * STAGE + (FS + wt * TW) * (BKT * 1024) + kt * 1024 + lane * 16;
+    const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem + (wf * FW) * (BKT * 1024) + lane * 16;
+    const unsigned lds_x = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem + (FS + wt * TW) * (BKT * 1024) + lane * 16;
+    auto read_frags = [&](int buf, int ks, auto kt_tag) {
+        constexpr int KT = decltype(kt_tag)::value;
+        const unsigned so = (ks % NST) * STAGE;
+        const unsigned bw = lds_w + so, bx = lds_x + so;
+        if (buf == 0) {
+            lds_read_frags<FW, BKT * 1024, KT * 1024>(fa[0], bw);
+            lds_read_frags<TW, BKT * 1024, KT * 1024>(fb_[0], bx);
+        } else {
+            lds_read_frags<FW, BKT * 1024, KT * 1024>(fa[1], bw);
+            lds_read_frags<TW, BKT * 1024, KT * 1024>(fb_[1], bx);
+        }
+    };
+    auto frags_ready = [&](int buf, bool newer_in_flight) {
+        if (newer_in_flight) wait_lgkmcnt<FW + TW>();
+        else wait_lgkmcnt<0>();
+        // tie the registers to the wait: the MFMAs below must not be scheduled above it
 #pragma unroll
-        for (int i = 0; i < FW; ++i) fa[buf][i] = *(const f16x8 *)(sW + i * (BKT * 1024));
+        for (int i = 0; i < FW; ++i) asm volatile("" : "+v"(fa[buf][i]));
 #pragma unroll
-        for (int j = 0; j < TW; ++j) fb_[buf][j] = *(const f16x8 *)(sX + j * (BKT * 1024));
+        for (int j = 0; j < TW; ++j) asm volatile("" : "+v"(fb_[buf][j]));
     };
     auto publish_next = [&](int ks) {
         // loads issued after those of step ks + 1 (and still allowed in flight): steps ks + 2 .. ks + NST - 2
@@ -211,40 +260,197 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     if (nsteps > 0) {
         wait_vmcnt<0>();  // prologue: stage 0 (whatever else is in flight lands too; once per kernel)
         __builtin_amdgcn_s_barrier();
-        read_frags(0, 0, 0);
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): enter the loop with nothing pending (see the loop's end)
+        read_frags(0, 0, std::integral_constant<int, 0>{});
     }
-    // One stage of MFMAs.  HAS_NEXT is a compile-time flag so that the steady-state loop body is straight-line
-    // code: with a branch around the next stage's fragment reads, the two paths would merge with different
-    // numbers of LDS reads pending and the compiler would have to wait for all of them before the MFMAs.
+    auto mfma_group = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < FW; ++i)
+#pragma unroll
+            for (int j = 0; j < TW; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
+    };
+    // One stage of MFMAs.  HAS_NEXT is a compile-time flag so that the steady-state loop body is straight-line code.
+    auto stage = [&](int ks, auto has_next) {
+        // k-tiles 0 .. BKT-2: prefetch the next k-tile of this stage, then multiply the current one
+        read_frags(1, ks, std::integral_constant<int, 1>{});
+        frags_ready(0, true);
+        mfma_group(0);
+        if constexpr (BKT == 4) {
+            read_frags(0, ks, std::integral_constant<int, 2>{});
+            frags_ready(1, true);
+            mfma_group(1);
+            read_frags(1, ks, std::integral_constant<int, 3>{});
+            frags_ready(0, true);
+            mfma_group(0);
+        }
+        // last k-tile: publish the next stage and prefetch its first k-tile
+        if constexpr (decltype(has_next)::value) {
+            publish_next(ks);
+            read_frags(0, ks + 1, std::integral_constant<int, 0>{});
+            frags_ready(1, true);
+        } else {
+            frags_ready(1, false);
+        }
+        mfma_group(1);
+    };
+    for (int ks = 0; ks + 1 < nsteps; ++ks) stage(ks, std::true_type{});
+    if (nsteps > 0) stage(nsteps - 1, std::false_type{});
+    gemm_epilogue<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane);
+}
+
+// ---- wide-N GEMM of a prefill chunk: whole-chunk token tile, asymmetric rings ------------------------------------
+// A prefill chunk of a few hundred tokens makes the projection GEMMs stream their weights from HBM at a rate close
+// to the HBM roofline (arithmetic intensity = chunk length flop/byte), so what limits them is how far ahead of
+// use the weight loads can be issued: lookahead = LDS bytes devoted to in-flight weights / consumption rate.  The
+// activations of the chunk, by contrast, are a few MiB that every workgroup re-reads from L2.  This kernel
+// therefore gives a workgroup ALL token strips of a 512-token block (so weights are fetched once, not once per
+// token block) and splits LDS into a deep ring for the small weight stages (NSW stages of FS x BKT KiB) and a
+// shallow ring for the large activation stages (NSX stages of 16 x BKT KiB).  Loads are counted per wavefront
+// and complete in order, so the two rings are filled by different wavefronts: 0..3 load activations, 4..7 load
+// weights; each waits only for its own loads and the stage barrier publishes both.
+// Eight wavefronts: wavefront w owns token strips 2w, 2w+1 and all FS feature strips (FS x 2 MFMA tiles).
+template <int FS, int BKT, int NSW, int NSX, int EPI>
+__global__ __launch_bounds__(512) void gemm_ft_kernel(GemmArgs a) {
+    constexpr int TS = 16, FW = FS, TW = 2, NW = 8;
+    constexpr int WSTAGE = FS * BKT * 1024, XSTAGE = TS * BKT * 1024;
+    constexpr int XLPW = TS * BKT / 4, WLPW = FS * BKT / 4;  // loads per loading wavefront per stage
+    static_assert(BKT == 2, "fragment double-buffer parity");
+    static_assert((FS * BKT) % 4 == 0, "weight units divide over four wavefronts");
+    static_assert(NSX >= 3 && NSW >= 3 && NSW <= 8, "ring depths");
+    static_assert(EPI != EPI_SWIGLU || FW % 2 == 0, "gate/up strip pairs stay in one wavefront");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char *ringW = smem, *ringX = smem + NSW * WSTAGE;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const bool x_loader = w < 4;
+    int nblk = gridDim.x, bid = blockIdx.x;
+    if (a.n_xcd > 1 && nblk % a.n_xcd == 0) bid = (bid % a.n_xcd) * (nblk / a.n_xcd) + bid / a.n_xcd;
+    const int tb = bid % a.n_tblk, fb = bid / a.n_tblk;
+    const int ft0 = fb * FS, tt0 = tb * TS;
+    const int z = blockIdx.z;
+    const int ktile0 = z * a.ksteps_per_split * 4;
+    int ktiles = (a.Kp >> 4) - ktile0;
+    if (ktiles > a.ksteps_per_split * 4) ktiles = a.ksteps_per_split * 4;
+    const int nsteps = ktiles / BKT;
+    const size_t strip_bytes = (size_t)(a.Kp >> 4) * 1024;
+
+    constexpr int MAXL = XLPW > WLPW ? XLPW : WLPW;
+    const char *ub[MAXL];
+#pragma unroll
+    for (int i = 0; i < MAXL; ++i) {
+        const int u = (w & 3) + 4 * i, p = u / BKT, kt = u % BKT;
+        const char *base;
+        if (x_loader) {
+            int s_ = tt0 + p;
+            if (s_ >= a.n_ttiles) s_ = a.n_ttiles - 1;  // out-of-range strips duplicate a valid one; never stored
+            base = (const char *)a.X + (size_t)s_ * strip_bytes;
+        } else {
+            int s_ = ft0 + (p < FS ? p : FS - 1);
+            if (s_ >= a.n_ftiles) s_ = a.n_ftiles - 1;
+            base = (const char *)a.W + (size_t)s_ * strip_bytes;
+        }
+        ub[i] = base + (size_t)(ktile0 + kt) * 1024 + lane * 16;
+    }
+    auto issue = [&](int ks) {  // this wavefront's share of stage ks of its ring
+        if (x_loader) {
+            char *dst = ringX + (ks % NSX) * XSTAGE + (w & 3) * 1024;
+#pragma unroll
+            for (int i = 0; i < XLPW; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ub[i] + (size_t)ks * (BKT * 1024)),
+                                                 (__attribute__((address_space(3))) void *)(dst + i * 4096), 16, 0, 0);
+        } else {
+            char *dst = ringW + (ks % NSW) * WSTAGE + (w & 3) * 1024;
+#pragma unroll
+            for (int i = 0; i < WLPW; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ub[i] + (size_t)ks * (BKT * 1024)),
+                                                 (__attribute__((address_space(3))) void *)(dst + i * 4096), 16, 0, 0);
+        }
+    };
+
+    f32x16 acc[FW][TW];
+#pragma unroll
+    for (int i = 0; i < FW; ++i)
+#pragma unroll
+        for (int j = 0; j < TW; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    {
+        const int pro = x_loader ? NSX - 1 : NSW - 1;
+        for (int s_ = 0; s_ < pro; ++s_)
+            if (s_ < nsteps) issue(s_);
+    }
+
+    f16x8 fa[2][FW], fb_[2][TW];
+    const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) char *)ringW + lane * 16;
+    const unsigned lds_x = (unsigned)(size_t)(__attribute__((address_space(3))) char *)ringX + (2 * w) * (BKT * 1024) + lane * 16;
+    auto read_frags = [&](int buf, int ks, int kt) {
+        const unsigned offw = (ks % NSW) * WSTAGE + kt * 1024, offx = (ks % NSX) * XSTAGE + kt * 1024;
+#pragma unroll
+        for (int i = 0; i < FW; ++i) asm volatile("ds_read_b128 %0, %1" : "=v"(fa[buf][i]) : "v"(lds_w + offw + i * (BKT * 1024)));
+#pragma unroll
+        for (int j = 0; j < TW; ++j) asm volatile("ds_read_b128 %0, %1" : "=v"(fb_[buf][j]) : "v"(lds_x + offx + j * (BKT * 1024)));
+    };
+    auto frags_ready = [&](int buf, bool newer_in_flight) {
+        if (newer_in_flight) wait_lgkmcnt<FW + TW>();
+        else wait_lgkmcnt<0>();
+#pragma unroll
+        for (int i = 0; i < FW; ++i) asm volatile("" : "+v"(fa[buf][i]));
+#pragma unroll
+        for (int j = 0; j < TW; ++j) asm volatile("" : "+v"(fb_[buf][j]));
+    };
+    auto publish_next = [&](int ks) {
+        // own loads issued after those of step ks + 1 and allowed to stay in flight
+        const int later = nsteps - 2 - ks;
+        if (x_loader) {
+            if (NSX >= 4 && later >= NSX - 3) wait_vmcnt<(NSX >= 4 ? NSX - 3 : 0) * XLPW>();
+            else wait_vmcnt<0>();
+        } else {
+            const int g_ = later < NSW - 3 ? later : NSW - 3;
+            switch (g_) {
+                case 5: wait_vmcnt<5 * WLPW>(); break;
+                case 4: wait_vmcnt<4 * WLPW>(); break;
+                case 3: wait_vmcnt<3 * WLPW>(); break;
+                case 2: wait_vmcnt<2 * WLPW>(); break;
+                case 1: wait_vmcnt<1 * WLPW>(); break;
+                default: wait_vmcnt<0>(); break;
+            }
+        }
+        __builtin_amdgcn_s_barrier();
+        const int nxt = ks + (x_loader ? NSX - 1 : NSW - 1);
+        if (nxt < nsteps) issue(nxt);
+    };
+    if (nsteps > 0) {
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        read_frags(0, 0, 0);
+    }
     auto stage = [&](int ks, auto has_next) {
 #pragma unroll
         for (int kt = 0; kt < BKT; ++kt) {
             const int c = kt & 1;
+            bool newer = true;
             if (kt == BKT - 1) {
                 if constexpr (decltype(has_next)::value) {
                     publish_next(ks);
                     read_frags(c ^ 1, ks + 1, 0);
+                } else {
+                    newer = false;
                 }
             } else {
                 read_frags(c ^ 1, ks, kt + 1);
             }
-            __builtin_amdgcn_sched_barrier(0);
+            frags_ready(c, newer);
 #pragma unroll
             for (int i = 0; i < FW; ++i)
 #pragma unroll
                 for (int j = 0; j < TW; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
         }
-        // The fragments of the next stage's first k-tile were requested a whole k-tile of MFMAs ago: settle the
-        // LDS counter here, at no cost, so that no read is pending across the loop back-edge (where the compiler
-        // would otherwise wait for everything, including the reads it has just issued).
-        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
     };
     for (int ks = 0; ks + 1 < nsteps; ++ks) stage(ks, std::true_type{});
     if (nsteps > 0) stage(nsteps - 1, std::false_type{});
-    gemm_epilogue<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane);
+    gemm_epilogue<FW, TW, EPI>(a, acc, ft0, tt0 + 2 * w, z, lane);
 }
 
 // Finishes a split-K GEMM: sums the S fp32 partials in slice order and applies the epilogue.

@@ -283,8 +283,8 @@ static int run_rmsnorm(const PhaseRun &r, const void *x, const bf16_t *g, f16_t 
 static int plan_attn_splits(int n_tokens, int n_q_heads, int max_total_len) {
     const int wave_tasks = ((n_tokens + 31) / 32) * n_q_heads;
     int S = (2048 + wave_tasks / 2) / wave_tasks;
-    const int tiles = (max_total_len + 63) / 64;
-    S = std::min(S, tiles / 4);  // at least 4 key tiles per split
+    const int tiles = (max_total_len + kAttnTile - 1) / kAttnTile;
+    S = std::min(S, tiles / 8);  // at least 8 key tiles per split
     return std::max(1, std::min(S, 8));
 }
 
@@ -293,7 +293,7 @@ static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
     nexus_ctx *c = r.c;
     const int G = c->m.n_q_heads / c->m.n_kv_heads;
     AttnPrefillArgs a = base;
-    constexpr int smem = 2 * 8 * kPage * HD * 2 + kAttnMaxPages * 4;
+    constexpr int smem = kAttnStages * 4 * kPage * HD * 2 + kAttnMaxPages * 4;
 #define NX_ATTN_CASE(GG, SPB)                                                                                        \
     case GG: {                                                                                                       \
         auto kern = attn_prefill_kernel<HD, GG, SPB>;                                                                \
@@ -332,12 +332,12 @@ static int launch_attn_decode(const PhaseRun &r, const AttnDecodeArgs &a) {
     nexus_ctx *c = r.c;
     const int G = c->m.n_q_heads / c->m.n_kv_heads;
     const int items = a.n_reqs * c->m.n_kv_heads * a.max_spans;
-    dim3 grid((items + 3) / 4), mgrid(a.n_reqs * c->m.n_q_heads);
+    dim3 grid((items + kDecWaves - 1) / kDecWaves), mgrid(a.n_reqs * c->m.n_q_heads);
 #define NX_DEC_CASE(GG)                                                                           \
     case GG: {                                                                                    \
         {                                                                                         \
             Tracer tr(c, r.phase, NEXUS_K_ATTN_DECODE, r.s);                                      \
-            hipLaunchKernelGGL((attn_decode_kernel<HD, GG>), grid, dim3(256), 0, r.s, a);         \
+            hipLaunchKernelGGL((attn_decode_kernel<HD, GG>), grid, dim3(64 * kDecWaves), 0, r.s, a);         \
         }                                                                                         \
         HIP_TRY(hipGetLastError());                                                               \
         {                                                                                         \
