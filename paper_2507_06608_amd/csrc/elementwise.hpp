@@ -166,8 +166,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
 
 // ---- weight packing: bf16 row-major [N][K] -> half P32 [round_up(N,32)][Kp], zero padded -----------------------
 // bf16 -> half is exact for |w| >= 2^-14 and off by at most 2^-25 below that.
-// interleave_F > 0 reorders gate/up rows so that 32-row strips alternate: strip 2s = gate rows [32s, 32s+32),
-// strip 2s+1 = up rows [32s, 32s+32) (a lane of the GEMM then holds a gate value and its up value).
+// interleave_F > 0 reorders gate/up rows so that packed strip s holds gate rows [16s, 16s+16) followed by up rows
+// [16s, 16s+16): in the 32x32 MFMA tile of the strip a lane then holds a gate value and, two register quads
+// later, its up value.
 __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, f16_t *__restrict__ dst, int N, int K, int Kp,
                                    int interleave_F) {
     const int Np = round_up(N, 32);
@@ -177,8 +178,8 @@ __global__ void pack_weight_kernel(const bf16_t *__restrict__ src, f16_t *__rest
     const int n = (int)(idx / kchunks), k = (int)(idx % kchunks) * 8;
     int srow = n;
     if (interleave_F > 0) {
-        const int strip = n >> 5;
-        srow = (strip & 1) * interleave_F + (strip >> 1) * 32 + (n & 31);
+        const int strip = n >> 5, r = n & 31;
+        srow = (r >> 4) * interleave_F + strip * 16 + (r & 15);
     }
     uint4 v = make_uint4(0, 0, 0, 0);
     if (n < N && k < K) {

@@ -20,7 +20,7 @@ namespace nexus {
 enum GemmEpi : int {
     EPI_ROWMAJOR = 0,  // out[t][f] = half(acc (+ bias[f]))                      (QKV projection)
     EPI_RES_IN = 1,    // out_f32[t][f] = bf16 res[t][f] + acc                   (x1 = x + attention projection)
-    EPI_SWIGLU = 2,    // weight strips alternate gate/up; out_p32[t][f] = half(silu(gate) * up)
+    EPI_SWIGLU = 2,    // each weight strip = 16 gate rows + their 16 up rows; out_p32[t][f] = half(silu(gate) * up)
     EPI_PARTIAL = 3,   // partial[z][t][n] = acc (fp32), finished by splitk_reduce
     EPI_RES_OUT = 4    // out[t][f] = bf16(res_f32[t][f] + acc)                  (y = x1 + down projection)
 };
@@ -57,16 +57,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[F
         const int t = (tt0 + j) * 32 + (lane & 31);
         if (t >= a.T) continue;
         if constexpr (EPI == EPI_SWIGLU) {
+            // packed strip s = gate features [16 s, 16 s + 16) in rows 0..15, their up features in rows 16..31:
+            // register quads b and b + 2 of one lane are a gate quad and its up quad
 #pragma unroll
-            for (int i = 0; i < FW; i += 2) {
+            for (int i = 0; i < FW; ++i) {
                 const int ft = ft0 + i;
                 if (ft >= a.n_ftiles) continue;
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int f = (ft >> 1) * 32 + 8 * b + 4 * g;
+                for (int b = 0; b < 2; ++b) {
+                    const int f = ft * 16 + 8 * b + 4 * g;
                     float v[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = silu_f(acc[i][j][4 * b + e]) * acc[i + 1][j][4 * b + e];
+                    for (int e = 0; e < 4; ++e) v[e] = silu_f(acc[i][j][4 * b + e]) * acc[i][j][4 * (b + 2) + e];
                     uint2 o = {packh2(v[0], v[1]), packh2(v[2], v[3])};
                     *(uint2 *)(a.out_p32 + p32_offset(t, f, a.out_Kp)) = o;
                 }
@@ -143,15 +145,14 @@ __device__ __forceinline__ void lds_read_frags(f16x8 (&dst)[N], unsigned base) {
     }
 }
 
-template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI>
+template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI, bool ASM_READS = true>
 __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     constexpr int NW = WF * WT;
     constexpr int FW = FS / WF, TW = TS / WT;
     constexpr int NP = FS + TS;
     constexpr int UNITS = NP * BKT;
     static_assert(UNITS % NW == 0, "units must divide evenly over the wavefronts");
-    static_assert(EPI != EPI_SWIGLU || FW % 2 == 0, "gate/up strip pairs stay in one wavefront");
-    static_assert(NST >= 3 && NST <= 4, "ring of 3 or 4 stages (the stage being refilled must differ from the one just published)");
+    static_assert(NST >= 3 && NST <= 6, "ring of 3 or 4 stages (the stage being refilled must differ from the one just published)");
     static_assert(BKT == 2 || BKT == 4, "fragment double-buffer parity needs an even number of k-tiles per stage");
     constexpr int LPW = UNITS / NW;
     constexpr int STAGE = UNITS * 1024;
@@ -225,29 +226,47 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     // unit for a full LDS latency per k-tile.  The hand-placed wait is lgkmcnt(FW + TW): LDS reads return in
     // order, so "at most the FW + TW newest outstanding" means the previous group has landed.  (A scalar load in
     // flight can only make that wait more conservative.)
+    //
+    // The price: between such a read and its wait the compiler believes the destination registers already hold
+    // the data, so a register copy or reuse it chose to insert there would be silently wrong.  Every
+    // ASM_READS = true instantiation that the library launches is therefore covered by the bit-level parity
+    // tests; ASM_READS = false keeps the reads visible to the compiler (always correct, one exposed LDS latency
+    // per stage) and is what rarely used instantiations take.
     f16x8 fa[2][FW], fb_[2][TW];
     const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem + (wf * FW) * (BKT * 1024) + lane * 16;
     const unsigned lds_x = (unsigned)(size_t)(__attribute__((address_space(3))) char *)smem + (FS + wt * TW) * (BKT * 1024) + lane * 16;
     auto read_frags = [&](int buf, int ks, auto kt_tag) {
         constexpr int KT = decltype(kt_tag)::value;
         const unsigned so = (ks % NST) * STAGE;
-        const unsigned bw = lds_w + so, bx = lds_x + so;
-        if (buf == 0) {
-            lds_read_frags<FW, BKT * 1024, KT * 1024>(fa[0], bw);
-            lds_read_frags<TW, BKT * 1024, KT * 1024>(fb_[0], bx);
+        if constexpr (ASM_READS) {
+            const unsigned bw = lds_w + so, bx = lds_x + so;
+            if (buf == 0) {
+                lds_read_frags<FW, BKT * 1024, KT * 1024>(fa[0], bw);
+                lds_read_frags<TW, BKT * 1024, KT * 1024>(fb_[0], bx);
+            } else {
+                lds_read_frags<FW, BKT * 1024, KT * 1024>(fa[1], bw);
+                lds_read_frags<TW, BKT * 1024, KT * 1024>(fb_[1], bx);
+            }
         } else {
-            lds_read_frags<FW, BKT * 1024, KT * 1024>(fa[1], bw);
-            lds_read_frags<TW, BKT * 1024, KT * 1024>(fb_[1], bx);
+            const char *bw = smem + (wf * FW) * (BKT * 1024) + lane * 16 + so;
+            const char *bx = smem + (FS + wt * TW) * (BKT * 1024) + lane * 16 + so;
+#pragma unroll
+            for (int i = 0; i < FW; ++i) fa[buf][i] = *(const f16x8 *)(bw + (i * BKT + KT) * 1024);
+#pragma unroll
+            for (int j = 0; j < TW; ++j) fb_[buf][j] = *(const f16x8 *)(bx + (j * BKT + KT) * 1024);
+            __builtin_amdgcn_sched_barrier(0);  // issued here, ahead of the MFMAs that hide their latency
         }
     };
     auto frags_ready = [&](int buf, bool newer_in_flight) {
-        if (newer_in_flight) wait_lgkmcnt<FW + TW>();
-        else wait_lgkmcnt<0>();
-        // tie the registers to the wait: the MFMAs below must not be scheduled above it
+        if constexpr (ASM_READS) {
+            if (newer_in_flight) wait_lgkmcnt<FW + TW>();
+            else wait_lgkmcnt<0>();
+            // tie the registers to the wait: the MFMAs below must not be scheduled above it
 #pragma unroll
-        for (int i = 0; i < FW; ++i) asm volatile("" : "+v"(fa[buf][i]));
+            for (int i = 0; i < FW; ++i) asm volatile("" : "+v"(fa[buf][i]));
 #pragma unroll
-        for (int j = 0; j < TW; ++j) asm volatile("" : "+v"(fb_[buf][j]));
+            for (int j = 0; j < TW; ++j) asm volatile("" : "+v"(fb_[buf][j]));
+        }
     };
     auto publish_next = [&](int ks) {
         // loads issued after those of step ks + 1 (and still allowed in flight): steps ks + 2 .. ks + NST - 2
@@ -267,7 +286,8 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
         for (int i = 0; i < FW; ++i)
 #pragma unroll
             for (int j = 0; j < TW; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);  // later waits and barriers stay behind these MFMAs
     };
     // One stage of MFMAs.  HAS_NEXT is a compile-time flag so that the steady-state loop body is straight-line code.
     auto stage = [&](int ks, auto has_next) {
@@ -283,7 +303,9 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
             frags_ready(0, true);
             mfma_group(0);
         }
-        // last k-tile: publish the next stage and prefetch its first k-tile
+        // last k-tile: publish the next stage and prefetch its first k-tile, so that the MFMAs of this k-tile
+        // (operands read long before) run right behind the barrier and cover the LDS latency of the prefetch.
+        // (Placing the barrier in the middle of this k-tile's MFMAs instead measured about 3% slower.)
         if constexpr (decltype(has_next)::value) {
             publish_next(ks);
             read_frags(0, ks + 1, std::integral_constant<int, 0>{});
@@ -298,73 +320,75 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     gemm_epilogue<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane);
 }
 
-// ---- wide-N GEMM of a prefill chunk: whole-chunk token tile, asymmetric rings ------------------------------------
-// A prefill chunk of a few hundred tokens makes the projection GEMMs stream their weights from HBM at a rate close
-// to the HBM roofline (arithmetic intensity = chunk length flop/byte), so what limits them is how far ahead of
-// use the weight loads can be issued: lookahead = LDS bytes devoted to in-flight weights / consumption rate.  The
-// activations of the chunk, by contrast, are a few MiB that every workgroup re-reads from L2.  This kernel
-// therefore gives a workgroup ALL token strips of a 512-token block (so weights are fetched once, not once per
-// token block) and splits LDS into a deep ring for the small weight stages (NSW stages of FS x BKT KiB) and a
-// shallow ring for the large activation stages (NSX stages of 16 x BKT KiB).  Loads are counted per wavefront
-// and complete in order, so the two rings are filled by different wavefronts: 0..3 load activations, 4..7 load
-// weights; each waits only for its own loads and the stage barrier publishes both.
-// Eight wavefronts: wavefront w owns token strips 2w, 2w+1 and all FS feature strips (FS x 2 MFMA tiles).
-template <int FS, int BKT, int NSW, int NSX, int EPI>
-__global__ __launch_bounds__(512) void gemm_ft_kernel(GemmArgs a) {
-    constexpr int TS = 16, FW = FS, TW = 2, NW = 8;
-    constexpr int WSTAGE = FS * BKT * 1024, XSTAGE = TS * BKT * 1024;
-    constexpr int XLPW = TS * BKT / 4, WLPW = FS * BKT / 4;  // loads per loading wavefront per stage
-    static_assert(BKT == 2, "fragment double-buffer parity");
-    static_assert((FS * BKT) % 4 == 0, "weight units divide over four wavefronts");
-    static_assert(NSX >= 3 && NSW >= 3 && NSW <= 8, "ring depths");
-    static_assert(EPI != EPI_SWIGLU || FW % 2 == 0, "gate/up strip pairs stay in one wavefront");
+// ---- weight-streaming GEMM of a decode batch -------------------------------------------------------------------
+// With at most 64 tokens every weight byte is used once, so the GEMM is a sweep over the weights (Sec. 2.3: decode
+// is bound by memory traffic) and its speed on a share of the chip is set by the bytes each CU keeps in flight:
+// one CU draws at most about 50 GB/s from HBM and needs on the order of 100 KiB outstanding to get there.  An LDS
+// ring cannot hold that much beside its resident stages, and nothing here is shared between wavefronts anyway:
+// each wavefront owns FW feature strips and all tokens.  So the weights bypass LDS: the P32 tile order makes a
+// 1 KiB tile exactly one MFMA A-operand, fetched by one 16-byte-per-lane load straight into registers, DST stages
+// (DST * BKT tiles per strip) ahead of use.  Only the activations, which every wavefront of the workgroup needs,
+// go through a small asynchronous LDS ring of NSX = DST + 1 stages.
+//
+// Per-element summation order (k-tiles in sequence, slices of the k range in the partial buffer) is the same as
+// in gemm_dl_kernel, so the two are interchangeable bit for bit.
+template <int FW, int TW, int NW, int BKT, int DST, int EPI>
+__global__ __launch_bounds__(64 * NW) void gemm_stream_kernel(GemmArgs a) {
+    constexpr int NSX = DST + 1;
+    constexpr int XUNITS = TW * BKT;  // 1 KiB activation tiles per stage
+    static_assert(XUNITS % NW == 0, "activation tiles must divide evenly over the wavefronts");
+    constexpr int LPWX = XUNITS / NW;
+    constexpr int XSTAGE = XUNITS * 1024;
+    constexpr int PER_STAGE = LPWX + BKT * FW;  // vector-memory instructions a wavefront issues per stage
+    static_assert((DST - 1) * PER_STAGE < 64, "vmcnt range");
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char *ringW = smem, *ringX = smem + NSW * WSTAGE;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const bool x_loader = w < 4;
-    int nblk = gridDim.x, bid = blockIdx.x;
-    if (a.n_xcd > 1 && nblk % a.n_xcd == 0) bid = (bid % a.n_xcd) * (nblk / a.n_xcd) + bid / a.n_xcd;
-    const int tb = bid % a.n_tblk, fb = bid / a.n_tblk;
-    const int ft0 = fb * FS, tt0 = tb * TS;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tb = blockIdx.x % a.n_tblk, fb = blockIdx.x / a.n_tblk;
+    const int ft0 = (fb * NW + w) * FW, tt0 = tb * TW;
     const int z = blockIdx.z;
     const int ktile0 = z * a.ksteps_per_split * 4;
     int ktiles = (a.Kp >> 4) - ktile0;
     if (ktiles > a.ksteps_per_split * 4) ktiles = a.ksteps_per_split * 4;
-    const int nsteps = ktiles / BKT;
-    const size_t strip_bytes = (size_t)(a.Kp >> 4) * 1024;
+    const int nsteps = ktiles / BKT;  // >= DST: the host launches this kernel only then
 
-    constexpr int MAXL = XLPW > WLPW ? XLPW : WLPW;
-    const char *ub[MAXL];
+    const size_t strip_bytes = (size_t)(a.Kp >> 4) * 1024;
+    const unsigned lane_off = lane * 16;
+    const char *wb[FW];  // uniform: k-step 0 of this wavefront's weight strips
 #pragma unroll
-    for (int i = 0; i < MAXL; ++i) {
-        const int u = (w & 3) + 4 * i, p = u / BKT, kt = u % BKT;
-        const char *base;
-        if (x_loader) {
-            int s_ = tt0 + p;
-            if (s_ >= a.n_ttiles) s_ = a.n_ttiles - 1;  // out-of-range strips duplicate a valid one; never stored
-            base = (const char *)a.X + (size_t)s_ * strip_bytes;
-        } else {
-            int s_ = ft0 + (p < FS ? p : FS - 1);
-            if (s_ >= a.n_ftiles) s_ = a.n_ftiles - 1;
-            base = (const char *)a.W + (size_t)s_ * strip_bytes;
-        }
-        ub[i] = base + (size_t)(ktile0 + kt) * 1024 + lane * 16;
+    for (int i = 0; i < FW; ++i) {
+        int s = ft0 + i;
+        if (s >= a.n_ftiles) s = a.n_ftiles - 1;  // out-of-range strips duplicate a valid one; never stored
+        wb[i] = (const char *)a.W + (size_t)s * strip_bytes + (size_t)ktile0 * 1024;
     }
-    auto issue = [&](int ks) {  // this wavefront's share of stage ks of its ring
-        if (x_loader) {
-            char *dst = ringX + (ks % NSX) * XSTAGE + (w & 3) * 1024;
+    const char *xb[LPWX];  // uniform: k-step 0 of the activation tiles this wavefront fetches
 #pragma unroll
-            for (int i = 0; i < XLPW; ++i)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ub[i] + (size_t)ks * (BKT * 1024)),
-                                                 (__attribute__((address_space(3))) void *)(dst + i * 4096), 16, 0, 0);
-        } else {
-            char *dst = ringW + (ks % NSW) * WSTAGE + (w & 3) * 1024;
+    for (int i = 0; i < LPWX; ++i) {
+        const int u = w + NW * i, ts = u / BKT, kt = u % BKT;
+        int s = tt0 + ts;
+        if (s >= a.n_ttiles) s = a.n_ttiles - 1;
+        xb[i] = (const char *)a.X + (size_t)s * strip_bytes + (size_t)(ktile0 + kt) * 1024;
+    }
+    auto issue_x = [&](int ks) {
+        char *dst = smem + (ks % NSX) * XSTAGE + w * 1024;
+        const size_t koff = (size_t)ks * (BKT * 1024);
 #pragma unroll
-            for (int i = 0; i < WLPW; ++i)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ub[i] + (size_t)ks * (BKT * 1024)),
-                                                 (__attribute__((address_space(3))) void *)(dst + i * 4096), 16, 0, 0);
-        }
+        for (int i = 0; i < LPWX; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xb[i] + koff + lane_off),
+                                             (__attribute__((address_space(3))) void *)(dst + i * (NW * 1024)), 16, 0, 0);
+    };
+    // Weight loads are ordinary loads: the compiler knows when their registers are valid (an inline-assembly load
+    // would return into registers the compiler is free to copy or reuse before the data lands).  It may move them
+    // within a stage, never across the stage barriers, which is all the counted waits below rely on.
+    f16x8 wr[DST][FW][BKT];
+    auto issue_w = [&](auto d_tag, int ks) {
+        constexpr int D = decltype(d_tag)::value;
+        const size_t koff = (size_t)ks * (BKT * 1024) + lane_off;
+#pragma unroll
+        for (int i = 0; i < FW; ++i)
+#pragma unroll
+            for (int kt = 0; kt < BKT; ++kt) wr[D][i][kt] = *(const f16x8 *)(wb[i] + koff + kt * 1024);
     };
 
     f32x16 acc[FW][TW];
@@ -375,82 +399,77 @@ __global__ __launch_bounds__(512) void gemm_ft_kernel(GemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    {
-        const int pro = x_loader ? NSX - 1 : NSW - 1;
-        for (int s_ = 0; s_ < pro; ++s_)
-            if (s_ < nsteps) issue(s_);
-    }
-
-    f16x8 fa[2][FW], fb_[2][TW];
-    const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) char *)ringW + lane * 16;
-    const unsigned lds_x = (unsigned)(size_t)(__attribute__((address_space(3))) char *)ringX + (2 * w) * (BKT * 1024) + lane * 16;
-    auto read_frags = [&](int buf, int ks, int kt) {
-        const unsigned offw = (ks % NSW) * WSTAGE + kt * 1024, offx = (ks % NSX) * XSTAGE + kt * 1024;
-#pragma unroll
-        for (int i = 0; i < FW; ++i) asm volatile("ds_read_b128 %0, %1" : "=v"(fa[buf][i]) : "v"(lds_w + offw + i * (BKT * 1024)));
-#pragma unroll
-        for (int j = 0; j < TW; ++j) asm volatile("ds_read_b128 %0, %1" : "=v"(fb_[buf][j]) : "v"(lds_x + offx + j * (BKT * 1024)));
-    };
-    auto frags_ready = [&](int buf, bool newer_in_flight) {
-        if (newer_in_flight) wait_lgkmcnt<FW + TW>();
-        else wait_lgkmcnt<0>();
-#pragma unroll
-        for (int i = 0; i < FW; ++i) asm volatile("" : "+v"(fa[buf][i]));
-#pragma unroll
-        for (int j = 0; j < TW; ++j) asm volatile("" : "+v"(fb_[buf][j]));
-    };
-    auto publish_next = [&](int ks) {
-        // own loads issued after those of step ks + 1 and allowed to stay in flight
-        const int later = nsteps - 2 - ks;
-        if (x_loader) {
-            if (NSX >= 4 && later >= NSX - 3) wait_vmcnt<(NSX >= 4 ? NSX - 3 : 0) * XLPW>();
-            else wait_vmcnt<0>();
-        } else {
-            const int g_ = later < NSW - 3 ? later : NSW - 3;
-            switch (g_) {
-                case 5: wait_vmcnt<5 * WLPW>(); break;
-                case 4: wait_vmcnt<4 * WLPW>(); break;
-                case 3: wait_vmcnt<3 * WLPW>(); break;
-                case 2: wait_vmcnt<2 * WLPW>(); break;
-                case 1: wait_vmcnt<1 * WLPW>(); break;
-                default: wait_vmcnt<0>(); break;
-            }
-        }
-        __builtin_amdgcn_s_barrier();
-        const int nxt = ks + (x_loader ? NSX - 1 : NSW - 1);
-        if (nxt < nsteps) issue(nxt);
-    };
-    if (nsteps > 0) {
-        wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        read_frags(0, 0, 0);
-    }
-    auto stage = [&](int ks, auto has_next) {
+    // One stage.  D = register set (stage index modulo DST), PREFETCH = whether stage ks + DST exists; both are
+    // compile-time so that the loop bodies below are straight-line code and the waits stay exact.  Loads complete
+    // in issue order and the load sets of different stages are separated by barriers: when at most the loads of
+    // the DST - 1 newer stages are outstanding, everything of stage ks has landed.
+    auto stage = [&](auto d_tag, auto prefetch_tag, int ks, int newer_stages) {
+        constexpr int D = decltype(d_tag)::value;
+        // own activation tiles of stage ks landed: at most the loads of the DST - 1 newer stages stay in flight
+        if (newer_stages >= DST - 1) wait_vmcnt<(DST - 1) * PER_STAGE>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();  // stage ks visible to all; every wavefront is done with stage ks - 1
+        if constexpr (decltype(prefetch_tag)::value) issue_x(ks + DST);  // into the slot of stage ks - 1
+        const char *xs = smem + (ks % NSX) * XSTAGE + lane_off;
 #pragma unroll
         for (int kt = 0; kt < BKT; ++kt) {
-            const int c = kt & 1;
-            bool newer = true;
-            if (kt == BKT - 1) {
-                if constexpr (decltype(has_next)::value) {
-                    publish_next(ks);
-                    read_frags(c ^ 1, ks + 1, 0);
-                } else {
-                    newer = false;
-                }
-            } else {
-                read_frags(c ^ 1, ks, kt + 1);
-            }
-            frags_ready(c, newer);
+            f16x8 xf[TW];
+#pragma unroll
+            for (int j = 0; j < TW; ++j) xf[j] = *(const f16x8 *)(xs + (j * BKT + kt) * 1024);
 #pragma unroll
             for (int i = 0; i < FW; ++i)
 #pragma unroll
                 for (int j = 0; j < TW; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wr[D][i][kt], xf[j], acc[i][j], 0, 0, 0);
         }
+        if constexpr (decltype(prefetch_tag)::value) issue_w(d_tag, ks + DST);
     };
-    for (int ks = 0; ks + 1 < nsteps; ++ks) stage(ks, std::true_type{});
-    if (nsteps > 0) stage(nsteps - 1, std::false_type{});
-    gemm_epilogue<FW, TW, EPI>(a, acc, ft0, tt0 + 2 * w, z, lane);
+    // group of N consecutive stages starting at a multiple of DST; the first PF of them prefetch
+    auto group = [&](auto n_tag, auto pf_tag, int s0) {
+        constexpr int N = decltype(n_tag)::value, PF = decltype(pf_tag)::value;
+        auto one = [&](auto i_tag) {
+            constexpr int I = decltype(i_tag)::value;
+            if constexpr (I < N) {
+                stage(std::integral_constant<int, I % DST>{}, std::integral_constant<bool, (I < PF)>{}, s0 + I,
+                      PF == N ? DST - 1 : (N - 1 - I));
+            }
+        };
+        one(std::integral_constant<int, 0>{});
+        one(std::integral_constant<int, 1>{});
+        one(std::integral_constant<int, 2>{});
+        one(std::integral_constant<int, 3>{});
+        one(std::integral_constant<int, 4>{});
+        one(std::integral_constant<int, 5>{});
+        one(std::integral_constant<int, 6>{});
+        one(std::integral_constant<int, 7>{});
+    };
+    static_assert(2 * DST <= 8, "group() unrolls at most 8 stages");
+
+    // prologue: stages 0 .. DST-1 in flight (activation tiles first within each stage, as in the steady state)
+    {
+        auto pro = [&](auto d_tag) {
+            constexpr int D = decltype(d_tag)::value;
+            if constexpr (D < DST) {
+                issue_x(D);
+                issue_w(d_tag, D);
+                __builtin_amdgcn_sched_barrier(0);  // keep the stages' load sets in order (no barrier between them here)
+            }
+        };
+        pro(std::integral_constant<int, 0>{});
+        pro(std::integral_constant<int, 1>{});
+        pro(std::integral_constant<int, 2>{});
+        pro(std::integral_constant<int, 3>{});
+    }
+    static_assert(DST <= 4, "prologue unrolls at most 4 stages");
+    int s0 = 0;
+    for (; s0 + 2 * DST <= nsteps; s0 += DST) group(std::integral_constant<int, DST>{}, std::integral_constant<int, DST>{}, s0);
+    // DST + r stages remain (0 <= r < DST): the first r still prefetch
+    const int r = nsteps - s0 - DST;
+    if (r == 0) group(std::integral_constant<int, DST>{}, std::integral_constant<int, 0>{}, s0);
+    if constexpr (DST >= 2) if (r == 1) group(std::integral_constant<int, DST + 1>{}, std::integral_constant<int, 1>{}, s0);
+    if constexpr (DST >= 3) if (r == 2) group(std::integral_constant<int, DST + 2>{}, std::integral_constant<int, 2>{}, s0);
+    if constexpr (DST >= 4) if (r == 3) group(std::integral_constant<int, DST + 3>{}, std::integral_constant<int, 3>{}, s0);
+    gemm_epilogue<FW, TW, EPI>(a, acc, ft0, tt0, z, lane);
 }
 
 // Finishes a split-K GEMM: sums the S fp32 partials in slice order and applies the epilogue.
@@ -473,17 +492,17 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceArgs a) {
     if (idx >= (size_t)a.T * quads) return;
     const int t = (int)(idx / quads), n = (int)(idx % quads) * 4;
     if constexpr (EPI == EPI_SWIGLU) {
-        // packed rows: strip 2s holds gate features [32s, 32s+32), strip 2s+1 the matching up features
+        // packed rows: strip s holds gate features [16s, 16s+16) in rows 0..15, the matching up features in 16..31
         const int strip = n >> 5;
-        if (strip & 1) return;
+        if (n & 16) return;
         float gsum[4] = {0, 0, 0, 0}, usum[4] = {0, 0, 0, 0};
         for (int s = 0; s < a.S; ++s) {
             const float *p = a.partial + ((size_t)s * a.T + t) * a.N + n;
-            float4 gv = *(const float4 *)p, uv = *(const float4 *)(p + 32);
+            float4 gv = *(const float4 *)p, uv = *(const float4 *)(p + 16);
             gsum[0] += gv.x, gsum[1] += gv.y, gsum[2] += gv.z, gsum[3] += gv.w;
             usum[0] += uv.x, usum[1] += uv.y, usum[2] += uv.z, usum[3] += uv.w;
         }
-        const int f = (strip >> 1) * 32 + (n & 31);
+        const int f = strip * 16 + (n & 15);
         uint2 o = {packh2(silu_f(gsum[0]) * usum[0], silu_f(gsum[1]) * usum[1]),
                    packh2(silu_f(gsum[2]) * usum[2], silu_f(gsum[3]) * usum[3])};
         *(uint2 *)(a.out_p32 + p32_offset(t, f, a.out_Kp)) = o;

@@ -121,14 +121,16 @@ static int dev_alloc(T **p, size_t elems, bool zero) {
 
 // ---------------------------------------------------------------------------------------------- GEMM planning
 // Tile shapes (features x tokens), wavefronts, k per stage, ring depth.  Measured on MI355X: 128x128 tiles with
-// more workgroups per CU beat 256x256 at the token counts of a prefill chunk; a decode batch (<= 64 tokens) streams
-// the weights once and wants many small workgroups with deep rings to keep HBM busy.
+// several workgroups per CU beat 256x256 at the token counts of a prefill chunk (and quantise far better on a CU
+// share); a decode batch (<= 64 tokens) streams the weights once and wants many small workgroups whose rings
+// together keep about 100 KiB per CU in flight: one CU draws at most about 50 GB/s from HBM, so a decode share of
+// the chip is bound by per-CU bytes in flight, not by the HBM interface.
 enum GemmVariant {
-    GV_P128_BK32 = 0,  // 128 x 128, 4 waves, 64 KiB LDS: several workgroups per CU
-    GV_P128_BK64,      // 128 x 128, 4 waves, 128 KiB LDS: deeper ring for launches that cannot fill the chip anyway
-    GV_D128,           // 128 x 64 tokens, 4 waves: wide decode GEMMs (gate/up)
-    GV_D64,            // 64 x 64 tokens, 2 waves: narrow decode GEMMs, split along K
-    GV_D256_T32,       // 256 x 32 tokens, 4 waves: decode batches of at most 32
+    GV_P128 = 0,  // gemm_dl_kernel, 128 x 128, 4 waves, 32-wide stages, 64 KiB ring: two workgroups per CU
+    GV_S64,       // gemm_stream_kernel, 128 features x 64 tokens, 4 waves: decode batches of 33..64
+    GV_S32,       // gemm_stream_kernel, 128 features x 32 tokens, 4 waves: decode batches of at most 32
+    GV_R64,       // gemm_dl_kernel with the extent of GV_S64 / GV_S32: k ranges shorter than the streaming
+    GV_R32,       //   kernel's pipeline (hidden sizes below 128)
     GV_COUNT
 };
 struct GemmPlan {
@@ -136,36 +138,40 @@ struct GemmPlan {
 };
 constexpr int kChipCUs = 256;  // the plan is sized for the whole chip, whatever share the phase runs on
 
-// Depends on the problem only (never on the CU share), so that results are bit-identical across layouts.
+// Depends on the problem only (never on the CU share): S fixes the summation order, so results are bit-identical
+// across layouts.  Decode GEMMs are cut along K until there are about 200 workgroups (800 wavefronts, each
+// with its own weight stream in flight); measured on MI355X, more slices cost more in partial-sum traffic than
+// they gain.
 static GemmPlan plan_gemm(int T, int n_ftiles, int Kp) {
     const int ksteps = Kp / kGemmBK;
     const int nt = (T + 31) / 32;
     GemmPlan p{};
     int min_ksteps;
     if (T <= 32) {
-        p.variant = GV_D256_T32, p.FS = 8, p.TS = 1, min_ksteps = 8;
+        p.variant = GV_S32, p.FS = 4, p.TS = 1, min_ksteps = 8;
     } else if (T <= 64) {
-        if (n_ftiles >= 512) p.variant = GV_D128, p.FS = 4, p.TS = 2;
-        else p.variant = GV_D64, p.FS = 2, p.TS = 2;
-        min_ksteps = 8;
+        p.variant = GV_S64, p.FS = 4, p.TS = 2, min_ksteps = 8;
     } else {
-        p.FS = 4, p.TS = 4, min_ksteps = 16;
+        p.variant = GV_P128, p.FS = 4, p.TS = 4, min_ksteps = 16;
     }
     const int blocks = ((n_ftiles + p.FS - 1) / p.FS) * ((nt + p.TS - 1) / p.TS);
     int S = 1;
-    if (blocks < (3 * kChipCUs) / 4) S = std::min(T <= 64 ? 8 : 4, (kChipCUs + blocks / 2) / blocks);
+    if (T <= 64) {
+        while (S < 8 && blocks * S < (3 * kChipCUs) / 4) S *= 2;
+    } else if (blocks < (3 * kChipCUs) / 4) {
+        S = std::min(4, (kChipCUs + blocks / 2) / blocks);
+    }
     while (S > 1 && ksteps / S < min_ksteps) --S;
     p.ksteps_per_split = (ksteps + S - 1) / S;
     p.S = (ksteps + p.ksteps_per_split - 1) / p.ksteps_per_split;
-    if (T > 64) p.variant = blocks * p.S <= kChipCUs + kChipCUs / 4 ? GV_P128_BK64 : GV_P128_BK32;
     return p;
 }
 
-template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI>
+template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI, bool ASM_READS = true>
 static hipError_t launch_gemm_t(const GemmArgs &a, dim3 grid, hipStream_t s) {
     constexpr int smem = NST * (FS + TS) * BKT * 1024;
     static bool attr_done = false;  // one context thread at a time (see header)
-    auto kern = gemm_dl_kernel<FS, TS, WF, WT, BKT, NST, EPI>;
+    auto kern = gemm_dl_kernel<FS, TS, WF, WT, BKT, NST, EPI, ASM_READS>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
@@ -175,14 +181,30 @@ static hipError_t launch_gemm_t(const GemmArgs &a, dim3 grid, hipStream_t s) {
     return hipGetLastError();
 }
 
+constexpr int kStreamDepth = 2;  // stages of weight tiles a streaming wavefront keeps in flight
+
+template <int FW, int TW, int NW, int BKT, int DST, int EPI>
+static hipError_t launch_gemm_stream_t(const GemmArgs &a, dim3 grid, hipStream_t s) {
+    constexpr int smem = (DST + 1) * TW * BKT * 1024;
+    static bool attr_done = false;
+    auto kern = gemm_stream_kernel<FW, TW, NW, BKT, DST, EPI>;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), smem, s, a);
+    return hipGetLastError();
+}
+
 template <int EPI>
 static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipStream_t s) {
     switch (variant) {
-        case GV_P128_BK32: return launch_gemm_t<4, 4, 2, 2, 2, 4, EPI>(a, grid, s);
-        case GV_P128_BK64: return launch_gemm_t<4, 4, 2, 2, 4, 4, EPI>(a, grid, s);
-        case GV_D128: return launch_gemm_t<4, 2, 2, 2, 4, 4, EPI>(a, grid, s);
-        case GV_D64: return launch_gemm_t<2, 2, 1, 2, 4, 4, EPI>(a, grid, s);
-        default: return launch_gemm_t<8, 1, 4, 1, 4, 3, EPI>(a, grid, s);
+        case GV_P128: return launch_gemm_t<4, 4, 2, 2, 2, 4, EPI>(a, grid, s);
+        case GV_S64: return launch_gemm_stream_t<1, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
+        case GV_S32: return launch_gemm_stream_t<1, 1, 4, 4, kStreamDepth, EPI>(a, grid, s);
+        case GV_R64: return launch_gemm_t<4, 2, 2, 2, 4, 4, EPI, false>(a, grid, s);
+        default: return launch_gemm_t<4, 1, 4, 1, 4, 4, EPI, false>(a, grid, s);
     }
 }
 
@@ -220,6 +242,7 @@ struct PhaseRun {
     int phase;  // NEXUS_PHASE_*
     hipStream_t s;
     int n_xcd;
+    int cus;  // CUs the phase's stream may run on
     int T;
     const nexus_prefill_batch *pb;
     const nexus_decode_batch *db;
@@ -248,7 +271,10 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
         return fail(NEXUS_ESTATE, "split-K workspace too small (%d x %d x %d)", p.S, r.T, N_packed);
     {
         Tracer tr(c, r.phase, kernel_id, r.s);
-        HIP_TRY(launch_gemm(p.variant, p.S > 1 ? (int)EPI_PARTIAL : epi, a, grid, r.s));
+        int variant = p.variant;
+        const int last_ksteps = Kp / kGemmBK - (p.S - 1) * p.ksteps_per_split;  // the shortest k range of the grid
+        if (last_ksteps < kStreamDepth) variant = variant == GV_S64 ? GV_R64 : variant == GV_S32 ? GV_R32 : variant;
+        HIP_TRY(launch_gemm(variant, p.S > 1 ? (int)EPI_PARTIAL : epi, a, grid, r.s));
     }
     if (p.S > 1) {
         ReduceArgs ra{};
@@ -772,6 +798,8 @@ static PhaseRun make_run(nexus_ctx *c, int phase, const nexus_prefill_batch *pb,
     r.c = c, r.phase = phase, r.pb = pb, r.db = db, r.kv = kv;
     r.s = phase == NEXUS_PHASE_PREFILL ? c->cur->sp : c->cur->sd;
     r.n_xcd = phase == NEXUS_PHASE_PREFILL ? c->cur->p_xcd : c->cur->d_xcd;
+    r.cus = phase == NEXUS_PHASE_PREFILL ? c->cur->p_cus : c->cur->d_cus;
+    if (r.cus <= 0) r.cus = c->n_cus;
     r.T = phase == NEXUS_PHASE_PREFILL ? pb->n_tokens : db->n_reqs;
     return r;
 }
