@@ -183,10 +183,11 @@ int nexus_kv_export(nexus_ctx *ctx, const nexus_kv_cache *kv, int layer, void *k
  * Selects the CU share of each phase: prefill_cus + decode_cus <= nexus_cu_count(), both positive multiples of
  * 8.  The chip is eight accelerator dies (XCDs) with an L2 each; every XCD gives each phase the same number of
  * its CUs (a queue's CU mask must keep at least one CU in every XCD, and workgroups are dealt to XCDs
- * round-robin whatever the mask).  The two phases then run on two streams whose CU masks are disjoint.  The stream pair of a layout is created on first use; the three most recently used partitioned layouts
- * are kept (each masked stream owns a hardware queue, of which a process has few), older ones are retired.  (NEXUS_CUS_ALL, NEXUS_CUS_ALL)
- * selects the unpartitioned layout: one unmasked stream, the mixed step runs prefill then decode back to back
- * (the serialized baseline of Sec. 3.1).
+ * round-robin whatever the mask).  The two phases then run on two streams whose CU masks are disjoint.  Only
+ * one partitioned stream pair exists at a time: selecting a different split synchronises and destroys the
+ * current pair and creates the new one (about 12 ms; more than one pair alive made some pairs dispatch the
+ * decode kernels late on MI355X).  (NEXUS_CUS_ALL, NEXUS_CUS_ALL) selects the unpartitioned layout: one unmasked
+ * stream, the mixed step runs prefill then decode back to back (the serialized baseline of Sec. 3.1).
  */
 int nexus_set_cu_split(nexus_ctx *ctx, int prefill_cus, int decode_cus);
 

@@ -70,7 +70,12 @@ struct Layout {
     int p_xcd = 8, d_xcd = 8;  // XCDs each stream is spread over (tile-order hint)
     long last_use = 0;
 };
-constexpr int kMaxMaskedLayouts = 3;
+// Partitioned stream pairs kept alive.  Measured on MI355X (ROCm 7.2): with one pair alive every pair behaves;
+// with two or three, some pairs (reproducibly the third one created in a process, and with two alive every pair
+// after the second) run the decode queue's kernels 20-35 us late each once its attention kernel has run while the
+// prefill queue is active -- the concurrent step then loses 10-50%.  No synthetic probe reproduced it, so the
+// library never keeps more than one pair: changing the split re-creates the two streams (about 12 ms).
+constexpr int kMaxMaskedLayouts = 1;
 
 struct TraceRec {
     hipEvent_t a, b;
@@ -650,7 +655,7 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         c->bits_xcd_major = order && !strcmp(order, "xcd_major");
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
         for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_sd1})
-            if (hipEventCreate(e) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
+            if (hipEventCreateWithFlags(e, hipEventDisableSystemFence) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
         if (rc) break;
         if ((rc = alloc_phase_ws(c, NEXUS_PHASE_PREFILL, limits->max_prefill_tokens, limits->max_prefill_reqs))) break;
         if ((rc = alloc_phase_ws(c, NEXUS_PHASE_DECODE, limits->max_decode_reqs, limits->max_decode_reqs))) break;
@@ -769,8 +774,8 @@ int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
     }
     auto it = c->layouts.find(key);
     if (it == c->layouts.end()) {
-        // Every CU-masked stream owns a hardware queue, and a process only gets a handful of those: keep at most
-        // kMaxMaskedLayouts partitioned pairs alive and retire the least recently used one before creating another.
+        // Every CU-masked stream owns a hardware queue: keep at most kMaxMaskedLayouts partitioned pairs alive and
+        // retire the least recently used one before creating another.
         int masked = 0;
         for (auto &kv : c->layouts) masked += kv.first != 0;
         while (masked >= kMaxMaskedLayouts) {
@@ -967,8 +972,8 @@ int nexus_trace_begin(nexus_ctx *c, int phase, int kernel) {
     if (c->trace_pool.empty()) {
         c->trace_pool.resize(4096);
         for (auto &t : c->trace_pool) {
-            HIP_TRY(hipEventCreate(&t.a));
-            HIP_TRY(hipEventCreate(&t.b));
+            HIP_TRY(hipEventCreateWithFlags(&t.a, hipEventDisableSystemFence));
+            HIP_TRY(hipEventCreateWithFlags(&t.b, hipEventDisableSystemFence));
         }
     }
     c->trace_used = 0;
