@@ -202,8 +202,11 @@ int nexus_decode_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexu
 /*
  * Both phases of one step.  With a partitioned layout they are enqueued on the two CU-masked streams after a
  * common fork event and run concurrently; with the unpartitioned layout they run back to back.  The two
- * sub-batches must touch disjoint requests and pages.  caller_stream (a hipStream_t, may be NULL) is made to
- * precede the fork and to wait for both phases.  timing may be NULL; when given the call blocks until done.
+ * sub-batches must touch disjoint requests and pages.  Steps of one context never overlap: each phase starts
+ * after both phases of the previous nexus_mixed_step.  caller_stream (a hipStream_t) is made to precede the fork
+ * and to wait for both phases; with NULL the step is ordered after the context's previous work only, and the
+ * caller synchronises with nexus_sync (inputs must be complete when the call is made).  timing may be NULL; when
+ * given the call blocks until done.
  */
 int nexus_mixed_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_prefill_batch *pb,
                      const nexus_decode_batch *db, const nexus_kv_cache *kv, void *caller_stream,

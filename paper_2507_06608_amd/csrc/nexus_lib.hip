@@ -841,6 +841,10 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
         if (split) HIP_TRY(hipStreamWaitEvent(L->sd, c->ev_caller, 0));
     }
     if (split) {
+        // steps of one context never overlap: this step's prefill phase follows the previous step's decode phase
+        // (a no-op before the first step), and through the fork below so does its decode phase the previous
+        // prefill phase.  A request that finished prefilling in step n can therefore decode in step n + 1.
+        HIP_TRY(hipStreamWaitEvent(L->sp, c->ev_sd1, 0));
         // fork: the decode stream starts when the prefill stream reaches this point
         HIP_TRY(hipEventRecord(c->ev_fork, L->sp));
         HIP_TRY(hipStreamWaitEvent(L->sd, c->ev_fork, 0));
@@ -852,7 +856,7 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
     NX_TRY(run_phase(make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le));
     if (timing) HIP_TRY(hipEventRecord(c->ev_sp1, L->sp));
     NX_TRY(run_phase(make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le));
-    if (timing || (cs && split)) HIP_TRY(hipEventRecord(c->ev_sd1, L->sd));
+    if (timing || split) HIP_TRY(hipEventRecord(c->ev_sd1, L->sd));
     if (cs) {
         if (split) {
             if (!timing) HIP_TRY(hipEventRecord(c->ev_sp1, L->sp));
