@@ -85,6 +85,7 @@ struct nexus_ctx {
     nexus_model_desc m{};
     nexus_limits lim{};
     int device = 0, n_cus = 0, n_xcd = 8, cus_per_xcd = 32;
+    bool allow_p256 = true;
     int q_dim = 0, kv_dim = 0, n_qkv = 0;
     std::vector<LayerW> layers;
     PhaseWs ws[2];
@@ -132,6 +133,8 @@ static int dev_alloc(T **p, size_t elems, bool zero) {
 // the chip is bound by per-CU bytes in flight, not by the HBM interface.
 enum GemmVariant {
     GV_P128 = 0,  // gemm_dl_kernel, 128 x 128, 4 waves, 32-wide stages, 64 KiB ring: two workgroups per CU
+    GV_P256,      // gemm_dl_kernel, 256 x 256, 8 waves, 128 KiB ring: half the LDS and L2 traffic per flop, for GEMMs
+                  //   with several such tiles per CU of the share (same per-element summation order as GV_P128)
     GV_S64,       // gemm_stream_kernel, 128 features x 64 tokens, 4 waves: decode batches of 33..64
     GV_S32,       // gemm_stream_kernel, 128 features x 32 tokens, 4 waves: decode batches of at most 32
     GV_R64,       // gemm_dl_kernel with the extent of GV_S64 / GV_S32: k ranges shorter than the streaming
@@ -206,6 +209,7 @@ template <int EPI>
 static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipStream_t s) {
     switch (variant) {
         case GV_P128: return launch_gemm_t<4, 4, 2, 2, 2, 4, EPI>(a, grid, s);
+        case GV_P256: return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI>(a, grid, s);
         case GV_S64: return launch_gemm_stream_t<1, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S32: return launch_gemm_stream_t<1, 1, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_R64: return launch_gemm_t<4, 2, 2, 2, 4, 4, EPI, false>(a, grid, s);
@@ -268,17 +272,29 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
     a.out = out, a.res = res, a.bias = bias, a.ld_out = ld_out;
     a.out_p32 = out_p32, a.out_Kp = out_p32 ? p32_kp(out_K) : 0;
     a.partial = ws.partial;
-    a.n_tblk = (a.n_ttiles + p.TS - 1) / p.TS;
+    // Ring geometry and tile extent may follow the CU share (they do not change any element's summation order; the
+    // split factor S, which does, is problem-only).  256 x 256 tiles do about 15% more flops per CU-second than
+    // 128 x 128 (half the LDS and L2 traffic per flop) but quantise worse: one per CU against two.  Measured at
+    // K = 4096 on MI355X: a round of 256-tiles takes 127 us, a round of 128-tiles (two per CU) 75 us; the estimate
+    // below reproduced the measured times of all four projection GEMMs at 512 and 8192 tokens within 5%.
+    int variant = p.variant, FS = p.FS, TS = p.TS;
+    if (variant == GV_P128 && p.S == 1 && c->allow_p256) {
+        const long n128 = (long)((a.n_ttiles + 3) / 4) * ((n_ftiles + 3) / 4);
+        const long n256 = (long)((a.n_ttiles + 7) / 8) * ((n_ftiles + 7) / 8);
+        const long est128 = (n128 + 2 * r.cus - 1) / (2 * r.cus) * 75;
+        const long est256 = (n256 + r.cus - 1) / r.cus * 127;
+        if (est256 < est128) variant = GV_P256, FS = 8, TS = 8;
+    }
+    const int last_ksteps = Kp / kGemmBK - (p.S - 1) * p.ksteps_per_split;  // the shortest k range of the grid
+    if (last_ksteps < kStreamDepth) variant = variant == GV_S64 ? GV_R64 : variant == GV_S32 ? GV_R32 : variant;
+    a.n_tblk = (a.n_ttiles + TS - 1) / TS;
     a.n_xcd = r.n_xcd;
-    const int n_fblk = (n_ftiles + p.FS - 1) / p.FS;
+    const int n_fblk = (n_ftiles + FS - 1) / FS;
     dim3 grid(a.n_tblk * n_fblk, 1, p.S);
     if (p.S > 1 && (size_t)p.S * r.T * N_packed > ws.partial_elems)
         return fail(NEXUS_ESTATE, "split-K workspace too small (%d x %d x %d)", p.S, r.T, N_packed);
     {
         Tracer tr(c, r.phase, kernel_id, r.s);
-        int variant = p.variant;
-        const int last_ksteps = Kp / kGemmBK - (p.S - 1) * p.ksteps_per_split;  // the shortest k range of the grid
-        if (last_ksteps < kStreamDepth) variant = variant == GV_S64 ? GV_R64 : variant == GV_S32 ? GV_R32 : variant;
         HIP_TRY(launch_gemm(variant, p.S > 1 ? (int)EPI_PARTIAL : epi, a, grid, r.s));
     }
     if (p.S > 1) {
@@ -653,6 +669,9 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         c->cus_per_xcd = c->n_cus / c->n_xcd;
         const char *order = getenv("NEXUS_CU_BIT_ORDER");
         c->bits_xcd_major = order && !strcmp(order, "xcd_major");
+        // test hook: the 256 x 256 GEMM tiles can be switched off to compare them bit for bit with the 128 x 128 ones
+        const char *tiles = getenv("NEXUS_GEMM_TILES");
+        c->allow_p256 = !(tiles && !strcmp(tiles, "128"));
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
         for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_sd1})
             if (hipEventCreateWithFlags(e, hipEventDisableSystemFence) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }

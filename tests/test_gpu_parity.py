@@ -307,3 +307,66 @@ def test_cfg2_full_size_sampled_outputs_in_bench_launch_configuration(nx, oracle
             assert_close(f"K {name} pos {pos}", f32(kg[full_page, :, pos % ps]), ref["k_pool"][sp_page, :, pos % ps])
             assert_close(f"V {name} pos {pos}", f32(vg[full_page, :, pos % ps]), ref["v_pool"][sp_page, :, pos % ps])
     ctx.close()
+
+
+def test_cfg3_heavy_mix_full_size_sampled(nx, oracle, monkeypatch):
+    """The heavy mix at full size (4 x 2048-token chunks over prefixes up to 6144, 256 decode requests with contexts
+    up to 8192; one layer).  Long chunks take the 256 x 256 GEMM tiles and the decode batch of 256 takes the tiled
+    GEMM instead of the streaming one.  The oracle evaluates the first 16 rows of every chunk (rows 0, 2048, 4096,
+    6144 of the batch: four different token blocks, four prefix lengths) and five decode requests; every other
+    output row is covered by a property that holds at any size: the step computed with 128 x 128 tiles only (same
+    per-element summation order, different kernels) and the serialized step must both reproduce it bit for bit."""
+    _announce("cfg3 full size, sampled")
+    wl = synth.config(3, seed=0, kv_device="cuda:0")
+    w = synth.make_weights(wl.shape, 0)
+    pb_host, d = wl.prefill, wl.decode
+
+    def run(split, tiles):
+        if tiles:
+            monkeypatch.setenv("NEXUS_GEMM_TILES", tiles)
+        else:
+            monkeypatch.delenv("NEXUS_GEMM_TILES", raising=False)
+        ctx = nx.context_for(wl)
+        ctx.load_layer(0, w)
+        kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+        pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+        ctx.set_cu_split(*split)
+        ctx.mixed_step(pb, db, kv)
+        ctx.sync()
+        out = (pb.y.clone(), db.y.clone(), ctx.kv_export(kv))
+        ctx.close()
+        return out
+
+    yp, yd, kv_after = run((224, 32), None)
+    assert torch.isfinite(yp.float()).all() and torch.isfinite(yd.float()).all()
+    for split, tiles in (((nx.CUS_ALL, nx.CUS_ALL), None), ((192, 64), "128")):
+        yp2, yd2, kv2 = run(split, tiles)
+        assert torch.equal(yp2.view(torch.int16), yp.view(torch.int16)), (split, tiles)
+        assert torch.equal(yd2.view(torch.int16), yd.view(torch.int16)), (split, tiles)
+        for a, b in zip(kv2, kv_after):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (split, tiles)
+        del yp2, yd2, kv2
+
+    n_pre = 16
+    order = np.argsort(d.ctx_len)
+    dec_sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 3, 200})
+    sub = synth.subset_for_oracle(wl, list(range(pb_host.n_reqs)), dec_sample)
+    sp = sub.prefill
+    rows = np.concatenate([np.arange(int(sp.cu_chunk[r]), int(sp.cu_chunk[r]) + n_pre) for r in range(sp.n_reqs)])
+    sub.prefill = synth.PrefillBatch(sp.x[torch.as_tensor(rows)], np.arange(sp.n_reqs + 1, dtype=np.int32) * n_pre, sp.prefix_len, sp.page_table)
+    ref = run_oracle(oracle, sub, w)
+    full_rows = np.concatenate([np.arange(int(pb_host.cu_chunk[r]), int(pb_host.cu_chunk[r]) + n_pre) for r in range(pb_host.n_reqs)])
+    assert_close("cfg3 prefill sampled rows", f32(yp[torch.as_tensor(full_rows, device=yp.device)]), ref["y_p"])
+    assert_close("cfg3 decode sample", f32(yd[dec_sample]), ref["y_d"])
+    pages = sub.notes["pages"]
+    ps = wl.shape.page_size
+    kg, vg = kv_after
+    checks = [(f"prefill {r}", sub.prefill.page_table[r], range(int(sp.prefix_len[r]), int(sp.prefix_len[r]) + n_pre))
+              for r in range(sp.n_reqs)]
+    checks += [(f"decode {j}", sub.decode.page_table[i], [int(sub.decode.ctx_len[i])]) for i, j in enumerate(dec_sample)]
+    for name, req_row, positions in checks:
+        for pos in positions:
+            sp_page = int(req_row[pos // ps])
+            full_page = pages[sp_page]
+            assert_close(f"K {name} pos {pos}", f32(kg[full_page, :, pos % ps]), ref["k_pool"][sp_page, :, pos % ps])
+            assert_close(f"V {name} pos {pos}", f32(vg[full_page, :, pos % ps]), ref["v_pool"][sp_page, :, pos % ps])
