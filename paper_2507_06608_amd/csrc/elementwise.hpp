@@ -6,11 +6,20 @@
 namespace nexus {
 
 // ---- RMSNorm: h = x * rsqrt(mean(x^2) + eps) * g, one workgroup per token, fp32 statistics -----------------
-// Input row-major [T][d], bf16 (the layer input) or fp32 (the residual stream after attention); output half, in
-// P32 tile order (operand of the following GEMM).
-template <int MAXC, bool IN_F32>  // 8-element chunks per thread, d <= MAXC * 256 * 8
+// Input row-major [T][d]: bf16 (the layer input), fp32 (the residual stream after attention), or -- fused with the
+// end of a split-K output projection -- the S fp32 partial slices of that GEMM plus the bf16 residual, in which
+// case the kernel also writes the residual stream x1 = residual + sum of slices (slices added in order, then the
+// residual, exactly as splitk_reduce_kernel does).  Output half, in P32 tile order (operand of the next GEMM).
+enum RmsIn { RMS_IN_BF16 = 0, RMS_IN_F32 = 1, RMS_IN_PARTIAL = 2 };
+struct RmsPartial {
+    const float *partial;  // [S][T][d]
+    int S, T;
+    const bf16_t *res;     // [T][d]
+    float *x1_out;         // [T][d]
+};
+template <int MAXC, int IN>  // 8-element chunks per thread, d <= MAXC * 256 * 8
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x, const bf16_t *__restrict__ g,
-                                                      f16_t *__restrict__ out_p32, int d, int Kp, float eps) {
+                                                      f16_t *__restrict__ out_p32, int d, int Kp, float eps, RmsPartial pp) {
     __shared__ float red[4];
     const int t = blockIdx.x, tid = threadIdx.x;
     const int nchunk = d >> 3;
@@ -20,11 +29,30 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x
     for (int c = 0; c < MAXC; ++c) {
         const int ci = tid + c * 256;
         if (ci < nchunk) {
-            if (IN_F32) {
+            if (IN == RMS_IN_F32) {
                 const float4 *row = (const float4 *)((const float *)x + (size_t)t * d);
                 float4 a0 = row[2 * ci], a1 = row[2 * ci + 1];
                 v[c][0] = a0.x, v[c][1] = a0.y, v[c][2] = a0.z, v[c][3] = a0.w;
                 v[c][4] = a1.x, v[c][5] = a1.y, v[c][6] = a1.z, v[c][7] = a1.w;
+            } else if (IN == RMS_IN_PARTIAL) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
+                for (int s = 0; s < pp.S; ++s) {
+                    const float4 *row = (const float4 *)(pp.partial + ((size_t)s * pp.T + t) * d);
+                    float4 a0 = row[2 * ci], a1 = row[2 * ci + 1];
+                    v[c][0] += a0.x, v[c][1] += a0.y, v[c][2] += a0.z, v[c][3] += a0.w;
+                    v[c][4] += a1.x, v[c][5] += a1.y, v[c][6] += a1.z, v[c][7] += a1.w;
+                }
+                uint4 u = ((const uint4 *)(pp.res + (size_t)t * d))[ci];
+                uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[c][2 * e] += bf2f(wds[e] & 0xffff);
+                    v[c][2 * e + 1] += bf2f(wds[e] >> 16);
+                }
+                float4 *orow = (float4 *)(pp.x1_out + (size_t)t * d);
+                orow[2 * ci] = make_float4(v[c][0], v[c][1], v[c][2], v[c][3]);
+                orow[2 * ci + 1] = make_float4(v[c][4], v[c][5], v[c][6], v[c][7]);
             } else {
                 const uint4 *row = (const uint4 *)((const bf16_t *)x + (size_t)t * d);
                 uint4 u = row[ci];
@@ -87,6 +115,11 @@ struct RopeArgs {
     bf16_t *k_pool, *v_pool;
     int n_pages;
     bf16_t *q_out;  // prefill: P32 with request-aligned 32-row tiles; decode: row-major [T][Hq*hd]
+    // When the QKV projection was split along K, its S fp32 partial slices [S][T][Hq*hd + 2*Hkv*hd] (+ bias) are
+    // summed here instead of by a reduce kernel; the sum is rounded to half first, as that kernel would have.
+    const float *partial;
+    int S;
+    const bf16_t *bias;
 };
 
 template <bool PREFILL>
@@ -118,19 +151,43 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
     const int ptab = pos < a.n_pos ? pos : a.n_pos - 1;
     const float2 *tab = a.rope_tab + (size_t)ptab * half;
 
+    const int width = qd + 2 * kvd;
+    auto load8 = [&](int col, float (&o)[8]) {
+        if (a.partial) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = 0.f;
+            for (int s = 0; s < a.S; ++s) {
+                const float4 *p = (const float4 *)(a.partial + ((size_t)s * a.T + t) * width + col);
+                const float4 a0 = p[0], a1 = p[1];
+                o[0] += a0.x, o[1] += a0.y, o[2] += a0.z, o[3] += a0.w;
+                o[4] += a1.x, o[5] += a1.y, o[6] += a1.z, o[7] += a1.w;
+            }
+            if (a.bias) {
+                const uint4 b = *(const uint4 *)(a.bias + col);
+                const uint32_t bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] += bf2f((bw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = h2f(f2h(o[e]));
+        } else {
+            const uint4 u = *(const uint4 *)(row + col);
+            const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = h2f((f16_t)((w[e >> 1] >> ((e & 1) * 16)) & 0xffff));
+        }
+    };
     const int rope_units = (a.Hq + a.Hkv) * cph;
     const int v_units = a.Hkv * (hd >> 3);
     for (int u = threadIdx.x; u < rope_units + v_units; u += 256) {
         if (u < rope_units) {
             const int h = u / cph, c = u % cph;  // head (q heads first, then k heads), pair chunk
-            const f16_t *src = row + (size_t)h * hd + c * 8;
-            uint4 lo = *(const uint4 *)src, hi = *(const uint4 *)(src + half);
-            uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
-            float ol[8], oh[8];
+            float xl[8], xh[8], ol[8], oh[8];
+            load8(h * hd + c * 8, xl);
+            load8(h * hd + half + c * 8, xh);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float x0 = h2f((f16_t)((lw[e >> 1] >> ((e & 1) * 16)) & 0xffff));
-                const float x1 = h2f((f16_t)((hw[e >> 1] >> ((e & 1) * 16)) & 0xffff));
+                const float x0 = xl[e], x1 = xh[e];
                 const float2 cs = tab[c * 8 + e];
                 ol[e] = x0 * cs.x - x1 * cs.y;
                 oh[e] = x1 * cs.x + x0 * cs.y;
@@ -154,12 +211,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
         } else if (page_ok) {
             const int vu = u - rope_units;
             const int kvh = vu / (hd >> 3), c = vu % (hd >> 3);
-            uint4 vv = *(const uint4 *)(row + qd + kvd + (size_t)kvh * hd + c * 8);
-            uint32_t vw[4] = {vv.x, vv.y, vv.z, vv.w};
+            float vv[8];
+            load8(qd + kvd + kvh * hd + c * 8, vv);
             bf16_t *blk = a.v_pool + ((size_t)page * a.Hkv + kvh) * (kPage * hd);
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                blk[vblk_offset(slot, c * 8 + e, hd)] = f2bf(h2f((f16_t)((vw[e >> 1] >> ((e & 1) * 16)) & 0xffff)));
+            for (int e = 0; e < 8; ++e) blk[vblk_offset(slot, c * 8 + e, hd)] = f2bf(vv[e]);
         }
     }
 }

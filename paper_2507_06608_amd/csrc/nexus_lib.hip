@@ -258,8 +258,11 @@ struct PhaseRun {
     const nexus_kv_cache *kv;
 };
 
+// deferred_S (may be null): when given and the GEMM is split along K, the partial slices are left in the workspace
+// for the caller's next kernel to sum (see run_rmsnorm_partial) and *deferred_S receives their number, else 0.
 static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_packed, const f16_t *X, int K, int epi,
-                    void *out, const void *res, const bf16_t *bias, int ld_out, f16_t *out_p32, int out_K) {
+                    void *out, const void *res, const bf16_t *bias, int ld_out, f16_t *out_p32, int out_K,
+                    int *deferred_S = nullptr) {
     nexus_ctx *c = r.c;
     PhaseWs &ws = c->ws[r.phase];
     const int Kp = p32_kp(K);
@@ -297,7 +300,8 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
         Tracer tr(c, r.phase, kernel_id, r.s);
         HIP_TRY(launch_gemm(variant, p.S > 1 ? (int)EPI_PARTIAL : epi, a, grid, r.s));
     }
-    if (p.S > 1) {
+    if (deferred_S) *deferred_S = p.S > 1 ? p.S : 0;
+    if (p.S > 1 && !deferred_S) {
         ReduceArgs ra{};
         ra.partial = ws.partial, ra.S = p.S, ra.T = r.T, ra.N = N_packed;
         ra.out = out, ra.res = res, ra.bias = bias, ra.ld_out = ld_out, ra.out_p32 = out_p32, ra.out_Kp = a.out_Kp;
@@ -313,14 +317,14 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
     return NEXUS_OK;
 }
 
-template <bool IN_F32>
-static int run_rmsnorm(const PhaseRun &r, const void *x, const bf16_t *g, f16_t *out_p32) {
+template <int IN>
+static int run_rmsnorm(const PhaseRun &r, const void *x, const bf16_t *g, f16_t *out_p32, RmsPartial pp = RmsPartial{}) {
     nexus_ctx *c = r.c;
     const int d = c->m.hidden;
     Tracer tr(c, r.phase, NEXUS_K_RMSNORM, r.s);
-    if (d <= 2048) hipLaunchKernelGGL((rmsnorm_kernel<1, IN_F32>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
-    else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_kernel<2, IN_F32>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
-    else hipLaunchKernelGGL((rmsnorm_kernel<4, IN_F32>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps);
+    if (d <= 2048) hipLaunchKernelGGL((rmsnorm_kernel<1, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps, pp);
+    else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_kernel<2, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps, pp);
+    else hipLaunchKernelGGL((rmsnorm_kernel<4, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps, pp);
     HIP_TRY(hipGetLastError());
     return NEXUS_OK;
 }
@@ -415,11 +419,13 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
     bf16_t *k_pool = (bf16_t *)((char *)r.kv->k_pool + (size_t)layer * r.kv->layer_stride_bytes);
     bf16_t *v_pool = (bf16_t *)((char *)r.kv->v_pool + (size_t)layer * r.kv->layer_stride_bytes);
 
-    NX_TRY(run_rmsnorm<false>(r, x_in, L.g1, ws.h));
+    NX_TRY(run_rmsnorm<RMS_IN_BF16>(r, x_in, L.g1, ws.h));
+    int qkv_slices = 0;  // a split-K QKV projection is summed by the rotary kernel
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_QKV, L.wqkv, c->n_qkv, ws.h, m.hidden, EPI_ROWMAJOR, ws.qkv, nullptr, L.bqkv, c->n_qkv,
-                    nullptr, 0));
+                    nullptr, 0, &qkv_slices));
     {
         RopeArgs a{};
+        a.partial = qkv_slices ? ws.partial : nullptr, a.S = qkv_slices, a.bias = L.bqkv;
         a.qkv = ws.qkv, a.T = r.T, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads, a.hd = m.head_dim;
         a.rope_tab = c->rope_tab, a.n_pos = c->lim.max_positions;
         a.cu_chunk = prefill ? r.pb->cu_chunk : nullptr;
@@ -451,9 +457,17 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
         a.scale_log2e = scale_log2e, a.part_o = ws.part_o, a.part_ml = ws.part_ml, a.out = ws.attn;
         NX_TRY(m.head_dim == 128 ? launch_attn_decode<128>(r, a) : launch_attn_decode<64>(r, a));
     }
+    // x1 = x + attn W_o^T, h2 = RMSNorm(x1): when the projection is split along K its reduction, the residual add
+    // and the norm are one kernel
+    int o_slices = 0;
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_O, L.wo, m.hidden, ws.attn, c->q_dim, EPI_RES_IN, ws.x1, x_in, nullptr, m.hidden,
-                    nullptr, 0));
-    NX_TRY(run_rmsnorm<true>(r, ws.x1, L.g2, ws.h));
+                    nullptr, 0, &o_slices));
+    if (o_slices) {
+        RmsPartial pp{ws.partial, o_slices, r.T, (const bf16_t *)x_in, ws.x1};
+        NX_TRY(run_rmsnorm<RMS_IN_PARTIAL>(r, nullptr, L.g2, ws.h, pp));
+    } else {
+        NX_TRY(run_rmsnorm<RMS_IN_F32>(r, ws.x1, L.g2, ws.h));
+    }
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_GATE_UP, L.wgu, 2 * m.ffn, ws.h, m.hidden, EPI_SWIGLU, nullptr, nullptr, nullptr, 0,
                     ws.act, m.ffn));
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_DOWN, L.wdown, m.hidden, ws.act, m.ffn, EPI_RES_OUT, y_out, ws.x1, nullptr, m.hidden,
