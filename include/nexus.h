@@ -231,6 +231,75 @@ int nexus_profile_split(nexus_ctx *ctx, int layer_begin, int layer_end, const ne
 int nexus_choose_split(int n_cand, const float *t_prefill_ms, const float *t_decode_ms, const float *t_step_ms,
                        float t_prefill_all_ms, float t_decode_all_ms, int policy, float alpha, float beta);
 
+/* ---- partition controller: cost model, objectives, greedy search, buffer zone (host only, no GPU work) ------ */
+
+/*
+ * One operator of a phase for the latency model of Sec. 4.1.1: its compute time on a share r of the GPU is
+ * flops / (r C) up to the saturation share r_sat and flops / (r_sat C) * (1 + lambda (r - r_sat)) beyond it
+ * (Eq. 7); its memory time is bytes / B.  kind tells the contention model which traffic is attention (Eq. 8-9).
+ */
+typedef enum { NEXUS_OP_DENSE = 0, NEXUS_OP_ATTENTION = 1 } nexus_op_kind;
+typedef struct {
+    double flops, bytes; /* per iteration of the phase (all layers) */
+    double r_sat;        /* in (0, 1] */
+    double lambda;
+    int32_t kind;        /* nexus_op_kind */
+    int32_t reserved;
+} nexus_cost_op;
+typedef struct {
+    double peak_flops;       /* C */
+    double peak_bytes_per_s; /* B */
+    int32_t n_prefill_ops, n_decode_ops;
+    const nexus_cost_op *prefill_ops, *decode_ops; /* host arrays, caller-owned */
+} nexus_cost_model;
+
+/*
+ * CostModel(phase, R) of Alg. 1: latency in seconds of `phase` on `share` of `total` equal steps of the GPU while
+ * the other phase holds the rest; a phase is the sum over its operators of max(compute time, memory time)
+ * (Eq. 5-6).  Decode attention moves its bytes at the bandwidth left by prefill: with P_attn the fraction of
+ * prefill's time spent in attention (Eq. 8), decode gets m_d / (m_d + m_p1) of B during it and m_d / (m_d + m_p2)
+ * otherwise (m_d, m_p1, m_p2: bytes of decode attention, prefill attention, prefill dense operators), Eq. 9.
+ * share == total means the phase is alone (no contention).  1 <= share <= total, else NEXUS_EINVAL.
+ */
+int nexus_cost_latency(const nexus_cost_model *model, int phase, int share, int total, double *seconds);
+
+/*
+ * AdjustPartition of Alg. 1 for the prioritised `target_phase`: starting from the current split, the target gives
+ * up steps until the other phase's modelled latency is within its budget (alpha x prefill's, beta x decode's
+ * latency alone on the whole GPU, Sec. 4.1.2), then takes steps back while the budget still holds.  Both phases
+ * keep at least one step.  Outputs: the new prefill share and (if non-null) the number of model evaluations.
+ */
+int nexus_adjust_partition(const nexus_cost_model *model, int target_phase, int cur_prefill_share, int total,
+                           double alpha, double beta, int32_t *new_prefill_share, int32_t *evaluations);
+
+/*
+ * PartitionController of Alg. 1: decode is prioritised when kv_usage > kv_switch, prefill otherwise (Sec. 4.1.2,
+ * runtime switching); a change of fewer than `delta` steps is suppressed (the buffer zone of Sec. 4.2).
+ */
+int nexus_partition_controller(const nexus_cost_model *model, double kv_usage, double kv_switch,
+                               int cur_prefill_share, int total, double alpha, double beta, int delta,
+                               int32_t *new_prefill_share);
+
+/*
+ * Extracts an operator's curve parameters from n measured (share in (0, 1], seconds) points (Sec. 4.1.1: R_sat
+ * and lambda come from measurements under varying allocations; the paper does not say how): each measured share
+ * is tried as R_sat, the effective work is the mean of t r C at or below it, lambda the least-squares slope of
+ * t / t_sat - 1 above it; the candidate with the smallest squared relative error is returned.  n >= 1.
+ */
+int nexus_cost_fit(int n, const double *shares, const double *seconds, double peak_flops, double *flops,
+                   double *r_sat, double *lambda);
+
+/*
+ * Algorithmic flops and bytes of the five operators of each phase (order: QKV, attention, O, gate/up, down) for
+ * `layers` layers of `desc`, from the quantities the controller sees (Fig. 6): prefill_tokens = P_T and the
+ * (query, visible key) pairs of its attention, prefill_kv_tokens = KV_p (tokens whose K/V the chunk reads),
+ * decode_reqs = B_d, decode_kv_tokens = KV_d.  Dense operators move their weights once, attention the K/V it
+ * reads.  r_sat is set to 1 and lambda to 0; nexus_cost_fit refines them.  Both arrays have 5 entries.
+ */
+int nexus_cost_describe(const nexus_model_desc *desc, int layers, double prefill_tokens, double prefill_pairs,
+                        double prefill_kv_tokens, double decode_reqs, double decode_kv_tokens,
+                        nexus_cost_op *prefill_ops, nexus_cost_op *decode_ops);
+
 /* ---- measurement and test hooks ----------------------------------------------------------------------------- */
 
 /* Kernel ids for nexus_trace_*: one per kernel family on the path. */

@@ -30,7 +30,8 @@ EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "n
            "nexus_kv_import", "nexus_kv_export", "nexus_set_cu_split",
            "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_profile_split",
            "nexus_choose_split", "nexus_trace_begin", "nexus_trace_read", "nexus_debug_fetch",
-           "nexus_debug_cu_probe")
+           "nexus_debug_cu_probe", "nexus_cost_latency", "nexus_adjust_partition", "nexus_partition_controller",
+           "nexus_cost_fit", "nexus_cost_describe")
 
 
 class NexusError(RuntimeError):
@@ -67,6 +68,16 @@ class PrefillBatchC(C.Structure):
 class DecodeBatchC(C.Structure):
     _fields_ = [("n_reqs", C.c_int32), ("x", C.c_void_p), ("y", C.c_void_p), ("ctx_len", C.c_void_p),
                 ("page_table", C.c_void_p), ("max_pages", C.c_int32), ("max_ctx", C.c_int32)]
+
+
+class CostOp(C.Structure):
+    _fields_ = [("flops", C.c_double), ("bytes", C.c_double), ("r_sat", C.c_double), ("lam", C.c_double),
+                ("kind", C.c_int32), ("reserved", C.c_int32)]
+
+
+class CostModelC(C.Structure):
+    _fields_ = [("peak_flops", C.c_double), ("peak_bytes_per_s", C.c_double), ("n_prefill_ops", C.c_int32),
+                ("n_decode_ops", C.c_int32), ("prefill_ops", C.POINTER(CostOp)), ("decode_ops", C.POINTER(CostOp))]
 
 
 class StepTiming(C.Structure):
@@ -259,6 +270,58 @@ class Nexus:
         out = np.zeros(8 * 128, np.int32)
         _check(lib().nexus_debug_cu_probe(self._ctx, phase, n_blocks, out.ctypes.data_as(C.c_void_p)))
         return out.reshape(8, 8, 16)
+
+
+OP_DENSE, OP_ATTENTION = 0, 1
+
+
+class CostModel:
+    """Host-side latency model of the two phases (marshalling only; the arithmetic is in the library).
+    ops: sequences of (flops, bytes, r_sat, lambda, kind)."""
+
+    def __init__(self, peak_flops: float, peak_bytes_per_s: float, prefill_ops, decode_ops):
+        self._p = (CostOp * max(len(prefill_ops), 1))(*[CostOp(*o, 0) for o in prefill_ops])
+        self._d = (CostOp * max(len(decode_ops), 1))(*[CostOp(*o, 0) for o in decode_ops])
+        self.c = CostModelC(peak_flops, peak_bytes_per_s, len(prefill_ops), len(decode_ops), self._p, self._d)
+
+    def latency(self, phase: int, share: int, total: int) -> float:
+        out = C.c_double()
+        _check(lib().nexus_cost_latency(C.byref(self.c), phase, share, total, C.byref(out)))
+        return out.value
+
+    def adjust_partition(self, target_phase: int, cur_prefill_share: int, total: int, alpha: float, beta: float):
+        new, ev = C.c_int32(), C.c_int32()
+        _check(lib().nexus_adjust_partition(C.byref(self.c), target_phase, cur_prefill_share, total, C.c_double(alpha),
+                                            C.c_double(beta), C.byref(new), C.byref(ev)))
+        return new.value, ev.value
+
+    def partition_controller(self, kv_usage: float, kv_switch: float, cur_prefill_share: int, total: int, alpha: float,
+                             beta: float, delta: int) -> int:
+        new = C.c_int32()
+        _check(lib().nexus_partition_controller(C.byref(self.c), C.c_double(kv_usage), C.c_double(kv_switch),
+                                                cur_prefill_share, total, C.c_double(alpha), C.c_double(beta), delta,
+                                                C.byref(new)))
+        return new.value
+
+
+def cost_fit(shares, seconds, peak_flops: float):
+    n = len(shares)
+    a, b = (C.c_double * n)(*shares), (C.c_double * n)(*seconds)
+    f, r, l = C.c_double(), C.c_double(), C.c_double()
+    _check(lib().nexus_cost_fit(n, a, b, C.c_double(peak_flops), C.byref(f), C.byref(r), C.byref(l)))
+    return f.value, r.value, l.value
+
+
+def cost_describe(shape, layers: int, prefill_tokens: float, prefill_pairs: float, prefill_kv_tokens: float,
+                  decode_reqs: float, decode_kv_tokens: float):
+    """Algorithmic (flops, bytes, 1.0, 0.0, kind) of QKV, attention, O, gate/up, down for each phase."""
+    md = ModelDesc(shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, layers, shape.page_size,
+                   shape.rms_eps, shape.rope_theta)
+    p, d = (CostOp * 5)(), (CostOp * 5)()
+    _check(lib().nexus_cost_describe(C.byref(md), layers, C.c_double(prefill_tokens), C.c_double(prefill_pairs),
+                                     C.c_double(prefill_kv_tokens), C.c_double(decode_reqs), C.c_double(decode_kv_tokens), p, d))
+    unpack = lambda ops: [(o.flops, o.bytes, o.r_sat, o.lam, o.kind) for o in ops]
+    return unpack(p), unpack(d)
 
 
 def context_for(w: Workload, device: int = 0, n_layers: int = 1) -> Nexus:
