@@ -1,0 +1,148 @@
+"""Validation of the partition cost model (Sec. 4.1) against measurements on the GPU: the per-operator saturation
+curves are extracted from traced kernel times of each phase alone on varying CU shares (as the paper prescribes),
+and the calibrated model's predictions are compared with the measured concurrent step and the measured choice."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cost_model as cm
+from paper_2507_06608_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nx():
+    from paper_2507_06608_amd import binding
+    binding.lib()          # fails loudly if the library was not built
+    assert torch.cuda.is_available()
+    return binding
+
+PEAK_FLOPS, PEAK_BW = 2.5e15, 8.0e12
+TOTAL = 32  # one step = one CU in each of the 8 XCDs
+
+# traced kernel families that make up each of the five modelled operators (QKV, attention, O, gate/up, down);
+# the two RMSNorm launches share one id and are split between QKV and gate/up
+PREFILL_OPS = (("gemm_qkv", "rope_append"), ("attn_prefill", "attn_merge"), ("gemm_o",), ("gemm_gate_up",), ("gemm_down", "splitk_reduce"))
+DECODE_OPS = (("gemm_qkv", "rope_append"), ("attn_decode", "attn_merge"), ("gemm_o",), ("gemm_gate_up",), ("gemm_down", "splitk_reduce"))
+
+
+def op_times(ctx, phase, run, groups, reps=6):
+    per_kernel = {}
+    for k in {k for g in groups for k in g} | {"rmsnorm"}:
+        ctx.trace_begin(phase, k)
+        for _ in range(reps):
+            run()
+        ms, n = ctx.trace_read()
+        per_kernel[k] = ms * 1e-3 * n / reps
+    t = [sum(per_kernel[k] for k in g) for g in groups]
+    t[0] += per_kernel["rmsnorm"] / 2
+    t[3] += per_kernel["rmsnorm"] / 2
+    # the gaps between dependent launches belong to the phase but to no kernel: spread them over the operators in
+    # proportion, so that the operator times add up to the phase as it runs untraced
+    ctx.sync()
+    t0 = time.perf_counter()
+    for _ in range(4 * reps):
+        run()
+    ctx.sync()
+    phase_s = (time.perf_counter() - t0) / (4 * reps)
+    scale = phase_s / sum(t)
+    return [v * scale for v in t]
+
+
+def test_calibrated_model_against_measured_splits(nx):
+    print("[gpu test] cost model calibration and validation", flush=True)
+    wl = synth.config(2, seed=0, kv_device="cuda:0")
+    w = synth.make_weights(wl.shape, 0)
+    ctx = nx.context_for(wl)
+    ctx.load_layer(0, w)
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+    p, d = wl.prefill, wl.decode
+    pairs = float(sum(int(n) * int(pre) + int(n) * (int(n) + 1) // 2 for n, pre in zip(p.chunk_len, p.prefix_len)))
+    kv_p = float((p.prefix_len + p.chunk_len).sum())
+    kv_d = float((d.ctx_len + 1).sum())
+    alg_p, alg_d = nx.cost_describe(wl.shape, 1, p.n_tokens, pairs, kv_p, d.n_reqs, kv_d)
+
+    shares = list(range(4, TOTAL, 4)) + [TOTAL]
+    meas = {nx.PHASE_PREFILL: [], nx.PHASE_DECODE: []}
+    for s in shares:
+        for phase, groups, run in ((nx.PHASE_PREFILL, PREFILL_OPS, lambda: ctx.prefill_chunk(pb, kv)),
+                                   (nx.PHASE_DECODE, DECODE_OPS, lambda: ctx.decode_step(db, kv))):
+            if s == TOTAL:
+                ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
+            elif phase == nx.PHASE_PREFILL:
+                ctx.set_cu_split(8 * s, 256 - 8 * s)
+            else:
+                ctx.set_cu_split(256 - 8 * s, 8 * s)
+            for _ in range(3):
+                run()
+            ctx.sync()
+            meas[phase].append(op_times(ctx, phase, run, groups))
+    rs = [s / TOTAL for s in shares]
+
+    def calibrated(alg, rows):
+        ops = []
+        for i, (flops, nbytes, _, _, kind) in enumerate(alg):
+            c, r_sat, lam = nx.cost_fit(rs, [row[i] for row in rows], PEAK_FLOPS)
+            ops.append((c, nbytes, r_sat, lam, kind))
+        return ops
+    ops_p, ops_d = calibrated(alg_p, meas[nx.PHASE_PREFILL]), calibrated(alg_d, meas[nx.PHASE_DECODE])
+    for name, ops in (("prefill", ops_p), ("decode", ops_d)):
+        print(f"[cost model] {name} operators (effective GFLOP, R_sat, lambda): " +
+              ", ".join(f"({o[0] / 1e9:.1f}, {o[2]:.3f}, {o[3]:+.2f})" for o in ops), flush=True)
+    model = nx.CostModel(PEAK_FLOPS, PEAK_BW, ops_p, ops_d)
+    oracle_model = cm.Model(PEAK_FLOPS, PEAK_BW, [cm.Op(*o) for o in ops_p], [cm.Op(*o) for o in ops_d])
+
+    cands = list(range(32, 256, 32))
+    prof = ctx.profile_split(pb, db, kv, cands, nx.POLICY_MIN_STEP, repeats=5)
+
+    # (a) Eq. 5-6 with the calibrated curves against each phase timed alone, untraced, on its share (the
+    # contention term is off for a phase on its own: the other phase has no operators)
+    alone_p = nx.CostModel(PEAK_FLOPS, PEAK_BW, ops_p, [])
+    alone_d = nx.CostModel(PEAK_FLOPS, PEAK_BW, [], ops_d)
+    mp = [alone_p.latency(nx.PHASE_PREFILL, c // 8, TOTAL) * 1e3 for c in cands]
+    md = [alone_d.latency(nx.PHASE_DECODE, TOTAL - c // 8, TOTAL) * 1e3 for c in cands]
+    print("[cost model] prefill CUs:            " + " ".join(f"{c:7d}" for c in cands))
+    print("[cost model] prefill alone, model ms:" + " ".join(f"{t:7.3f}" for t in mp))
+    print("[cost model] prefill alone, timed ms:" + " ".join(f"{t:7.3f}" for t in prof["t_prefill_ms"]))
+    print("[cost model] decode alone, model ms: " + " ".join(f"{t:7.3f}" for t in md))
+    print("[cost model] decode alone, timed ms: " + " ".join(f"{t:7.3f}" for t in prof["t_decode_ms"]), flush=True)
+    for c, a, b in zip(cands, mp, prof["t_prefill_ms"]):
+        assert a == pytest.approx(b, rel=0.2), ("prefill alone", c)
+    for c, a, b in zip(cands, md, prof["t_decode_ms"]):
+        assert a == pytest.approx(b, rel=0.2), ("decode alone", c)
+
+    # (b) concurrent step: prediction max(T_prefill(R_p), T_decode(1 - R_p | R_p)) against the measured step
+    pred = []
+    for c in cands:
+        s = c // 8
+        tp, td = model.latency(nx.PHASE_PREFILL, s, TOTAL), model.latency(nx.PHASE_DECODE, TOTAL - s, TOTAL)
+        assert tp == pytest.approx(cm.cost_model(oracle_model, cm.PREFILL, s, TOTAL), rel=1e-12)
+        assert td == pytest.approx(cm.cost_model(oracle_model, cm.DECODE, TOTAL - s, TOTAL), rel=1e-12)
+        pred.append(max(tp, td) * 1e3)
+    print("[cost model] prefill CUs:        " + " ".join(f"{c:7d}" for c in cands))
+    print("[cost model] predicted step ms:  " + " ".join(f"{t:7.3f}" for t in pred))
+    print("[cost model] measured step ms:   " + " ".join(f"{t:7.3f}" for t in prof["t_step_ms"]), flush=True)
+    for c, a, b in zip(cands, pred, prof["t_step_ms"]):
+        assert a == pytest.approx(b, rel=0.25), ("concurrent step", c)
+    assert abs(int(np.argmin(pred)) - int(np.argmin(prof["t_step_ms"]))) <= 1
+
+    # (c) the greedy search on the model against the same objectives applied to the measured curves
+    for target, policy in ((nx.PHASE_PREFILL, nx.POLICY_PREFILL_PRIORITIZED), (nx.PHASE_DECODE, nx.POLICY_DECODE_PRIORITIZED)):
+        share, evals = model.adjust_partition(target, TOTAL // 2, TOTAL, 1.3, 1.1)
+        i = nx.choose_split(prof["t_prefill_ms"], prof["t_decode_ms"], prof["t_step_ms"], prof["t_prefill_all_ms"],
+                            prof["t_decode_all_ms"], policy, 1.3, 1.1)
+        print(f"[cost model] target {'prefill' if target == nx.PHASE_PREFILL else 'decode'}: model picks {8 * share} prefill CUs "
+              f"in {evals} evaluations, measured curves pick {cands[i]}", flush=True)
+        assert abs(8 * share - cands[i]) <= 48
+
+    # (d) Sec. 3.3: more prefill KV traffic at a fixed partition can only slow the modelled decode
+    def with_prefix(kv_tokens):
+        a_p, a_d = nx.cost_describe(wl.shape, 1, p.n_tokens, p.n_tokens * kv_tokens, kv_tokens, d.n_reqs, kv_d)
+        op = [(ops_p[i][0] * (a_p[i][0] / alg_p[i][0]) if i == 1 else ops_p[i][0], a_p[i][1], ops_p[i][2], ops_p[i][3], ops_p[i][4]) for i in range(5)]
+        return nx.CostModel(PEAK_FLOPS, PEAK_BW, op, ops_d).latency(nx.PHASE_DECODE, 16, TOTAL)
+    assert with_prefix(10000) >= with_prefix(2000)
+    ctx.close()
