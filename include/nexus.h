@@ -160,7 +160,9 @@ typedef enum {
 /* Creates a context on `device` (HIP ordinal): streams, workspace sized by `limits`, rotary table. */
 int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int device, nexus_ctx **out);
 void nexus_destroy(nexus_ctx *ctx);
-/* Packs one layer's weights (device pointers) into the library's own tile-ordered copy.  Synchronous. */
+/* Packs one layer's weights (device pointers) into the library's own tile-ordered copy.  Synchronous: returns when
+ * the copy is complete.  The packing runs on a stream of the library's own, which does not wait for any other
+ * stream: work that produces the source tensors must have finished before the call. */
 int nexus_load_layer(nexus_ctx *ctx, int layer, const nexus_layer_weights *w);
 /* Waits for everything the context has enqueued. */
 int nexus_sync(nexus_ctx *ctx);

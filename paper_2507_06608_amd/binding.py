@@ -188,8 +188,8 @@ class Nexus:
         dev = {k: (None if v is None else v.to(self.device, torch.bfloat16).contiguous()) for k, v in w.items()}
         cw = LayerWeights(*[None if dev.get(k) is None else dev[k].data_ptr() for k in
                             ("attn_norm_g", "w_qkv", "b_qkv", "w_o", "ffn_norm_g", "w_gate_up", "w_down")])
+        torch.cuda.synchronize(self.device)   # the library's stream does not wait for torch's: sources must be complete
         _check(lib().nexus_load_layer(self._ctx, layer, C.byref(cw)))
-        torch.cuda.synchronize(self.device)
 
     # -- KV cache
     def make_kv(self, k_canon: torch.Tensor, v_canon: torch.Tensor, layers: int = 1):

@@ -69,13 +69,21 @@ def _bf16(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
 
 
-def make_weights(shape: ModelShape, seed: int, layer: int = 0) -> Dict[str, torch.Tensor]:
+def weight_std(shape: ModelShape) -> float:
+    """Standard deviation of the weight matrices: 0.02 as the configurations state it, except for the 70B shape,
+    whose configuration names no distribution: there the variance follows the fan-in (0.02 at hidden 4096, so
+    0.02 / sqrt(2) at 8192), which keeps a layer's output at the scale of its input instead of 7 times larger."""
+    return 0.02 * (4096.0 / shape.hidden) ** 0.5 if shape.name == "llama3_70b" else 0.02
+
+
+def make_weights(shape: ModelShape, seed: int, layer: int = 0, std: Optional[float] = None) -> Dict[str, torch.Tensor]:
     """bf16 CPU tensors of one layer, in the [out_features, in_features] orientation."""
     rng = np.random.default_rng([seed, 1000 + layer])
     d, F = shape.hidden, shape.ffn
+    std = np.float32(weight_std(shape) if std is None else std)
 
     def mat(r, c):
-        return _bf16(rng.standard_normal((r, c), dtype=np.float32) * np.float32(0.02))
+        return _bf16(rng.standard_normal((r, c), dtype=np.float32) * std)
 
     def gain():
         return _bf16(1.0 + rng.standard_normal(d, dtype=np.float32) * np.float32(0.02))
@@ -211,7 +219,17 @@ def config(idx: int, seed: int = 0, kv_device: str = "cpu") -> Workload:
         pre = rng.integers(0, 6145, size=4).tolist()
         return make_workload("cfg3_llama3_8b_heavy", SHAPES["llama3_8b"], seed, chunk_lens=[2048] * 4,
                              prefix_lens=pre, decode_ctx=ctx, kv_device=kv_device)
-    raise ValueError(f"config {idx} is not a single-layer workload of this build")
+    if idx == 4:
+        # One iteration of the trace-driven configuration at its caps: a full 1024-token chunk in the middle of a
+        # long prompt next to a full decode pool (output positions on top of lognormal-like prompt lengths).
+        ctx = np.minimum(8192 + 1024, rng.lognormal(np.log(1024.0), 0.8, size=128) + rng.lognormal(np.log(256.0), 0.7, size=128))
+        return make_workload("cfg4_qwen25_14b_iteration", SHAPES["qwen25_14b"], seed, chunk_lens=[1024],
+                             prefix_lens=[3072], decode_ctx=[int(c) for c in ctx], kv_device=kv_device)
+    if idx == 5:
+        ctx = rng.integers(1024, 4097, size=64).tolist()
+        return make_workload("cfg5_llama3_70b_2048over2048_64dec", SHAPES["llama3_70b"], seed, chunk_lens=[2048],
+                             prefix_lens=[2048], decode_ctx=ctx, kv_device=kv_device)
+    raise ValueError(f"no configuration {idx}")
 
 
 def subset_for_oracle(w: Workload, prefill_reqs: List[int], decode_reqs: List[int]):

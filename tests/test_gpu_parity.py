@@ -309,6 +309,35 @@ def test_cfg2_full_size_sampled_outputs_in_bench_launch_configuration(nx, oracle
     ctx.close()
 
 
+def _check_sampled(oracle, tag, wl, w, yp, yd, kv_after, n_pre=16):
+    """Oracle on the first n_pre rows of every chunk and on five decode requests (shortest, longest and median
+    context and two fixed ones) of a workload too large to evaluate whole, with the K/V those rows append."""
+    pb_host, d = wl.prefill, wl.decode
+    order = np.argsort(d.ctx_len)
+    dec_sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 3, d.n_reqs - 2})
+    sub = synth.subset_for_oracle(wl, list(range(pb_host.n_reqs)), dec_sample)
+    sp = sub.prefill
+    rows = np.concatenate([np.arange(int(sp.cu_chunk[r]), int(sp.cu_chunk[r]) + n_pre) for r in range(sp.n_reqs)])
+    sub.prefill = synth.PrefillBatch(sp.x[torch.as_tensor(rows)], np.arange(sp.n_reqs + 1, dtype=np.int32) * n_pre, sp.prefix_len, sp.page_table)
+    ref = run_oracle(oracle, sub, w)
+    full_rows = np.concatenate([np.arange(int(pb_host.cu_chunk[r]), int(pb_host.cu_chunk[r]) + n_pre) for r in range(pb_host.n_reqs)])
+    assert_close(f"{tag} prefill sampled rows", f32(yp[torch.as_tensor(full_rows, device=yp.device)]), ref["y_p"])
+    assert_close(f"{tag} decode sample", f32(yd[dec_sample]), ref["y_d"])
+    pages = sub.notes["pages"]
+    ps = wl.shape.page_size
+    kg, vg = kv_after
+    checks = [(f"prefill {r}", sub.prefill.page_table[r], range(int(sp.prefix_len[r]), int(sp.prefix_len[r]) + n_pre))
+              for r in range(sp.n_reqs)]
+    checks += [(f"decode {j}", sub.decode.page_table[i], [int(sub.decode.ctx_len[i])]) for i, j in enumerate(dec_sample)]
+    for name, req_row, positions in checks:
+        for pos in positions:
+            sp_page = int(req_row[pos // ps])
+            full_page = pages[sp_page]
+            assert_close(f"{tag} K {name} pos {pos}", f32(kg[full_page, :, pos % ps]), ref["k_pool"][sp_page, :, pos % ps])
+            assert_close(f"{tag} V {name} pos {pos}", f32(vg[full_page, :, pos % ps]), ref["v_pool"][sp_page, :, pos % ps])
+
+
+
 def test_cfg3_heavy_mix_full_size_sampled(nx, oracle, monkeypatch):
     """The heavy mix at full size (4 x 2048-token chunks over prefixes up to 6144, 256 decode requests with contexts
     up to 8192; one layer).  Long chunks take the 256 x 256 GEMM tiles and the decode batch of 256 takes the tiled
@@ -347,26 +376,82 @@ def test_cfg3_heavy_mix_full_size_sampled(nx, oracle, monkeypatch):
             assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (split, tiles)
         del yp2, yd2, kv2
 
-    n_pre = 16
-    order = np.argsort(d.ctx_len)
-    dec_sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 3, 200})
-    sub = synth.subset_for_oracle(wl, list(range(pb_host.n_reqs)), dec_sample)
-    sp = sub.prefill
-    rows = np.concatenate([np.arange(int(sp.cu_chunk[r]), int(sp.cu_chunk[r]) + n_pre) for r in range(sp.n_reqs)])
-    sub.prefill = synth.PrefillBatch(sp.x[torch.as_tensor(rows)], np.arange(sp.n_reqs + 1, dtype=np.int32) * n_pre, sp.prefix_len, sp.page_table)
-    ref = run_oracle(oracle, sub, w)
-    full_rows = np.concatenate([np.arange(int(pb_host.cu_chunk[r]), int(pb_host.cu_chunk[r]) + n_pre) for r in range(pb_host.n_reqs)])
-    assert_close("cfg3 prefill sampled rows", f32(yp[torch.as_tensor(full_rows, device=yp.device)]), ref["y_p"])
-    assert_close("cfg3 decode sample", f32(yd[dec_sample]), ref["y_d"])
-    pages = sub.notes["pages"]
-    ps = wl.shape.page_size
-    kg, vg = kv_after
-    checks = [(f"prefill {r}", sub.prefill.page_table[r], range(int(sp.prefix_len[r]), int(sp.prefix_len[r]) + n_pre))
-              for r in range(sp.n_reqs)]
-    checks += [(f"decode {j}", sub.decode.page_table[i], [int(sub.decode.ctx_len[i])]) for i, j in enumerate(dec_sample)]
-    for name, req_row, positions in checks:
-        for pos in positions:
-            sp_page = int(req_row[pos // ps])
-            full_page = pages[sp_page]
-            assert_close(f"K {name} pos {pos}", f32(kg[full_page, :, pos % ps]), ref["k_pool"][sp_page, :, pos % ps])
-            assert_close(f"V {name} pos {pos}", f32(vg[full_page, :, pos % ps]), ref["v_pool"][sp_page, :, pos % ps])
+    _check_sampled(oracle, "cfg3", wl, w, yp, yd, kv_after)
+
+
+@pytest.mark.parametrize("idx,layer,split", [(4, 47, (160, 96)), (5, 79, (192, 64))])
+def test_larger_model_shapes_full_size_sampled(nx, oracle, idx, layer, split):
+    """One layer of the 14B-shaped (G = 5, hidden 5120) and the 70B-shaped (G = 8, hidden 8192, FFN 28672)
+    configurations at full batch size, with the weights of a late layer of the stack: concurrent == serialized bit
+    for bit, and the oracle on sampled rows."""
+    _announce(f"cfg{idx} one layer at full size, sampled")
+    wl = synth.config(idx, seed=0, kv_device="cuda:0")
+    w = synth.make_weights(wl.shape, 0, layer)
+
+    def run(split):
+        ctx = nx.context_for(wl)
+        ctx.load_layer(0, w)
+        kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+        pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+        ctx.set_cu_split(*split)
+        ctx.mixed_step(pb, db, kv)
+        ctx.sync()
+        out = (pb.y.clone(), db.y.clone(), ctx.kv_export(kv))
+        ctx.close()
+        return out
+
+    yp, yd, kv_after = run(split)
+    yp2, yd2, kv2 = run((nx.CUS_ALL, nx.CUS_ALL))
+    assert torch.equal(yp2.view(torch.int16), yp.view(torch.int16))
+    assert torch.equal(yd2.view(torch.int16), yd.view(torch.int16))
+    for a, b in zip(kv2, kv_after):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    del yp2, yd2, kv2
+    _check_sampled(oracle, f"cfg{idx}", wl, w, yp, yd, kv_after)
+
+
+def test_cfg5_full_depth_80_layers_resident(nx):
+    """The 70B-shaped stack at full depth on the one GPU: 80 layers of packed weights (~137 GB) and 80 layers of
+    KV (~55 GB) resident, one mixed step through all of them.  Layer weights are drawn on the device (a host copy
+    of 137 GB is avoided); parity of this shape is the business of the sampled-layer test above, this one checks
+    what only the full depth can show: it fits, the layer-to-layer hand-over works over 80 layers on both streams,
+    and concurrent == serialized bit for bit."""
+    _announce("cfg5 full depth")
+    wl = synth.config(5, seed=0, kv_device="cuda:0")
+    s = wl.shape
+    free, total = torch.cuda.mem_get_info(0)
+    need = s.n_layers * (2 * s.params_per_layer + 2 * wl.k_pool.numel() * 2) + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free device memory, {free >> 30} GiB available")
+    ctx = nx.context_for(wl, n_layers=s.n_layers)
+    g = torch.Generator(device="cuda:0")
+    for l in range(s.n_layers):
+        g.manual_seed(1000 + l)
+
+        def mat(r, c):
+            return (torch.randn((r, c), generator=g, device="cuda:0") * synth.weight_std(s)).to(torch.bfloat16)
+
+        def gain():
+            return (1.0 + torch.randn(s.hidden, generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
+        ctx.load_layer(l, {"attn_norm_g": gain(), "w_qkv": mat(s.n_qkv, s.hidden), "w_o": mat(s.hidden, s.q_dim),
+                           "ffn_norm_g": gain(), "w_gate_up": mat(2 * s.ffn, s.hidden), "w_down": mat(s.hidden, s.ffn)})
+        if l % 20 == 19:
+            print(f"[cfg5] {l + 1} layers loaded", flush=True)
+    pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+    outs = []
+    for split in ((224, 32), (nx.CUS_ALL, nx.CUS_ALL)):
+        kv = ctx.make_kv(wl.k_pool, wl.v_pool, layers=s.n_layers)
+        ctx.set_cu_split(*split)
+        ctx.mixed_step(pb, db, kv, layers=(0, s.n_layers))
+        ctx.sync()
+        t = ctx.mixed_step(pb, db, kv, layers=(0, s.n_layers), timing=True)
+        print(f"[cfg5] split {split}: step {t.t_step_ms:.1f} ms over {s.n_layers} layers, decode {t.t_decode_ms:.1f} ms", flush=True)
+        ctx.mixed_step(pb, db, kv, layers=(0, s.n_layers))
+        ctx.sync()
+        outs.append((pb.y.clone(), db.y.clone()))
+        del kv
+        ctx._kv_keep = None
+    assert torch.isfinite(outs[0][0].float()).all() and torch.isfinite(outs[0][1].float()).all()
+    assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16))
+    assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
+    ctx.close()
