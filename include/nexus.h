@@ -302,6 +302,89 @@ int nexus_cost_describe(const nexus_model_desc *desc, int layers, double prefill
                         double prefill_kv_tokens, double decode_reqs, double decode_kv_tokens,
                         nexus_cost_op *prefill_ops, nexus_cost_op *decode_ops);
 
+/* ---- phase-specific schedulers and the iteration loop around them (Sec. 4.3, Alg. 2; host only) ---------- */
+
+/*
+ * The prefill queue is ordered either by arrival (FCFS) or by Shortest Prompt First with the age term of Eq. 10:
+ * score = remaining prompt tokens - gamma * (now - arrival), lowest first, ties to the earlier arrival, then to the
+ * lower id.  Requests are taken in that order while the batch's tokens stay within token_budget (Alg. 2); the
+ * first request that does not fit ends the batch, after taking what is left of the budget as a partial chunk when
+ * chunk_tail is set (chunked prefill, Sec. 5; without it a prompt longer than the budget is never scheduled).
+ * Decode is FCFS (Sec. 4.3.2): a request whose last prompt chunk has committed has emitted its first token and
+ * joins the decode pool, in the order of those commits, as soon as the pool has room; every pool member decodes
+ * one token per iteration until it has emitted output_len tokens.
+ * KV pages: a request is admitted to its first chunk only when the pages of its whole lifetime
+ * (prompt_len + output_len - 1 tokens) can be reserved; a request that cannot holds back the not yet admitted
+ * requests behind it, never the admitted ones.  Pages are taken from a free list as positions get written and go
+ * back when the request finishes.
+ */
+typedef struct nexus_sched nexus_sched;
+typedef enum { NEXUS_PREFILL_FCFS = 0, NEXUS_PREFILL_SPF = 1 } nexus_prefill_policy;
+typedef struct {
+    int32_t prefill_policy;   /* nexus_prefill_policy                                             */
+    int32_t token_budget;     /* B of Alg. 2: prompt tokens per iteration                         */
+    int32_t max_prefill_reqs; /* requests per prefill batch; 0 = no limit                         */
+    int32_t max_decode_reqs;  /* capacity of the decode pool                                      */
+    int32_t page_size, n_pages;
+    int32_t chunk_tail;       /* see above; 1 for chunked prefill                                 */
+    int32_t reserved;         /* must be 0                                                        */
+    double gamma;             /* tokens per second of age (Sec. 5 uses 15)                        */
+    const int32_t *page_order; /* host, a permutation of 0..n_pages-1: the order in which the free list first hands
+                                  pages out; NULL for 0, 1, 2, ...  Copied by nexus_sched_create.  */
+} nexus_sched_config;
+
+/*
+ * The batches of one iteration.  All pointers are host memory owned by the scheduler, valid until its next call.
+ * Page tables are [n][max_pages] row-major, -1 past a request's own pages; a request holds exactly the pages
+ * covering the positions it will have written when the iteration commits.  The fields map one to one onto
+ * nexus_prefill_batch / nexus_decode_batch.
+ */
+typedef struct {
+    int32_t n_prefill, prefill_tokens;
+    const int32_t *prefill_req;        /* [n_prefill] request ids                           */
+    const int32_t *prefill_prefix;     /* [n_prefill] tokens already cached                 */
+    const int32_t *prefill_chunk;      /* [n_prefill] tokens of this chunk                  */
+    const int32_t *prefill_cu_chunk;   /* [n_prefill + 1] exclusive prefix sum of the above */
+    const int32_t *prefill_page_table;
+    int32_t prefill_max_pages, prefill_max_chunk, prefill_max_total_len;
+    int32_t n_decode;
+    const int32_t *decode_req;         /* [n_decode] request ids, in pool order             */
+    const int32_t *decode_ctx;         /* [n_decode] tokens cached before the step          */
+    const int32_t *decode_page_table;
+    int32_t decode_max_pages, decode_max_ctx;
+    int32_t kv_used_pages, kv_total_pages; /* pages holding tokens / pool size: KV_u of Alg. 1 */
+} nexus_sched_batch;
+
+typedef struct {
+    double arrival_s, first_token_s, finish_s; /* -1 while not reached */
+    int32_t prompt_len, output_len, prefilled, emitted, n_pages, state; /* state: 0 waiting, 1 ready, 2 decoding, 3 done */
+} nexus_sched_request_info;
+
+/* Serving metrics of Sec. 6.1 over what has been committed so far; percentiles are nearest-rank. */
+typedef struct {
+    int32_t n_submitted, n_first_token, n_finished, reserved;
+    int64_t prefill_tokens, decode_tokens;
+    double ttft_mean, ttft_p50, ttft_p95, ttft_p99, ttft_max;          /* first token - arrival              */
+    double tbt_mean, tbt_p50, tbt_p95, tbt_p99, tbt_max;               /* between consecutive tokens         */
+    double norm_latency_mean, norm_latency_p95;                        /* (finish - arrival) / output tokens */
+} nexus_sched_summary;
+
+int nexus_sched_create(const nexus_sched_config *cfg, nexus_sched **out);
+void nexus_sched_destroy(nexus_sched *s);
+/* Queues a request (arrival in seconds on the caller's clock; prompt_len, output_len >= 1).  Fails with
+ * NEXUS_ESHAPE when the request's lifetime needs more pages than the pool has. */
+int nexus_sched_submit(nexus_sched *s, double arrival_s, int32_t prompt_len, int32_t output_len, int32_t *id_out);
+/* Forms the batches of the iteration starting at now_s from the requests with arrival <= now_s.  Either batch may
+ * be empty.  Must be followed by nexus_sched_commit before the next call. */
+int nexus_sched_next(nexus_sched *s, double now_s, nexus_sched_batch *out);
+/* The iteration formed by the last nexus_sched_next completed at end_s (>= its now_s). */
+int nexus_sched_commit(nexus_sched *s, double end_s);
+int nexus_sched_request(const nexus_sched *s, int32_t id, nexus_sched_request_info *out);
+int nexus_sched_summarize(const nexus_sched *s, nexus_sched_summary *out);
+/* Raw samples: kind 0 = TTFT (by request id), 1 = TBT (in commit order), 2 = normalised latency (by request id).
+ * Writes up to cap doubles to host `out` (may be NULL with cap 0) and the total number available to *n. */
+int nexus_sched_samples(const nexus_sched *s, int kind, double *out, int32_t cap, int32_t *n);
+
 /* ---- measurement and test hooks ----------------------------------------------------------------------------- */
 
 /* Kernel ids for nexus_trace_*: one per kernel family on the path. */

@@ -9,6 +9,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+from dataclasses import dataclass
 from typing import Dict, Optional, Sequence
 
 import numpy as np
@@ -31,7 +32,9 @@ EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "n
            "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_profile_split",
            "nexus_choose_split", "nexus_trace_begin", "nexus_trace_read", "nexus_debug_fetch",
            "nexus_debug_cu_probe", "nexus_cost_latency", "nexus_adjust_partition", "nexus_partition_controller",
-           "nexus_cost_fit", "nexus_cost_describe")
+           "nexus_cost_fit", "nexus_cost_describe",
+           "nexus_sched_create", "nexus_sched_destroy", "nexus_sched_submit", "nexus_sched_next", "nexus_sched_commit",
+           "nexus_sched_request", "nexus_sched_summarize", "nexus_sched_samples")
 
 
 class NexusError(RuntimeError):
@@ -96,9 +99,10 @@ def lib():
         _lib = C.CDLL(LIB_PATH)
         _lib.nexus_last_error.restype = C.c_char_p
         for name in EXPORTS:
-            if name not in ("nexus_last_error", "nexus_destroy"):
+            if name not in ("nexus_last_error", "nexus_destroy", "nexus_sched_destroy"):
                 getattr(_lib, name).restype = C.c_int
         _lib.nexus_destroy.restype = None
+        _lib.nexus_sched_destroy.restype = None
         _lib.nexus_choose_split.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
                                             C.c_int, C.c_float, C.c_float]
     return _lib
@@ -334,3 +338,121 @@ def context_for(w: Workload, device: int = 0, n_layers: int = 1) -> Nexus:
         max_pos = max(max_pos, int(d.ctx_len.max()) + 1)
     return Nexus(w.shape, max_prefill_tokens=p.n_tokens if p else 1, max_prefill_reqs=p.n_reqs if p else 1,
                  max_decode_reqs=d.n_reqs if d else 1, max_positions=max_pos, device=device, n_layers=n_layers)
+
+
+# ---- phase-specific schedulers (host only) ------------------------------------------------------------------------
+PREFILL_FCFS, PREFILL_SPF = 0, 1
+_I32P = C.POINTER(C.c_int32)
+
+
+class SchedConfigC(C.Structure):
+    _fields_ = [("prefill_policy", C.c_int32), ("token_budget", C.c_int32), ("max_prefill_reqs", C.c_int32),
+                ("max_decode_reqs", C.c_int32), ("page_size", C.c_int32), ("n_pages", C.c_int32),
+                ("chunk_tail", C.c_int32), ("reserved", C.c_int32), ("gamma", C.c_double), ("page_order", _I32P)]
+
+
+class SchedBatchC(C.Structure):
+    _fields_ = [("n_prefill", C.c_int32), ("prefill_tokens", C.c_int32), ("prefill_req", _I32P),
+                ("prefill_prefix", _I32P), ("prefill_chunk", _I32P), ("prefill_cu_chunk", _I32P),
+                ("prefill_page_table", _I32P), ("prefill_max_pages", C.c_int32), ("prefill_max_chunk", C.c_int32),
+                ("prefill_max_total_len", C.c_int32), ("n_decode", C.c_int32), ("decode_req", _I32P),
+                ("decode_ctx", _I32P), ("decode_page_table", _I32P), ("decode_max_pages", C.c_int32),
+                ("decode_max_ctx", C.c_int32), ("kv_used_pages", C.c_int32), ("kv_total_pages", C.c_int32)]
+
+
+class SchedRequestInfo(C.Structure):
+    _fields_ = [("arrival_s", C.c_double), ("first_token_s", C.c_double), ("finish_s", C.c_double),
+                ("prompt_len", C.c_int32), ("output_len", C.c_int32), ("prefilled", C.c_int32), ("emitted", C.c_int32),
+                ("n_pages", C.c_int32), ("state", C.c_int32)]
+
+
+class SchedSummary(C.Structure):
+    _fields_ = [("n_submitted", C.c_int32), ("n_first_token", C.c_int32), ("n_finished", C.c_int32), ("reserved", C.c_int32),
+                ("prefill_tokens", C.c_int64), ("decode_tokens", C.c_int64)] + \
+               [(k, C.c_double) for k in ("ttft_mean", "ttft_p50", "ttft_p95", "ttft_p99", "ttft_max", "tbt_mean", "tbt_p50",
+                                          "tbt_p95", "tbt_p99", "tbt_max", "norm_latency_mean", "norm_latency_p95")]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
+def _arr(ptr, n) -> np.ndarray:
+    return np.ctypeslib.as_array(ptr, shape=(n,)).copy() if n else np.zeros(0, np.int32)
+
+
+@dataclass
+class SchedIteration:
+    """Host copies of one iteration's batches (the scheduler's own arrays are only valid until its next call)."""
+    prefill_req: np.ndarray
+    prefill_prefix: np.ndarray
+    prefill_chunk: np.ndarray
+    prefill_cu_chunk: np.ndarray
+    prefill_page_table: np.ndarray   # [n_prefill, max_pages]
+    prefill_max_chunk: int
+    prefill_max_total_len: int
+    decode_req: np.ndarray
+    decode_ctx: np.ndarray
+    decode_page_table: np.ndarray    # [n_decode, max_pages]
+    decode_max_ctx: int
+    kv_used_pages: int
+    kv_total_pages: int
+
+
+class Scheduler:
+    """Marshalling around nexus_sched_*; every decision is taken in the library."""
+
+    def __init__(self, policy: int, token_budget: int, max_decode_reqs: int, page_size: int, n_pages: int,
+                 gamma: float = 15.0, chunk_tail: bool = True, max_prefill_reqs: int = 0, page_order=None):
+        order = None if page_order is None else np.ascontiguousarray(page_order, np.int32)
+        cfg = SchedConfigC(policy, token_budget, max_prefill_reqs, max_decode_reqs, page_size, n_pages, int(chunk_tail), 0,
+                           gamma, None if order is None else order.ctypes.data_as(_I32P))
+        self._s = C.c_void_p()
+        _check(lib().nexus_sched_create(C.byref(cfg), C.byref(self._s)))
+
+    def close(self):
+        if self._s:
+            lib().nexus_sched_destroy(self._s)
+            self._s = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def submit(self, arrival_s: float, prompt_len: int, output_len: int) -> int:
+        rid = C.c_int32()
+        _check(lib().nexus_sched_submit(self._s, C.c_double(arrival_s), prompt_len, output_len, C.byref(rid)))
+        return rid.value
+
+    def next(self, now_s: float) -> SchedIteration:
+        b = SchedBatchC()
+        _check(lib().nexus_sched_next(self._s, C.c_double(now_s), C.byref(b)))
+        npf, nd = b.n_prefill, b.n_decode
+        return SchedIteration(
+            _arr(b.prefill_req, npf), _arr(b.prefill_prefix, npf), _arr(b.prefill_chunk, npf), _arr(b.prefill_cu_chunk, npf + 1),
+            _arr(b.prefill_page_table, npf * b.prefill_max_pages).reshape(npf, b.prefill_max_pages), b.prefill_max_chunk,
+            b.prefill_max_total_len, _arr(b.decode_req, nd), _arr(b.decode_ctx, nd),
+            _arr(b.decode_page_table, nd * b.decode_max_pages).reshape(nd, b.decode_max_pages), b.decode_max_ctx,
+            b.kv_used_pages, b.kv_total_pages)
+
+    def commit(self, end_s: float):
+        _check(lib().nexus_sched_commit(self._s, C.c_double(end_s)))
+
+    def request(self, rid: int) -> SchedRequestInfo:
+        info = SchedRequestInfo()
+        _check(lib().nexus_sched_request(self._s, rid, C.byref(info)))
+        return info
+
+    def summary(self) -> dict:
+        out = SchedSummary()
+        _check(lib().nexus_sched_summarize(self._s, C.byref(out)))
+        return out.as_dict()
+
+    def samples(self, kind: int) -> np.ndarray:
+        n = C.c_int32()
+        _check(lib().nexus_sched_samples(self._s, kind, None, 0, C.byref(n)))
+        out = np.zeros(n.value, np.float64)
+        if n.value:
+            _check(lib().nexus_sched_samples(self._s, kind, out.ctypes.data_as(C.POINTER(C.c_double)), n.value, C.byref(n)))
+        return out

@@ -19,18 +19,11 @@
 #include "cost_model.hpp"
 #include "elementwise.hpp"
 #include "gemm.hpp"
+#include "status.hpp"
 
 using namespace nexus;
 
 // ---------------------------------------------------------------------------------------------- errors
-static thread_local char g_err[512] = "";
-static int fail(int code, const char *fmt, ...) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(g_err, sizeof(g_err), fmt, ap);
-    va_end(ap);
-    return code;
-}
 #define HIP_TRY(expr)                                                                                              \
     do {                                                                                                           \
         hipError_t e_ = (expr);                                                                                    \

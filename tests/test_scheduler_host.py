@@ -1,0 +1,126 @@
+"""The library's schedulers (host-only C ABI) against the oracle: identical decisions iteration by iteration on
+random traces, identical metrics, valid page tables, argument errors."""
+import numpy as np
+import pytest
+
+from oracle import scheduler as sch
+from paper_2507_06608_amd import binding as nx
+from tests.test_scheduler_pins import random_trace
+
+
+def _drive(policy, trace, budget, cap, ps, n_pages, gamma, max_prefill, dt, chunk_tail=True, page_order=None, iters=None):
+    lib_s = nx.Scheduler(policy, budget, cap, ps, n_pages, gamma=gamma, chunk_tail=chunk_tail, max_prefill_reqs=max_prefill,
+                         page_order=page_order)
+    ora = sch.Loop(policy, budget, cap, ps, n_pages, gamma=gamma, chunk_tail=chunk_tail, max_prefill_reqs=max_prefill or None)
+    for a, p, o in trace:
+        assert lib_s.submit(a, p, o) == ora.submit(a, p, o)
+    i = 0
+    while (iters is None and any(r.finish_time is None for r in ora.reqs)) or (iters is not None and i < iters):
+        now, end = i * dt, (i + 1) * dt
+        it, ref = lib_s.next(now), ora.next(now)
+        # what is unique: who runs, from where, how much
+        assert list(zip(it.prefill_req, it.prefill_prefix, it.prefill_chunk)) == ref.prefill, i
+        assert list(zip(it.decode_req, it.decode_ctx)) == ref.decode, i
+        assert it.prefill_cu_chunk.tolist() == np.concatenate([[0], np.cumsum([n for _, _, n in ref.prefill])]).astype(int).tolist()
+        assert it.kv_used_pages == ref.kv_used_pages and it.kv_total_pages == n_pages
+        # what is not (which pages): valid -- exact page counts, nothing shared, padding -1
+        held = []
+        for row, (rid, prefix, n) in zip(it.prefill_page_table, ref.prefill):
+            k = sch.pages_for(prefix + n, ps)
+            assert (row[:k] >= 0).all() and (row[k:] == -1).all()
+            held += row[:k].tolist()
+        for row, (rid, c) in zip(it.decode_page_table, ref.decode):
+            k = sch.pages_for(c + 1, ps)
+            assert (row[:k] >= 0).all() and (row[k:] == -1).all()
+            held += row[:k].tolist()
+        assert len(held) == len(set(held)) and all(p < n_pages for p in held)
+        if len(ref.prefill):
+            assert it.prefill_max_chunk == max(n for _, _, n in ref.prefill)
+            assert it.prefill_max_total_len == max(p + n for _, p, n in ref.prefill)
+        if len(ref.decode):
+            assert it.decode_max_ctx == max(c for _, c in ref.decode)
+        lib_s.commit(end)
+        ora.commit(end)
+        i += 1
+        assert i < 50000
+    return lib_s, ora
+
+
+@pytest.mark.parametrize("policy,seed,gamma", [(sch.FCFS, 1, 15.0), (sch.SPF, 2, 15.0), (sch.SPF, 3, 0.0), (sch.SPF, 4, 400.0)])
+def test_decisions_and_metrics_match_oracle(policy, seed, gamma):
+    trace = random_trace(seed, 150, rate=30.0)
+    rng = np.random.default_rng(seed)
+    lib_s, ora = _drive(policy, trace, budget=512, cap=16, ps=16, n_pages=2500, gamma=gamma, max_prefill=6, dt=0.05,
+                        page_order=rng.permutation(2500))
+    np.testing.assert_allclose(lib_s.samples(0), ora.ttft(), rtol=0, atol=0)
+    np.testing.assert_allclose(np.sort(lib_s.samples(1)), np.sort(ora.tbt()), rtol=0, atol=0)
+    np.testing.assert_allclose(lib_s.samples(2), ora.normalized_latency(), rtol=0, atol=0)
+    s = lib_s.summary()
+    assert s["n_submitted"] == s["n_first_token"] == s["n_finished"] == len(trace)
+    assert s["prefill_tokens"] == ora.prefill_tokens and s["decode_tokens"] == ora.decode_tokens
+    assert s["ttft_mean"] == pytest.approx(np.mean(ora.ttft()), rel=1e-12)
+    assert s["tbt_mean"] == pytest.approx(np.mean(ora.tbt()), rel=1e-12)
+    assert s["norm_latency_mean"] == pytest.approx(np.mean(ora.normalized_latency()), rel=1e-12)
+    # nearest-rank percentiles are numpy's inverted-CDF percentiles
+    for key, q, data in (("ttft_p50", 50, ora.ttft()), ("ttft_p95", 95, ora.ttft()), ("ttft_p99", 99, ora.ttft()),
+                         ("tbt_p95", 95, ora.tbt()), ("tbt_p99", 99, ora.tbt()), ("norm_latency_p95", 95, ora.normalized_latency())):
+        assert s[key] == np.percentile(data, q, method="inverted_cdf"), key
+    assert s["ttft_max"] == max(ora.ttft()) and s["tbt_max"] == max(ora.tbt())
+    for rid in (0, 17, len(trace) - 1):
+        info, r = lib_s.request(rid), ora.reqs[rid]
+        assert (info.arrival_s, info.first_token_s, info.finish_s) == (r.arrival, r.first_token_time, r.finish_time)
+        assert (info.prompt_len, info.output_len, info.prefilled, info.emitted, info.n_pages, info.state) == \
+               (r.prompt_len, r.output_len, r.prompt_len, r.output_len, 0, 3)
+
+
+def test_tight_kv_pool_and_printed_filling_rule():
+    trace = random_trace(9, 80, rate=40.0, prompt_cap=900)
+    _drive(sch.SPF, trace, budget=1024, cap=8, ps=16, n_pages=160, gamma=15.0, max_prefill=0, dt=0.05)
+    # printed rule: prompts above the budget stay in the queue for good, so run a fixed number of iterations
+    _drive(sch.FCFS, trace, budget=256, cap=8, ps=16, n_pages=4000, gamma=15.0, max_prefill=0, dt=0.05, chunk_tail=False, iters=300)
+
+
+def test_partial_state_is_reported():
+    s = nx.Scheduler(nx.PREFILL_FCFS, 100, 2, 16, 64)
+    s.submit(0.0, 150, 3)
+    s.next(0.0)
+    s.commit(1.0)
+    info = s.request(0)
+    assert (info.prefilled, info.emitted, info.n_pages, info.state, info.first_token_s) == (100, 0, 7, 0, -1.0)
+    s.next(1.0)
+    s.commit(2.0)
+    info = s.request(0)
+    assert (info.prefilled, info.emitted, info.n_pages, info.state, info.first_token_s) == (150, 1, 10, 1, 2.0)
+    it = s.next(2.0)
+    assert it.decode_req.tolist() == [0] and s.request(0).state == 2
+    s.commit(3.0)
+    assert s.summary()["n_first_token"] == 1 and s.summary()["n_finished"] == 0
+
+
+def test_argument_errors():
+    with pytest.raises(nx.NexusError):
+        nx.Scheduler(7, 100, 2, 16, 64)
+    with pytest.raises(nx.NexusError):
+        nx.Scheduler(nx.PREFILL_SPF, 0, 2, 16, 64)
+    with pytest.raises(nx.NexusError):
+        nx.Scheduler(nx.PREFILL_SPF, 100, 2, 16, 64, gamma=-1.0)
+    with pytest.raises(nx.NexusError):
+        nx.Scheduler(nx.PREFILL_SPF, 100, 2, 16, 4, page_order=[0, 1, 1, 3])
+    s = nx.Scheduler(nx.PREFILL_SPF, 100, 2, 16, 4)
+    with pytest.raises(nx.NexusError):
+        s.submit(0.0, 0, 1)
+    with pytest.raises(nx.NexusError):
+        s.submit(0.0, 60, 6)           # 65 tokens: 5 pages > 4
+    with pytest.raises(nx.NexusError):
+        s.submit(float("nan"), 10, 1)
+    with pytest.raises(nx.NexusError):
+        s.commit(1.0)                  # nothing pending
+    s.submit(0.0, 10, 1)
+    s.next(5.0)
+    with pytest.raises(nx.NexusError):
+        s.next(6.0)                    # previous iteration not committed
+    with pytest.raises(nx.NexusError):
+        s.commit(4.0)                  # ends before it starts
+    s.commit(5.5)
+    with pytest.raises(nx.NexusError):
+        s.request(5)
