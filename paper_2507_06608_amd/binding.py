@@ -214,6 +214,16 @@ class Nexus:
         self._kv_keep = (kp, vp)
         return kv
 
+    def alloc_kv(self, n_pages: int, layers: int):
+        """Zero-filled pools of `n_pages` pages for `layers` layers (all zeros is the same in either page layout)."""
+        s = self.shape
+        per_layer = n_pages * s.n_kv_heads * s.page_size * s.head_dim
+        kp = torch.zeros(layers * per_layer, dtype=torch.bfloat16, device=self.device)
+        vp = torch.zeros(layers * per_layer, dtype=torch.bfloat16, device=self.device)
+        torch.cuda.synchronize(self.device)
+        self._kv_keep = (kp, vp)
+        return KVCache(kp.data_ptr(), vp.data_ptr(), per_layer * 2, n_pages)
+
     def kv_export(self, kv: KVCache, layer: int = 0):
         s = self.shape
         shape = (kv.n_pages, s.n_kv_heads, s.page_size, s.head_dim)

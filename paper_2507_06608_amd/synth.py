@@ -267,3 +267,20 @@ def subset_for_oracle(w: Workload, prefill_reqs: List[int], decode_reqs: List[in
     v_pool = w.v_pool.index_select(0, idx).cpu()
     return Workload(w.name + "_subset", w.shape, w.seed, len(pages), prefill, decode, k_pool, v_pool,
                     notes={"pages": pages})
+
+
+def poisson_trace(seed: int, rate: float, horizon_s: float, prompt_median: float = 1024.0, prompt_sigma: float = 0.8,
+                  prompt_cap: int = 8192, output_median: float = 256.0, output_sigma: float = 0.7,
+                  output_cap: int = 2048) -> List[tuple]:
+    """Requests of the trace-driven configuration: Poisson arrivals at `rate` per second over `horizon_s`, prompt
+    lengths lognormal(median, sigma) capped, output lengths lognormal(median, sigma) capped.  Returns
+    (arrival_s, prompt_len, output_len) tuples in arrival order."""
+    rng = np.random.default_rng([seed, 4242])
+    out, t = [], 0.0
+    while True:
+        t += float(rng.exponential(1.0 / rate))
+        if t >= horizon_s:
+            return out
+        prompt = int(min(prompt_cap, max(1.0, rng.lognormal(np.log(prompt_median), prompt_sigma))))
+        output = int(min(output_cap, max(1.0, rng.lognormal(np.log(output_median), output_sigma))))
+        out.append((t, prompt, output))

@@ -1,0 +1,150 @@
+"""The trace-driven loop on the GPU: scheduler decisions against the oracle's loop, every output of a one-layer
+run against an oracle replay of each request, and the 48-layer 14B-shaped configuration over 200 iterations with
+concurrent == serialized bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import scheduler as sch
+from paper_2507_06608_amd import synth
+from tests.parity_util import assert_close, f32, oracle_model, oracle_weights
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nx():
+    from paper_2507_06608_amd import binding
+    binding.lib()          # fails loudly if the library was not built
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _oracle_loop(policy, trace, budget, cap, ps, n_pages, gamma, max_prefill):
+    loop = sch.Loop(policy, budget, cap, ps, n_pages, gamma=gamma, max_prefill_reqs=max_prefill)
+    for a, p, o in trace:
+        loop.submit(a, p, o)
+    return loop
+
+
+def _replay_request(oracle, m, ow, x_pool, rid, prompt, output, pool_rows):
+    """Layer outputs of one request from its synthetic inputs alone: the prompt in one shot (chunked prefill equals
+    one-shot prefill), then its decode steps in order."""
+    from paper_2507_06608_amd.serve import token_rows
+    n_pages = sch.pages_for(prompt + output - 1, m.page_size)
+    kp = np.zeros((n_pages, m.n_kv_heads, m.page_size, m.head_dim), np.float32)
+    vp = np.zeros_like(kp)
+    table = np.arange(n_pages, dtype=np.int32)[None, :]
+    xp = x_pool[token_rows(rid, 0, prompt, pool_rows)]
+    y_prefill = oracle.layer_prefill(m, ow, xp, np.array([0, prompt], np.int32), np.array([0], np.int32), table, kp, vp)
+    y_decode = []
+    for j in range(output - 1):
+        ctx = prompt + j
+        xd = x_pool[token_rows(rid, ctx, 1, pool_rows)]
+        y_decode.append(oracle.layer_decode(m, ow, xd, np.array([ctx], np.int32), table, kp, vp)[0])
+    return y_prefill, y_decode
+
+
+@pytest.mark.parametrize("shape_name,split", [("tiny", (128, 128)), ("tiny", None)])
+def test_one_layer_loop_against_oracle_replay(nx, oracle, shape_name, split):
+    """A short trace through one layer: prompts of several chunks, a decode pool of 4 that makes requests wait, a KV
+    pool small enough to block admissions.  Decisions must equal the oracle's loop; every prefill row and every
+    decode row the GPU produced must match the oracle's replay of that request."""
+    from paper_2507_06608_amd.serve import TraceRunner
+    print(f"[case] one-layer loop, {shape_name}, split {split}", flush=True)
+    shape = synth.SHAPES[shape_name]
+    rng = np.random.default_rng(5)
+    trace, t = [], 0.0
+    for _ in range(14):
+        t += float(rng.exponential(0.06))
+        trace.append((t, int(min(900, max(1, rng.lognormal(np.log(250.0), 0.8)))), int(rng.integers(1, 13))))
+    budget, cap, n_pages, gamma, max_prefill, dt = 256, 4, 150, 15.0, 4, 0.05
+    w = synth.make_weights(shape, 3)
+    run = TraceRunner(shape, 1, lambda l: w, policy=nx.PREFILL_SPF, token_budget=budget, max_decode_reqs=cap,
+                      n_pages=n_pages, gamma=gamma, max_prefill_reqs=max_prefill, max_positions=1024, split=split, seed=1,
+                      pool_rows=4096, page_order=rng.permutation(n_pages))
+    run.keep_outputs = True
+    run.submit(trace)
+    ref = _oracle_loop(sch.SPF, trace, budget, cap, shape.page_size, n_pages, gamma, max_prefill)
+    n_it = 0
+    while any(r.finish_time is None for r in ref.reqs):
+        it = ref.next(n_it * dt)
+        rec = run.step(n_it * dt, (n_it + 1) * dt)
+        ref.commit((n_it + 1) * dt)
+        assert rec.prefill == it.prefill and rec.decode == it.decode and rec.kv_used_pages == it.kv_used_pages, n_it
+        n_it += 1
+        assert n_it < 2000
+    assert run.sched.summary()["n_finished"] == len(trace)
+    np.testing.assert_array_equal(run.sched.samples(0), ref.ttft())
+
+    m, ow = oracle_model(oracle, shape), oracle_weights(w)
+    x_pool = f32(run.x_pool)
+    replay = {rid: _replay_request(oracle, m, ow, x_pool, rid, p, o, run.pool_rows) for rid, (a, p, o) in enumerate(trace)}
+    n_rows = 0
+    for (i, yp, yd), rec in zip(run.outputs, run.records):
+        off = 0
+        for rid, prefix, n in rec.prefill:
+            assert_close(f"it {i} prefill req {rid} [{prefix}:{prefix + n})", f32(yp[off:off + n]), replay[rid][0][prefix:prefix + n])
+            off += n
+            n_rows += n
+        for j, (rid, ctx) in enumerate(rec.decode):
+            assert_close(f"it {i} decode req {rid} ctx {ctx}", f32(yd[j]), replay[rid][1][ctx - trace[rid][1]])
+            n_rows += 1
+    assert n_rows == sum(p + o - 1 for _, p, o in trace)
+    run.close()
+
+
+def test_cfg4_trace_48_layers_200_iterations(nx):
+    """The trace-driven configuration: 14B-shaped stack of 48 layers, Poisson arrivals at 4 requests/s, lognormal
+    prompt and output lengths, 1024-token chunks, decode pool of 128, 200 iterations on a virtual clock of 50 ms
+    (decisions independent of the hardware).  Decisions equal the oracle's loop; the run on a 160/96 split and the
+    serialized run produce bit-identical outputs in every iteration (checksums of all output rows)."""
+    from paper_2507_06608_amd.serve import TraceRunner
+    print("[case] cfg4 trace, 48 layers, 200 iterations", flush=True)
+    shape = synth.SHAPES["qwen25_14b"]
+    free, _ = torch.cuda.mem_get_info(0)
+    n_pages = 12288
+    need = shape.n_layers * (2 * shape.params_per_layer + n_pages * shape.page_size * shape.kv_dim * 4) + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free device memory, {free >> 30} GiB available")
+    trace = synth.poisson_trace(0, rate=4.0, horizon_s=10.0)
+    budget, cap, gamma, max_prefill, dt, iters = 1024, 128, 15.0, 8, 0.05, 200
+    g = torch.Generator(device="cuda:0")
+
+    def weights(l):
+        g.manual_seed(1000 + l)
+        std = synth.weight_std(shape)
+
+        def mat(r, c):
+            return (torch.randn((r, c), generator=g, device="cuda:0") * std).to(torch.bfloat16)
+
+        def gain():
+            return (1.0 + torch.randn(shape.hidden, generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
+        return {"attn_norm_g": gain(), "w_qkv": mat(shape.n_qkv, shape.hidden), "w_o": mat(shape.hidden, shape.q_dim),
+                "ffn_norm_g": gain(), "w_gate_up": mat(2 * shape.ffn, shape.hidden), "w_down": mat(shape.hidden, shape.ffn)}
+
+    ref = _oracle_loop(sch.SPF, trace, budget, cap, shape.page_size, n_pages, gamma, max_prefill)
+    ref_its = sch.run_virtual(ref, iters, dt)
+    results = {}
+    for name, split in (("split 160/96", (160, 96)), ("serialized", None)):
+        run = TraceRunner(shape, shape.n_layers, weights, policy=nx.PREFILL_SPF, token_budget=budget, max_decode_reqs=cap,
+                          n_pages=n_pages, gamma=gamma, max_prefill_reqs=max_prefill, split=split, seed=2)
+        run.submit(trace)
+        for i in range(iters):
+            rec = run.step(i * dt, (i + 1) * dt, checksum=True)
+            assert rec.prefill == ref_its[i].prefill and rec.decode == ref_its[i].decode, (name, i)
+            if i % 50 == 49:
+                print(f"[cfg4] {name}: {i + 1} iterations", flush=True)
+        rep = run.report()
+        print(f"[cfg4] {name}: {rep['tokens']} tokens in {rep['gpu_seconds']:.2f} s of steps = {rep['tokens_per_s']:.0f} tokens/s, "
+              f"mean step {rep['mean_step_ms']:.1f} ms over {rep['busy_iterations']} busy iterations; virtual-clock TTFT mean "
+              f"{rep['ttft_mean']:.3f} s p95 {rep['ttft_p95']:.3f} s, TBT mean {rep['tbt_mean']:.3f} s", flush=True)
+        mixed = [r.step_ms for r in run.records if r.prefill_tokens and r.decode_reqs]
+        if mixed:
+            print(f"[cfg4] {name}: {len(mixed)} mixed iterations, mean {np.mean(mixed):.1f} ms, max {np.max(mixed):.1f} ms", flush=True)
+        results[name] = [r.checksum for r in run.records]
+        run.close()
+        del run
+        torch.cuda.empty_cache()
+    assert results["split 160/96"] == results["serialized"]
+    assert ref.prefill_tokens > 0 and ref.decode_tokens > 0
