@@ -115,8 +115,8 @@ class Loop:
         self.reserved_total = 0
         self.reqs: List[Request] = []
         self.pool: List[Request] = []
-        self.pending: Optional[Iteration] = None
-        self._pending_prefill: List[Tuple[Request, int]] = []
+        self._pending_prefill: Optional[List[Tuple[Request, int]]] = None
+        self._pending_decode: Optional[List[Request]] = None
         self.prefill_tokens = 0
         self.decode_tokens = 0
 
@@ -131,8 +131,10 @@ class Loop:
         while len(r.pages) < pages_for(tokens, self.page_size):
             r.pages.append(self.free.pop())
 
-    def next(self, now: float) -> Iteration:
-        assert self.pending is None
+    # ---- the two phases tick independently (Sec. 5: separate coroutines, each with its own scheduler); the
+    # ---- coupled iteration below is one tick of each
+    def next_prefill(self, now: float) -> List[Tuple[int, int, int]]:
+        assert self._pending_prefill is None
         waiting = [r for r in self.reqs if r.arrival <= now and r.remaining > 0]
         ordered = self.priority(waiting, now) if self.priority else order_queue(waiting, now, self.policy, self.gamma)
         # admission, in priority order: once a request's lifetime does not fit, no new request is admitted in this
@@ -153,6 +155,11 @@ class Loop:
         for r, take in batch:
             self._grow(r, r.prefilled + take)
             prefill.append((r.rid, r.prefilled, take))
+        self._pending_prefill = batch or None       # an empty batch is not an iteration: nothing to commit
+        return prefill
+
+    def next_decode(self, now: float) -> List[Tuple[int, int]]:
+        assert self._pending_decode is None
         # decode pool: first come (first prefilled), first served
         ready = sorted((r for r in self.reqs if r.ready_time is not None and not r.in_pool and r.finish_time is None),
                        key=lambda r: (r.ready_time, r.arrival, r.rid))
@@ -166,11 +173,15 @@ class Loop:
             ctx = r.prompt_len + r.emitted - 1
             self._grow(r, ctx + 1)
             decode.append((r.rid, ctx))
-        tables = {rid: list(self.reqs[rid].pages) for rid, _, _ in prefill}
-        tables.update({rid: list(self.reqs[rid].pages) for rid, _ in decode})
-        self._pending_prefill = batch
-        self.pending = Iteration(now, prefill, decode, tables, self.n_pages - len(self.free))
-        return self.pending
+        self._pending_decode = list(self.pool) or None
+        return decode
+
+    def page_table(self, rid: int) -> List[int]:
+        return list(self.reqs[rid].pages)
+
+    @property
+    def kv_used_pages(self) -> int:
+        return self.n_pages - len(self.free)
 
     def _finish(self, r: Request, end: float) -> None:
         r.finish_time = end
@@ -179,9 +190,9 @@ class Loop:
         self.reserved_total -= r.reserved
         r.reserved = 0
 
-    def commit(self, end: float) -> None:
-        assert self.pending is not None
-        for r in list(self.pool):
+    def commit_decode(self, end: float) -> None:
+        assert self._pending_decode is not None
+        for r in self._pending_decode:
             r.emitted += 1
             self.decode_tokens += 1
             r.tbt.append(end - r.last_token_time)
@@ -190,6 +201,10 @@ class Loop:
                 self.pool.remove(r)
                 r.in_pool = False
                 self._finish(r, end)
+        self._pending_decode = None
+
+    def commit_prefill(self, end: float) -> None:
+        assert self._pending_prefill is not None
         for r, take in self._pending_prefill:
             r.prefilled += take
             self.prefill_tokens += take
@@ -200,8 +215,21 @@ class Loop:
                     self._finish(r, end)
                 else:
                     r.ready_time = end
-        self.pending = None
-        self._pending_prefill = []
+        self._pending_prefill = None
+
+    # ---- the coupled iteration: both phases start together and the iteration ends when both have
+    def next(self, now: float) -> Iteration:
+        prefill = self.next_prefill(now)
+        decode = self.next_decode(now)
+        tables = {rid: self.page_table(rid) for rid, _, _ in prefill}
+        tables.update({rid: self.page_table(rid) for rid, _ in decode})
+        return Iteration(now, prefill, decode, tables, self.kv_used_pages)
+
+    def commit(self, end: float) -> None:
+        if self._pending_decode is not None:
+            self.commit_decode(end)
+        if self._pending_prefill is not None:
+            self.commit_prefill(end)
 
     # ---- metrics (Sec. 6.1)
     def ttft(self) -> List[float]:

@@ -57,6 +57,26 @@ def test_worked_example_loop_timeline():
     assert len(loop.free) == 64 and loop.reserved_total == 0
 
 
+def test_worked_example_independent_phase_ticks():
+    import pytest
+    g = _golden()
+    loop = sch.Loop(sch.FCFS, budget=100, max_decode=2, page_size=16, n_pages=64)
+    loop.submit(0.0, 150, 4)
+    loop.submit(0.0, 40, 2)
+    loop.submit(0.5, 250, 1)
+    used = []
+    for t, op, *expect in g["C.step"]:
+        got = getattr(loop, op)(float(t))
+        if op.startswith("next"):
+            assert got == _pairs(expect), (t, op)
+        used.append(loop.kv_used_pages)
+    assert used == [int(x) for x in g["C.kv_used"][0]]
+    assert loop.ttft() == pytest.approx([float(x) for x in g["C.ttft"][0]], abs=1e-12)
+    assert loop.tbt() == pytest.approx([float(x) for x in g["C.tbt"][0]], abs=1e-12)
+    assert loop.normalized_latency() == pytest.approx([float(x) for x in g["C.normalized_latency"][0]], abs=1e-12)
+    assert len(loop.free) == 64 and loop.reserved_total == 0
+
+
 def test_limits_of_gamma_are_shortest_first_and_arrival_order():
     rng = random.Random(1)
     reqs = [sch.Request(i, rng.uniform(0, 50), rng.randint(1, 5000), 1, prefilled=0) for i in range(40)]
