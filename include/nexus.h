@@ -201,6 +201,17 @@ int nexus_prefill_chunk(nexus_ctx *ctx, int layer_begin, int layer_end, const ne
 /* Decode phase alone, on the decode stream of the current layout. */
 int nexus_decode_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_decode_batch *db,
                       const nexus_kv_cache *kv);
+
+/*
+ * Completion of the last nexus_prefill_chunk / nexus_decode_step of a phase (nexus_phase), without waiting for the
+ * other phase: the two calls are asynchronous and, on a partitioned layout, run on different streams, so a caller
+ * may keep one loop per phase (Sec. 5) -- launch a phase, poll it, launch its next step -- as long as the two
+ * phases touch different requests' pages.  nexus_phase_query returns 1 when that call's work has completed (or
+ * none was made), 0 while it is running.  nexus_phase_wait blocks until it has and, if elapsed_ms is not NULL,
+ * stores the time between the call's first and last kernel on the GPU's clock.
+ */
+int nexus_phase_query(nexus_ctx *ctx, int phase);
+int nexus_phase_wait(nexus_ctx *ctx, int phase, float *elapsed_ms);
 /*
  * Both phases of one step.  With a partitioned layout they are enqueued on the two CU-masked streams after a
  * common fork event and run concurrently; with the unpartitioned layout they run back to back.  The two
@@ -379,6 +390,15 @@ int nexus_sched_submit(nexus_sched *s, double arrival_s, int32_t prompt_len, int
 int nexus_sched_next(nexus_sched *s, double now_s, nexus_sched_batch *out);
 /* The iteration formed by the last nexus_sched_next completed at end_s (>= its now_s). */
 int nexus_sched_commit(nexus_sched *s, double end_s);
+/*
+ * The two phases may also tick independently (Sec. 5 runs them as separate loops): nexus_sched_next_phase forms the
+ * batch of one phase (nexus_phase) and fills that phase's fields of *out (the other phase's are zeroed),
+ * nexus_sched_commit_phase completes it.  At most one tick per phase is open at a time; an empty batch opens none
+ * and needs no commit.  A request that completes its prompt at a prefill commit joins the pool at the next decode
+ * tick.  Not to be mixed with an open coupled iteration (NEXUS_ESTATE).
+ */
+int nexus_sched_next_phase(nexus_sched *s, int phase, double now_s, nexus_sched_batch *out);
+int nexus_sched_commit_phase(nexus_sched *s, int phase, double end_s);
 int nexus_sched_request(const nexus_sched *s, int32_t id, nexus_sched_request_info *out);
 int nexus_sched_summarize(const nexus_sched *s, nexus_sched_summary *out);
 /* Raw samples: kind 0 = TTFT (by request id), 1 = TBT (in commit order), 2 = normalised latency (by request id).

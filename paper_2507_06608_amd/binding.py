@@ -34,7 +34,8 @@ EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "n
            "nexus_debug_cu_probe", "nexus_cost_latency", "nexus_adjust_partition", "nexus_partition_controller",
            "nexus_cost_fit", "nexus_cost_describe",
            "nexus_sched_create", "nexus_sched_destroy", "nexus_sched_submit", "nexus_sched_next", "nexus_sched_commit",
-           "nexus_sched_request", "nexus_sched_summarize", "nexus_sched_samples")
+           "nexus_sched_request", "nexus_sched_summarize", "nexus_sched_samples", "nexus_sched_next_phase",
+           "nexus_sched_commit_phase", "nexus_phase_query", "nexus_phase_wait")
 
 
 class NexusError(RuntimeError):
@@ -250,6 +251,14 @@ class Nexus:
                                       C.byref(tm) if timing else None))
         return tm
 
+    def phase_done(self, phase: int) -> bool:
+        return bool(_check(lib().nexus_phase_query(self._ctx, phase)))
+
+    def phase_wait(self, phase: int) -> float:
+        ms = C.c_float()
+        _check(lib().nexus_phase_wait(self._ctx, phase, C.byref(ms)))
+        return ms.value
+
     def profile_split(self, pb: DevPrefill, db: DevDecode, kv: KVCache, cand_prefill_cus: Sequence[int], policy: int,
                       alpha: float = 1.3, beta: float = 1.1, repeats: int = 5, layers=(0, 1)):
         n = len(cand_prefill_cus)
@@ -438,13 +447,25 @@ class Scheduler:
     def next(self, now_s: float) -> SchedIteration:
         b = SchedBatchC()
         _check(lib().nexus_sched_next(self._s, C.c_double(now_s), C.byref(b)))
+        return self._iteration(b)
+
+    def _iteration(self, b: SchedBatchC) -> SchedIteration:
         npf, nd = b.n_prefill, b.n_decode
         return SchedIteration(
-            _arr(b.prefill_req, npf), _arr(b.prefill_prefix, npf), _arr(b.prefill_chunk, npf), _arr(b.prefill_cu_chunk, npf + 1),
-            _arr(b.prefill_page_table, npf * b.prefill_max_pages).reshape(npf, b.prefill_max_pages), b.prefill_max_chunk,
+            _arr(b.prefill_req, npf), _arr(b.prefill_prefix, npf), _arr(b.prefill_chunk, npf), _arr(b.prefill_cu_chunk, npf + 1 if b.prefill_cu_chunk else 0),
+            _arr(b.prefill_page_table, npf * b.prefill_max_pages).reshape(npf, max(b.prefill_max_pages, 1)), b.prefill_max_chunk,
             b.prefill_max_total_len, _arr(b.decode_req, nd), _arr(b.decode_ctx, nd),
-            _arr(b.decode_page_table, nd * b.decode_max_pages).reshape(nd, b.decode_max_pages), b.decode_max_ctx,
+            _arr(b.decode_page_table, nd * b.decode_max_pages).reshape(nd, max(b.decode_max_pages, 1)), b.decode_max_ctx,
             b.kv_used_pages, b.kv_total_pages)
+
+    def next_phase(self, phase: int, now_s: float) -> SchedIteration:
+        """One phase's tick; the other phase's arrays come back empty."""
+        b = SchedBatchC()
+        _check(lib().nexus_sched_next_phase(self._s, phase, C.c_double(now_s), C.byref(b)))
+        return self._iteration(b)
+
+    def commit_phase(self, phase: int, end_s: float):
+        _check(lib().nexus_sched_commit_phase(self._s, phase, C.c_double(end_s)))
 
     def commit(self, end_s: float):
         _check(lib().nexus_sched_commit(self._s, C.c_double(end_s)))

@@ -90,6 +90,8 @@ struct nexus_ctx {
     long use_clock = 0;
     bool bits_xcd_major = false;  // CU-mask bit order (see make_mask)
     hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr, ev_sd1 = nullptr;
+    hipEvent_t ev_ph0[2] = {nullptr, nullptr}, ev_ph1[2] = {nullptr, nullptr};  // start / end of the last single-phase call
+    bool ph_recorded[2] = {false, false};
     // tracing
     int trace_phase = -1, trace_kernel = -1;
     std::vector<TraceRec> trace_pool;
@@ -592,7 +594,7 @@ void nexus_destroy(nexus_ctx *c) {
     }
     (void)hipFree(c->rope_tab);
     (void)hipFree(c->probe_counts);
-    for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_sd1})
+    for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_sd1, c->ev_ph0[0], c->ev_ph0[1], c->ev_ph1[0], c->ev_ph1[1]})
         if (e) (void)hipEventDestroy(e);
     for (auto &t : c->trace_pool) (void)hipEventDestroy(t.a), (void)hipEventDestroy(t.b);
     delete c;
@@ -681,7 +683,7 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         const char *tiles = getenv("NEXUS_GEMM_TILES");
         c->allow_p256 = !(tiles && !strcmp(tiles, "128"));
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
-        for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_sd1})
+        for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_sd1, &c->ev_ph0[0], &c->ev_ph0[1], &c->ev_ph1[0], &c->ev_ph1[1]})
             if (hipEventCreateWithFlags(e, hipEventDisableSystemFence) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
         if (rc) break;
         if ((rc = alloc_phase_ws(c, NEXUS_PHASE_PREFILL, limits->max_prefill_tokens, limits->max_prefill_reqs))) break;
@@ -836,12 +838,22 @@ static PhaseRun make_run(nexus_ctx *c, int phase, const nexus_prefill_batch *pb,
     return r;
 }
 
+// A phase on its own: bracketed by events on the phase's stream so that the caller can poll for its completion
+// and read its duration while the other phase keeps running.
+static int run_single_phase(nexus_ctx *c, const PhaseRun &r, int lb, int le) {
+    HIP_TRY(hipEventRecord(c->ev_ph0[r.phase], r.s));
+    NX_TRY(run_phase(r, lb, le));
+    HIP_TRY(hipEventRecord(c->ev_ph1[r.phase], r.s));
+    c->ph_recorded[r.phase] = true;
+    return NEXUS_OK;
+}
+
 int nexus_prefill_chunk(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_kv_cache *kv) {
     NX_TRY(check_layers(c, lb, le));
     NX_TRY(check_kv(c, kv, le));
     NX_TRY(check_prefill(c, pb));
     DeviceGuard dg(c->device);
-    return run_phase(make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le);
+    return run_single_phase(c, make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le);
 }
 
 int nexus_decode_step(nexus_ctx *c, int lb, int le, const nexus_decode_batch *db, const nexus_kv_cache *kv) {
@@ -849,7 +861,28 @@ int nexus_decode_step(nexus_ctx *c, int lb, int le, const nexus_decode_batch *db
     NX_TRY(check_kv(c, kv, le));
     NX_TRY(check_decode(c, db));
     DeviceGuard dg(c->device);
-    return run_phase(make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le);
+    return run_single_phase(c, make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le);
+}
+
+int nexus_phase_query(nexus_ctx *c, int phase) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    if (phase != NEXUS_PHASE_PREFILL && phase != NEXUS_PHASE_DECODE) return fail(NEXUS_EINVAL, "unknown phase %d", phase);
+    if (!c->ph_recorded[phase]) return 1;
+    DeviceGuard dg(c->device);
+    const hipError_t e = hipEventQuery(c->ev_ph1[phase]);
+    if (e == hipSuccess) return 1;
+    if (e == hipErrorNotReady) return 0;
+    return fail(NEXUS_EHIP, "hipEventQuery failed: %s", hipGetErrorString(e));
+}
+
+int nexus_phase_wait(nexus_ctx *c, int phase, float *elapsed_ms) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    if (phase != NEXUS_PHASE_PREFILL && phase != NEXUS_PHASE_DECODE) return fail(NEXUS_EINVAL, "unknown phase %d", phase);
+    if (!c->ph_recorded[phase]) return fail(NEXUS_ESTATE, "no single-phase call has been made for this phase");
+    DeviceGuard dg(c->device);
+    HIP_TRY(hipEventSynchronize(c->ev_ph1[phase]));
+    if (elapsed_ms) HIP_TRY(hipEventElapsedTime(elapsed_ms, c->ev_ph0[phase], c->ev_ph1[phase]));
+    return NEXUS_OK;
 }
 
 int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,

@@ -53,16 +53,41 @@ int nexus_sched_submit(nexus_sched *s, double arrival_s, int32_t prompt_len, int
 int nexus_sched_next(nexus_sched *s, double now_s, nexus_sched_batch *out) {
     if (!s || !out) return fail(NEXUS_EINVAL, "null argument");
     if (!std::isfinite(now_s)) return fail(NEXUS_EINVAL, "time must be finite");
-    if (s->impl.pending()) return fail(NEXUS_ESTATE, "the previous iteration has not been committed");
+    if (s->impl.iteration_open() || s->impl.pending(NEXUS_PHASE_PREFILL) || s->impl.pending(NEXUS_PHASE_DECODE))
+        return fail(NEXUS_ESTATE, "the previous iteration has not been committed");
+    *out = nexus_sched_batch{};
     s->impl.next(now_s, out);
     return NEXUS_OK;
 }
 
 int nexus_sched_commit(nexus_sched *s, double end_s) {
     if (!s) return fail(NEXUS_EINVAL, "null scheduler");
-    if (!s->impl.pending()) return fail(NEXUS_ESTATE, "no iteration to commit");
-    if (!(end_s >= s->impl.pending_now())) return fail(NEXUS_EINVAL, "iteration ends (%g) before it starts (%g)", end_s, s->impl.pending_now());
+    if (!s->impl.iteration_open()) return fail(NEXUS_ESTATE, "no iteration to commit");
+    if (!(end_s >= s->impl.pending_now(NEXUS_PHASE_PREFILL))) return fail(NEXUS_EINVAL, "iteration ends (%g) before it starts (%g)", end_s, s->impl.pending_now(NEXUS_PHASE_PREFILL));
     s->impl.commit(end_s);
+    return NEXUS_OK;
+}
+
+int nexus_sched_next_phase(nexus_sched *s, int phase, double now_s, nexus_sched_batch *out) {
+    if (!s || !out) return fail(NEXUS_EINVAL, "null argument");
+    if (phase != NEXUS_PHASE_PREFILL && phase != NEXUS_PHASE_DECODE) return fail(NEXUS_EINVAL, "unknown phase %d", phase);
+    if (!std::isfinite(now_s)) return fail(NEXUS_EINVAL, "time must be finite");
+    if (s->impl.iteration_open()) return fail(NEXUS_ESTATE, "a coupled iteration is open");
+    if (s->impl.pending(phase)) return fail(NEXUS_ESTATE, "the previous tick of this phase has not been committed");
+    *out = nexus_sched_batch{};
+    if (phase == NEXUS_PHASE_PREFILL) s->impl.next_prefill(now_s, out);
+    else s->impl.next_decode(now_s, out);
+    return NEXUS_OK;
+}
+
+int nexus_sched_commit_phase(nexus_sched *s, int phase, double end_s) {
+    if (!s) return fail(NEXUS_EINVAL, "null scheduler");
+    if (phase != NEXUS_PHASE_PREFILL && phase != NEXUS_PHASE_DECODE) return fail(NEXUS_EINVAL, "unknown phase %d", phase);
+    if (s->impl.iteration_open()) return fail(NEXUS_ESTATE, "a coupled iteration is open");
+    if (!s->impl.pending(phase)) return fail(NEXUS_ESTATE, "this phase has no tick to commit");
+    if (!(end_s >= s->impl.pending_now(phase))) return fail(NEXUS_EINVAL, "tick ends (%g) before it starts (%g)", end_s, s->impl.pending_now(phase));
+    if (phase == NEXUS_PHASE_PREFILL) s->impl.commit_prefill(end_s);
+    else s->impl.commit_decode(end_s);
     return NEXUS_OK;
 }
 

@@ -3,9 +3,10 @@
 // progress, page allocation from a free list, token times -- that turns a stream of requests into the batch
 // descriptors the step calls take.  Plain C++ on host memory; no GPU work.
 //
-// One iteration is next(now) -> the caller runs the step -> commit(end).  A request emits its first token when its
-// last prompt chunk commits, then waits for a place in the decode pool (first prefilled, first served) and emits
-// one token per committed iteration until it has produced output_len tokens.
+// One tick of a phase is next_<phase>(now) -> the caller runs that phase's step -> commit_<phase>(end); the coupled
+// iteration next(now) / commit(end) is one tick of each.  A request emits its first token when its last prompt
+// chunk commits, then waits for a place in the decode pool (first prefilled, first served) and emits one token
+// per committed decode tick until it has produced output_len tokens.
 #pragma once
 #include <algorithm>
 #include <cmath>
@@ -37,8 +38,6 @@ public:
     int32_t pages_for(int64_t tokens) const { return (int32_t)((tokens + cfg_.page_size - 1) / cfg_.page_size); }
     int32_t lifetime_pages(int32_t prompt, int32_t output) const { return pages_for((int64_t)prompt + output - 1); }
     int32_t total_pages() const { return cfg_.n_pages; }
-    bool pending() const { return pending_; }
-    double pending_now() const { return now_; }
     size_t size() const { return reqs_.size(); }
     const Req &request(size_t i) const { return reqs_[i]; }
     int64_t prefill_tokens() const { return prefill_tokens_; }
@@ -53,9 +52,13 @@ public:
         return (int32_t)reqs_.size() - 1;
     }
 
-    // Forms the two batches of the iteration that starts at `now`.
-    void next(double now, nexus_sched_batch *out) {
-        now_ = now;
+    // The two phases tick independently (Sec. 5: separate coroutines, each with its own scheduler).  An empty
+    // batch is not pending: there is nothing to commit.
+    bool pending(int phase) const { return phase == NEXUS_PHASE_PREFILL ? prefill_pending_ : decode_pending_; }
+    double pending_now(int phase) const { return phase == NEXUS_PHASE_PREFILL ? prefill_now_ : decode_now_; }
+
+    void next_prefill(double now, nexus_sched_batch *out) {
+        prefill_now_ = now;
         // -- prefill queue: visible, not fully prefilled, in policy order (Alg. 2: score, sort)
         std::vector<Key> order;
         for (int32_t id : waiting_) {
@@ -97,6 +100,12 @@ public:
             if (take < remaining) break;
         }
         for (size_t i = 0; i < p_req_.size(); ++i) grow(reqs_[p_req_[i]], (int64_t)p_prefix_[i] + p_chunk_[i]);
+        prefill_pending_ = !p_req_.empty();
+        describe_prefill(out, total);
+    }
+
+    void next_decode(double now, nexus_sched_batch *out) {
+        decode_now_ = now;
         // -- decode pool: first prefilled, first served
         std::vector<Key> ready;
         for (int32_t id : ready_) ready.push_back({reqs_[id].ready_s, reqs_[id].arrival, id});
@@ -113,12 +122,12 @@ public:
             grow(r, (int64_t)ctx + 1);
             d_req_.push_back(id), d_ctx_.push_back(ctx);
         }
-        pending_ = true;
-        describe(out, total);
+        decode_pending_ = !d_req_.empty();
+        describe_decode(out);
     }
 
-    // Applies the iteration formed by the last next(): progress, token times, finished requests release their pages.
-    void commit(double end) {
+    // Token times and progress of a completed tick; finished requests release their pages.
+    void commit_decode(double end) {
         std::vector<int32_t> still;
         for (int32_t id : pool_) {
             Req &r = reqs_[id];
@@ -129,6 +138,11 @@ public:
             else still.push_back(id);
         }
         pool_.swap(still);
+        d_req_.clear(), d_ctx_.clear();
+        decode_pending_ = false;
+    }
+
+    void commit_prefill(double end) {
         for (size_t i = 0; i < p_req_.size(); ++i) {
             Req &r = reqs_[p_req_[i]];
             r.prefilled += p_chunk_[i], prefill_tokens_ += p_chunk_[i];
@@ -139,8 +153,21 @@ public:
                 else r.ready = true, r.ready_s = end, ready_.push_back(p_req_[i]);
             }
         }
-        p_req_.clear(), p_prefix_.clear(), p_chunk_.clear(), d_req_.clear(), d_ctx_.clear();
-        pending_ = false;
+        p_req_.clear(), p_prefix_.clear(), p_chunk_.clear();
+        prefill_pending_ = false;
+    }
+
+    // The coupled iteration: one tick of each phase, started together and committed together.
+    bool iteration_open() const { return iteration_open_; }
+    void next(double now, nexus_sched_batch *out) {
+        next_prefill(now, out);
+        next_decode(now, out);
+        iteration_open_ = true;
+    }
+    void commit(double end) {
+        if (decode_pending_) commit_decode(end);
+        if (prefill_pending_) commit_prefill(end);
+        iteration_open_ = false;
     }
 
 private:
@@ -170,26 +197,29 @@ private:
         for (size_t i = 0; i < ids.size(); ++i) std::copy(reqs[ids[i]].pages.begin(), reqs[ids[i]].pages.end(), t.begin() + i * w);
         *width = (int32_t)w;
     }
-    void describe(nexus_sched_batch *b, int32_t total) {
+    void describe_prefill(nexus_sched_batch *b, int32_t total) {
         p_cu_.assign(p_req_.size() + 1, 0);
-        int32_t max_chunk = 0, max_total = 0, max_ctx = 0;
+        int32_t max_chunk = 0, max_total = 0;
         for (size_t i = 0; i < p_req_.size(); ++i) {
             p_cu_[i + 1] = p_cu_[i] + p_chunk_[i];
             max_chunk = std::max(max_chunk, p_chunk_[i]);
             max_total = std::max(max_total, p_prefix_[i] + p_chunk_[i]);
         }
-        for (int32_t c : d_ctx_) max_ctx = std::max(max_ctx, c);
         table(reqs_, p_req_, p_table_, &b->prefill_max_pages);
-        table(reqs_, d_req_, d_table_, &b->decode_max_pages);
         b->n_prefill = (int32_t)p_req_.size(), b->prefill_tokens = total;
         b->prefill_req = p_req_.data(), b->prefill_prefix = p_prefix_.data(), b->prefill_chunk = p_chunk_.data();
         b->prefill_cu_chunk = p_cu_.data(), b->prefill_page_table = p_table_.data();
         b->prefill_max_chunk = max_chunk, b->prefill_max_total_len = max_total;
+        b->kv_used_pages = cfg_.n_pages - (int32_t)free_.size(), b->kv_total_pages = cfg_.n_pages;
+    }
+    void describe_decode(nexus_sched_batch *b) {
+        int32_t max_ctx = 0;
+        for (int32_t c : d_ctx_) max_ctx = std::max(max_ctx, c);
+        table(reqs_, d_req_, d_table_, &b->decode_max_pages);
         b->n_decode = (int32_t)d_req_.size();
         b->decode_req = d_req_.data(), b->decode_ctx = d_ctx_.data(), b->decode_page_table = d_table_.data();
         b->decode_max_ctx = max_ctx;
-        b->kv_used_pages = cfg_.n_pages - (int32_t)free_.size();
-        b->kv_total_pages = cfg_.n_pages;
+        b->kv_used_pages = cfg_.n_pages - (int32_t)free_.size(), b->kv_total_pages = cfg_.n_pages;
     }
 
     nexus_sched_config cfg_;
@@ -198,8 +228,8 @@ private:
     std::vector<int32_t> p_req_, p_prefix_, p_chunk_, p_cu_, p_table_, d_req_, d_ctx_, d_table_;
     std::vector<double> tbt_;
     int64_t reserved_total_ = 0, prefill_tokens_ = 0, decode_tokens_ = 0;
-    double now_ = 0;
-    bool pending_ = false;
+    double prefill_now_ = 0, decode_now_ = 0;
+    bool prefill_pending_ = false, decode_pending_ = false, iteration_open_ = false;
 };
 
 // Nearest-rank percentile (the smallest sample with at least q of the samples at or below it); 0 for no samples.

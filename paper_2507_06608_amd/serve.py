@@ -58,9 +58,14 @@ class TraceRunner:
             self.ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
         else:
             self.ctx.set_cu_split(*split)
+        self.split = split
         g = torch.Generator(device=self.ctx.device)
         g.manual_seed(seed * 104729 + 71)
         self.x_pool = torch.randn((pool_rows, shape.hidden), generator=g, device=self.ctx.device).to(torch.bfloat16)
+        torch.cuda.synchronize(self.ctx.device)
+        # CU-masked streams are blocking streams: anything issued on the NULL stream (torch's default) would wait
+        # for a running phase and hold the next one back.  The loop's own copies and gathers go to a side stream.
+        self.side = torch.cuda.Stream(device=self.ctx.device)
         self.pool_rows = pool_rows
         self.records: List[IterationRecord] = []
         self.keep_outputs = False
@@ -74,20 +79,27 @@ class TraceRunner:
         idx = torch.from_numpy(rows).to(self.ctx.device)
         return self.x_pool.index_select(0, idx)
 
+    def _prefill_batch(self, it):
+        with torch.cuda.stream(self.side):
+            rows = np.concatenate([token_rows(int(r), int(p), int(n), self.pool_rows)
+                                   for r, p, n in zip(it.prefill_req, it.prefill_prefix, it.prefill_chunk)])
+            b = nx.DevPrefill(PrefillBatch(self._gather(rows), it.prefill_cu_chunk, it.prefill_prefix, it.prefill_page_table),
+                              self.ctx.device)
+        return b
+
+    def _decode_batch(self, it):
+        with torch.cuda.stream(self.side):
+            rows = (it.decode_req.astype(np.int64) * ROW_STRIDE + it.decode_ctx) % self.pool_rows
+            b = nx.DevDecode(DecodeBatch(self._gather(rows), it.decode_ctx, it.decode_page_table), self.ctx.device)
+        return b
+
     def step(self, now_s: float, end_s: Optional[float] = None, checksum: bool = False) -> IterationRecord:
         """One iteration starting at now_s.  With end_s the scheduler is told the iteration ended then, whatever
         the step took (a virtual clock: decisions do not depend on the hardware); otherwise at now_s + measured."""
         it = self.sched.next(now_s)
-        dev = self.ctx.device
-        pb = db = None
-        if len(it.prefill_req):
-            rows = np.concatenate([token_rows(int(r), int(p), int(n), self.pool_rows)
-                                   for r, p, n in zip(it.prefill_req, it.prefill_prefix, it.prefill_chunk)])
-            pb = nx.DevPrefill(PrefillBatch(self._gather(rows), it.prefill_cu_chunk, it.prefill_prefix, it.prefill_page_table), dev)
-        if len(it.decode_req):
-            rows = np.array([token_rows(int(r), int(c), 1, self.pool_rows)[0] for r, c in zip(it.decode_req, it.decode_ctx)])
-            db = nx.DevDecode(DecodeBatch(self._gather(rows), it.decode_ctx, it.decode_page_table), dev)
-        torch.cuda.synchronize(dev)
+        pb = self._prefill_batch(it) if len(it.prefill_req) else None
+        db = self._decode_batch(it) if len(it.decode_req) else None
+        self.side.synchronize()
         layers = (0, self.n_layers)
         t0 = time.perf_counter()
         if pb is not None and db is not None:
@@ -107,9 +119,12 @@ class TraceRunner:
         if checksum:
             def h(t):
                 return 0 if t is None else int(t.y.view(torch.int16).to(torch.int64).sum().item())
-            rec.checksum = (h(pb), h(db))
+            with torch.cuda.stream(self.side):
+                rec.checksum = (h(pb), h(db))
         if self.keep_outputs:
-            self.outputs.append((len(self.records), None if pb is None else pb.y.clone(), None if db is None else db.y.clone()))
+            with torch.cuda.stream(self.side):
+                self.outputs.append((len(self.records), None if pb is None else pb.y.clone(), None if db is None else db.y.clone()))
+            self.side.synchronize()
         self.records.append(rec)
         return rec
 
@@ -122,6 +137,22 @@ class TraceRunner:
             else:
                 self.step(self.records[-1].end_s if self.records else 0.0, None, checksum)
         return self.records
+
+    def run_until_done(self, arrivals: Sequence[float], max_iterations: int = 100000):
+        """Coupled iterations on the measured clock until every submitted request has finished; the clock jumps to
+        the next arrival when an iteration finds nothing to do."""
+        arrivals = sorted(arrivals)
+        now = 0.0
+        for _ in range(max_iterations):
+            rec = self.step(now)
+            now = rec.end_s
+            if not rec.prefill_tokens and not rec.decode_reqs:
+                if self.sched.summary()["n_finished"] == len(arrivals):
+                    return self.records
+                later = [a for a in arrivals if a > now]
+                if later:
+                    now = later[0]
+        raise RuntimeError("trace did not finish")
 
     def report(self) -> dict:
         """Throughput over the measured step times plus the scheduler's serving metrics on its own clock."""
@@ -137,3 +168,110 @@ class TraceRunner:
     def close(self):
         self.sched.close()
         self.ctx.close()
+
+
+class DecoupledRunner(TraceRunner):
+    """The two phases as independent loops on one host thread (Sec. 5 runs them as separate coroutines): each phase
+    launches its next step as soon as its previous one has completed, whatever the other phase is doing, so decode
+    steps are not stretched to the length of a prefill chunk.  Needs a partitioned layout (two streams).
+
+    The scheduler's clock is the host's, started at the first call, and jumps over stretches in which neither
+    phase has anything to do (to the next arrival)."""
+
+    def __init__(self, *args, **kwargs):
+        self.borrow_idle_cus = kwargs.pop("borrow_idle_cus", True)
+        super().__init__(*args, **kwargs)
+        assert self.split is not None, "independent phase loops need a partitioned layout"
+        self.calls: List[tuple] = []     # (op, phase, time, batch) in call order, for replay against another scheduler
+        self.phase_records = {nx.PHASE_PREFILL: [], nx.PHASE_DECODE: []}   # (start_s, end_s, gpu_ms, tokens)
+
+    def _launch(self, phase: int, it, other_idle: bool) -> tuple:
+        layers = (0, self.n_layers)
+        # a phase that has the GPU to itself takes every CU (switching between the partitioned pair and the
+        # unpartitioned stream costs nothing); the other phase may start on its own share before this step ends
+        if self.borrow_idle_cus and other_idle:
+            self.ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
+        else:
+            self.ctx.set_cu_split(*self.split)
+        if phase == nx.PHASE_PREFILL:
+            b = self._prefill_batch(it)
+            self.side.synchronize()          # the gather only; the other phase keeps running
+            self.ctx.prefill_chunk(b, self.kv, layers=layers)
+            desc = list(zip(it.prefill_req.tolist(), it.prefill_prefix.tolist(), it.prefill_chunk.tolist()))
+            return b, desc, int(it.prefill_chunk.sum())
+        b = self._decode_batch(it)
+        self.side.synchronize()
+        self.ctx.decode_step(b, self.kv, layers=layers)
+        return b, list(zip(it.decode_req.tolist(), it.decode_ctx.tolist())), len(it.decode_req)
+
+    def run_decoupled(self, arrivals: Sequence[float], max_wall_s: float = 120.0):
+        """Runs until every submitted request has finished.  `arrivals`: the arrival times that were submitted
+        (to know where to jump when idle)."""
+        arrivals = sorted(arrivals)
+        t0, skipped = time.perf_counter(), 0.0
+        busy = {nx.PHASE_PREFILL: None, nx.PHASE_DECODE: None}
+        n_total = len(arrivals)
+        while True:
+            for phase in (nx.PHASE_DECODE, nx.PHASE_PREFILL):
+                if busy[phase] is not None and self.ctx.phase_done(phase):
+                    end = time.perf_counter() - t0 + skipped
+                    gpu_ms = self.ctx.phase_wait(phase)
+                    self.sched.commit_phase(phase, end)
+                    b, desc, start, tokens = busy[phase]
+                    self.calls.append(("commit", phase, end, None))
+                    self.phase_records[phase].append((start, end, gpu_ms, tokens))
+                    if self.keep_outputs:
+                        with torch.cuda.stream(self.side):
+                            self.outputs.append((phase, desc, b.y.clone()))
+                        self.side.synchronize()
+                    busy[phase] = None
+            work = {}
+            for phase in (nx.PHASE_DECODE, nx.PHASE_PREFILL):
+                if busy[phase] is None:
+                    now = time.perf_counter() - t0 + skipped
+                    it = self.sched.next_phase(phase, now)
+                    n = len(it.prefill_req) if phase == nx.PHASE_PREFILL else len(it.decode_req)
+                    if n:
+                        work[phase] = (it, now)
+                    else:
+                        self.calls.append(("next", phase, now, []))
+            for phase, (it, now) in work.items():
+                alone = busy[1 - phase] is None and (1 - phase) not in work
+                b, desc, tokens = self._launch(phase, it, alone)
+                busy[phase] = (b, desc, now, tokens)
+                self.calls.append(("next", phase, now, desc))
+            if busy[nx.PHASE_PREFILL] is None and busy[nx.PHASE_DECODE] is None:
+                if self.sched.summary()["n_finished"] == n_total:
+                    break
+                now = time.perf_counter() - t0 + skipped
+                later = [a for a in arrivals if a > now]
+                if later:
+                    skipped += later[0] - now
+            if time.perf_counter() - t0 > max_wall_s:
+                raise RuntimeError("decoupled run exceeded its wall-clock limit")
+        self.ctx.sync()
+
+    def report_decoupled(self) -> dict:
+        out = self.sched.summary()
+        for phase, name in ((nx.PHASE_PREFILL, "prefill"), (nx.PHASE_DECODE, "decode")):
+            recs = self.phase_records[phase]
+            out[f"{name}_steps"] = len(recs)
+            out[f"{name}_mean_gpu_ms"] = float(np.mean([r[2] for r in recs])) if recs else 0.0
+            out[f"{name}_mean_wall_ms"] = float(np.mean([(r[1] - r[0]) * 1e3 for r in recs])) if recs else 0.0
+            out[f"{name}_max_gpu_ms"] = float(np.max([r[2] for r in recs])) if recs else 0.0
+            out[f"{name}_max_wall_ms"] = float(np.max([(r[1] - r[0]) * 1e3 for r in recs])) if recs else 0.0
+        allrec = self.phase_records[nx.PHASE_PREFILL] + self.phase_records[nx.PHASE_DECODE]
+        if allrec:
+            # the GPU is busy from the first launch to the last completion, minus the stretches with nothing in flight
+            spans = sorted((r[0], r[1]) for r in allrec)
+            busy_s, cur0, cur1 = 0.0, spans[0][0], spans[0][1]
+            for a, b in spans[1:]:
+                if a > cur1:
+                    busy_s += cur1 - cur0
+                    cur0, cur1 = a, b
+                else:
+                    cur1 = max(cur1, b)
+            busy_s += cur1 - cur0
+            tokens = sum(r[3] for r in allrec)
+            out.update({"tokens": tokens, "gpu_seconds": busy_s, "tokens_per_s": tokens / busy_s})
+        return out

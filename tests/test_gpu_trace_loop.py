@@ -148,3 +148,128 @@ def test_cfg4_trace_48_layers_200_iterations(nx):
         torch.cuda.empty_cache()
     assert results["split 160/96"] == results["serialized"]
     assert ref.prefill_tokens > 0 and ref.decode_tokens > 0
+
+
+def test_decoupled_phase_loops_one_layer_against_oracle(nx, oracle):
+    """The two phases ticking independently on their own streams.  The order of ticks depends on how long the GPU
+    takes, so the decisions are checked by replaying the logged calls, with their times, on the oracle's loop; the
+    outputs do not depend on timing at all and are checked row by row against the oracle replay of each request."""
+    from paper_2507_06608_amd.serve import DecoupledRunner
+    print("[case] decoupled one-layer loop, tiny", flush=True)
+    shape = synth.SHAPES["tiny"]
+    rng = np.random.default_rng(6)
+    trace, t = [], 0.0
+    for _ in range(16):
+        t += float(rng.exponential(0.002))
+        trace.append((t, int(min(900, max(1, rng.lognormal(np.log(250.0), 0.8)))), int(rng.integers(1, 25))))
+    budget, cap, n_pages, gamma, max_prefill = 128, 4, 170, 15.0, 4
+    w = synth.make_weights(shape, 3)
+    run = DecoupledRunner(shape, 1, lambda l: w, policy=nx.PREFILL_SPF, token_budget=budget, max_decode_reqs=cap,
+                          n_pages=n_pages, gamma=gamma, max_prefill_reqs=max_prefill, max_positions=1024, split=(128, 128),
+                          seed=1, pool_rows=4096, page_order=rng.permutation(n_pages))
+    run.keep_outputs = True
+    run.submit(trace)
+    run.run_decoupled([a for a, _, _ in trace], max_wall_s=60.0)
+    assert run.sched.summary()["n_finished"] == len(trace)
+
+    ref = _oracle_loop(sch.SPF, trace, budget, cap, shape.page_size, n_pages, gamma, max_prefill)
+    overlapped = 0
+    open_ticks = set()
+    for op, phase, t_call, desc in run.calls:
+        if op == "next":
+            got = ref.next_prefill(t_call) if phase == nx.PHASE_PREFILL else ref.next_decode(t_call)
+            assert got == desc, (op, phase, t_call)
+            if desc:
+                open_ticks.add(phase)
+                overlapped += len(open_ticks) == 2
+        else:
+            (ref.commit_prefill if phase == nx.PHASE_PREFILL else ref.commit_decode)(t_call)
+            open_ticks.discard(phase)
+    assert all(r.finish_time is not None for r in ref.reqs)
+    np.testing.assert_array_equal(run.sched.samples(0), ref.ttft())
+    np.testing.assert_array_equal(np.sort(run.sched.samples(1)), np.sort(ref.tbt()))
+    print(f"[decoupled] {len(run.calls)} scheduler calls, {overlapped} ticks launched while the other phase was in flight", flush=True)
+    assert overlapped > 0
+
+    m, ow = oracle_model(oracle, shape), oracle_weights(w)
+    x_pool = f32(run.x_pool)
+    replay = {rid: _replay_request(oracle, m, ow, x_pool, rid, p, o, run.pool_rows) for rid, (a, p, o) in enumerate(trace)}
+    n_rows = 0
+    for phase, desc, y in run.outputs:
+        if phase == nx.PHASE_PREFILL:
+            off = 0
+            for rid, prefix, n in desc:
+                assert_close(f"prefill req {rid} [{prefix}:{prefix + n})", f32(y[off:off + n]), replay[rid][0][prefix:prefix + n])
+                off += n
+                n_rows += n
+        else:
+            for j, (rid, ctx) in enumerate(desc):
+                assert_close(f"decode req {rid} ctx {ctx}", f32(y[j]), replay[rid][1][ctx - trace[rid][1]])
+                n_rows += 1
+    assert n_rows == sum(p + o - 1 for _, p, o in trace)
+    run.close()
+
+
+@pytest.mark.parametrize("rate,horizon", [(4.0, 5.0), (12.0, 3.0)])
+def test_cfg4_decoupled_loops_cut_time_between_tokens(nx, rate, horizon):
+    """The 48-layer 14B-shaped stack on the measured clock, three ways: coupled iterations on the unpartitioned
+    GPU (prefill then decode, the serialized baseline), coupled iterations on a 160/96 split, and the two phases
+    as independent loops on the same split.  What the independent loops are for (Sec. 5): a decode step no longer
+    lasts as long as the prefill chunk next to it."""
+    from paper_2507_06608_amd.serve import DecoupledRunner, TraceRunner
+    print(f"[case] cfg4 on the measured clock: coupled vs decoupled, {rate} requests/s", flush=True)
+    shape = synth.SHAPES["qwen25_14b"]
+    n_pages = 12288
+    free, _ = torch.cuda.mem_get_info(0)
+    need = shape.n_layers * (2 * shape.params_per_layer + n_pages * shape.page_size * shape.kv_dim * 4) + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free device memory, {free >> 30} GiB available")
+    trace = synth.poisson_trace(1, rate=rate, horizon_s=horizon, output_cap=384)
+    arrivals = [a for a, _, _ in trace]
+    g = torch.Generator(device="cuda:0")
+
+    def weights(l):
+        g.manual_seed(1000 + l)
+        std = synth.weight_std(shape)
+
+        def mat(r, c):
+            return (torch.randn((r, c), generator=g, device="cuda:0") * std).to(torch.bfloat16)
+
+        def gain():
+            return (1.0 + torch.randn(shape.hidden, generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
+        return {"attn_norm_g": gain(), "w_qkv": mat(shape.n_qkv, shape.hidden), "w_o": mat(shape.hidden, shape.q_dim),
+                "ffn_norm_g": gain(), "w_gate_up": mat(2 * shape.ffn, shape.hidden), "w_down": mat(shape.hidden, shape.ffn)}
+
+    common = dict(policy=nx.PREFILL_SPF, token_budget=1024, max_decode_reqs=128, n_pages=n_pages, gamma=15.0,
+                  max_prefill_reqs=8, seed=2)
+    out = {}
+    for name, cls, split in (("coupled, unpartitioned", TraceRunner, None), ("coupled, 160/96", TraceRunner, (160, 96)),
+                             ("decoupled, 160/96", DecoupledRunner, (160, 96))):
+        run = cls(shape, shape.n_layers, weights, split=split, **common)
+        run.submit(trace)
+        if cls is DecoupledRunner:
+            run.run_decoupled(arrivals, max_wall_s=150.0)
+            rep = run.report_decoupled()
+        else:
+            run.run_until_done(arrivals)
+            rep = run.report()
+        assert rep["n_finished"] == len(trace)
+        out[name] = rep
+        print(f"[cfg4 measured {rate}/s] {name}: TTFT mean {rep['ttft_mean'] * 1e3:.0f} ms p95 {rep['ttft_p95'] * 1e3:.0f} ms | TBT mean "
+              f"{rep['tbt_mean'] * 1e3:.1f} ms p95 {rep['tbt_p95'] * 1e3:.1f} ms p99 {rep['tbt_p99'] * 1e3:.1f} ms | normalised latency mean "
+              f"{rep['norm_latency_mean'] * 1e3:.1f} ms | {rep['tokens']} tokens, {rep['tokens_per_s']:.0f} tokens/s of GPU-busy time", flush=True)
+        if cls is DecoupledRunner:
+            print(f"[cfg4 measured {rate}/s] {name}: {rep['prefill_steps']} prefill steps of {rep['prefill_mean_gpu_ms']:.1f} ms, "
+                  f"{rep['decode_steps']} decode steps of {rep['decode_mean_gpu_ms']:.1f} ms (GPU clock); longest decode step "
+                  f"{rep['decode_max_gpu_ms']:.1f} ms on the GPU, {rep['decode_max_wall_ms']:.1f} ms launch to commit", flush=True)
+            slow = sorted(run.phase_records[nx.PHASE_DECODE], key=lambda r: r[0] - r[1])[:5]
+            print("[cfg4 measured] slowest decode steps (start s, wall ms, gpu ms, reqs): " +
+                  ", ".join(f"({r[0]:.3f}, {(r[1] - r[0]) * 1e3:.1f}, {r[2]:.1f}, {r[3]})" for r in slow), flush=True)
+            print("[cfg4 measured] prefill steps (start s, wall ms, gpu ms, tokens): " +
+                  ", ".join(f"({r[0]:.3f}, {(r[1] - r[0]) * 1e3:.1f}, {r[2]:.1f}, {r[3]})" for r in run.phase_records[nx.PHASE_PREFILL][:12]), flush=True)
+        run.close()
+        del run
+        torch.cuda.empty_cache()
+    if rate > 4.0:
+        assert out["decoupled, 160/96"]["tbt_p95"] < out["coupled, unpartitioned"]["tbt_p95"]
+        assert out["decoupled, 160/96"]["tbt_p95"] < out["coupled, 160/96"]["tbt_p95"]

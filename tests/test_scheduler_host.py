@@ -124,3 +124,73 @@ def test_argument_errors():
     s.commit(5.5)
     with pytest.raises(nx.NexusError):
         s.request(5)
+
+
+def test_independent_phase_ticks_match_oracle():
+    """Random interleavings of the two phases' ticks with random durations: every batch and every metric equals the
+    oracle's under the same sequence of calls."""
+    rng = np.random.default_rng(11)
+    trace = random_trace(21, 90, rate=30.0, prompt_cap=1500)
+    budget, cap, ps, n_pages = 384, 6, 16, 900
+    lib_s = nx.Scheduler(nx.PREFILL_SPF, budget, cap, ps, n_pages, gamma=15.0, max_prefill_reqs=5)
+    ora = sch.Loop(sch.SPF, budget, cap, ps, n_pages, gamma=15.0, max_prefill_reqs=5)
+    for a, p, o in trace:
+        lib_s.submit(a, p, o)
+        ora.submit(a, p, o)
+    now = 0.0
+    busy_until = {nx.PHASE_PREFILL: None, nx.PHASE_DECODE: None}
+    n_calls = 0
+    while any(r.finish_time is None for r in ora.reqs):
+        for phase in (nx.PHASE_PREFILL, nx.PHASE_DECODE):
+            if busy_until[phase] is not None and busy_until[phase] <= now:
+                lib_s.commit_phase(phase, busy_until[phase])
+                (ora.commit_prefill if phase == nx.PHASE_PREFILL else ora.commit_decode)(busy_until[phase])
+                busy_until[phase] = None
+            if busy_until[phase] is None:
+                it = lib_s.next_phase(phase, now)
+                if phase == nx.PHASE_PREFILL:
+                    ref = ora.next_prefill(now)
+                    assert list(zip(it.prefill_req, it.prefill_prefix, it.prefill_chunk)) == ref and len(it.decode_req) == 0
+                    for row, (rid, prefix, n) in zip(it.prefill_page_table, ref):
+                        assert (row >= 0).sum() == sch.pages_for(prefix + n, ps)
+                    dur = 0.02 + 0.03 * rng.random()
+                else:
+                    ref = ora.next_decode(now)
+                    assert list(zip(it.decode_req, it.decode_ctx)) == ref and len(it.prefill_req) == 0
+                    for row, (rid, c) in zip(it.decode_page_table, ref):
+                        assert (row >= 0).sum() == sch.pages_for(c + 1, ps)
+                    dur = 0.004 + 0.004 * rng.random()
+                assert it.kv_used_pages == ora.kv_used_pages
+                if ref:
+                    busy_until[phase] = now + dur
+                n_calls += 1
+        pending = [t for t in busy_until.values() if t is not None]
+        now = min(pending) if pending else now + 0.01
+        assert n_calls < 200000
+    np.testing.assert_array_equal(lib_s.samples(0), ora.ttft())
+    np.testing.assert_array_equal(np.sort(lib_s.samples(1)), np.sort(ora.tbt()))
+    np.testing.assert_array_equal(lib_s.samples(2), ora.normalized_latency())
+    # decode ticks are several times shorter than prefill ticks here, and the TBT shows it
+    assert np.median(ora.tbt()) < 0.01
+
+
+def test_phase_tick_call_order_errors():
+    s = nx.Scheduler(nx.PREFILL_FCFS, 100, 2, 16, 64)
+    s.submit(0.0, 50, 3)
+    with pytest.raises(nx.NexusError):
+        s.commit_phase(nx.PHASE_PREFILL, 1.0)        # nothing open
+    assert len(s.next_phase(nx.PHASE_DECODE, 0.0).decode_req) == 0
+    with pytest.raises(nx.NexusError):
+        s.commit_phase(nx.PHASE_DECODE, 1.0)         # an empty batch opens no tick
+    s.next_phase(nx.PHASE_PREFILL, 0.0)
+    with pytest.raises(nx.NexusError):
+        s.next_phase(nx.PHASE_PREFILL, 0.5)          # still open
+    with pytest.raises(nx.NexusError):
+        s.next(0.5)                                  # coupled iteration while a tick is open
+    with pytest.raises(nx.NexusError):
+        s.next_phase(7, 0.5)
+    s.commit_phase(nx.PHASE_PREFILL, 1.0)
+    s.next(1.0)
+    with pytest.raises(nx.NexusError):
+        s.next_phase(nx.PHASE_DECODE, 1.0)           # coupled iteration open
+    s.commit(2.0)
