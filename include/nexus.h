@@ -190,6 +190,9 @@ int nexus_kv_export(nexus_ctx *ctx, const nexus_kv_cache *kv, int layer, void *k
  * current pair and creates the new one (about 12 ms; more than one pair alive made some pairs dispatch the
  * decode kernels late on MI355X).  (NEXUS_CUS_ALL, NEXUS_CUS_ALL) selects the unpartitioned layout: one unmasked
  * stream, the mixed step runs prefill then decode back to back (the serialized baseline of Sec. 3.1).
+ * CU-masked streams are blocking streams in HIP's sense (the call that creates them takes no flags): work issued
+ * on the NULL stream waits for them and holds them back.  A caller that overlaps its own copies or kernels with a
+ * running phase must issue them on a non-blocking stream.
  */
 int nexus_set_cu_split(nexus_ctx *ctx, int prefill_cus, int decode_cus);
 

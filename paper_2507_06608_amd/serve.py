@@ -183,7 +183,7 @@ class DecoupledRunner(TraceRunner):
         super().__init__(*args, **kwargs)
         assert self.split is not None, "independent phase loops need a partitioned layout"
         self.calls: List[tuple] = []     # (op, phase, time, batch) in call order, for replay against another scheduler
-        self.phase_records = {nx.PHASE_PREFILL: [], nx.PHASE_DECODE: []}   # (start_s, end_s, gpu_ms, tokens)
+        self.phase_records = {nx.PHASE_PREFILL: [], nx.PHASE_DECODE: []}   # (start_s, end_s, gpu_ms, tokens, host ms spent launching, ran alone)
 
     def _launch(self, phase: int, it, other_idle: bool) -> tuple:
         layers = (0, self.n_layers)
@@ -210,43 +210,47 @@ class DecoupledRunner(TraceRunner):
         arrivals = sorted(arrivals)
         t0, skipped = time.perf_counter(), 0.0
         busy = {nx.PHASE_PREFILL: None, nx.PHASE_DECODE: None}
-        n_total = len(arrivals)
+        n_total, n_visible = len(arrivals), 0
+        # an idle phase asks its scheduler again only when something it could act on has changed: a commit of
+        # either phase (requests become ready, pages come back) or a new arrival becoming visible
+        ask = {nx.PHASE_PREFILL: True, nx.PHASE_DECODE: True}
         while True:
             for phase in (nx.PHASE_DECODE, nx.PHASE_PREFILL):
                 if busy[phase] is not None and self.ctx.phase_done(phase):
                     end = time.perf_counter() - t0 + skipped
                     gpu_ms = self.ctx.phase_wait(phase)
                     self.sched.commit_phase(phase, end)
-                    b, desc, start, tokens = busy[phase]
+                    b, desc, start, tokens, launch_ms, alone = busy[phase]
                     self.calls.append(("commit", phase, end, None))
-                    self.phase_records[phase].append((start, end, gpu_ms, tokens))
+                    self.phase_records[phase].append((start, end, gpu_ms, tokens, launch_ms, alone))
                     if self.keep_outputs:
                         with torch.cuda.stream(self.side):
                             self.outputs.append((phase, desc, b.y.clone()))
                         self.side.synchronize()
                     busy[phase] = None
+                    ask[nx.PHASE_PREFILL] = ask[nx.PHASE_DECODE] = True
+            now = time.perf_counter() - t0 + skipped
+            while n_visible < n_total and arrivals[n_visible] <= now:
+                n_visible += 1
+                ask[nx.PHASE_PREFILL] = True
             work = {}
             for phase in (nx.PHASE_DECODE, nx.PHASE_PREFILL):
-                if busy[phase] is None:
-                    now = time.perf_counter() - t0 + skipped
+                if busy[phase] is None and ask[phase]:
+                    ask[phase] = False
                     it = self.sched.next_phase(phase, now)
-                    n = len(it.prefill_req) if phase == nx.PHASE_PREFILL else len(it.decode_req)
-                    if n:
-                        work[phase] = (it, now)
-                    else:
-                        self.calls.append(("next", phase, now, []))
-            for phase, (it, now) in work.items():
+                    if len(it.prefill_req) if phase == nx.PHASE_PREFILL else len(it.decode_req):
+                        work[phase] = it
+            for phase, it in work.items():
                 alone = busy[1 - phase] is None and (1 - phase) not in work
+                t_l = time.perf_counter()
                 b, desc, tokens = self._launch(phase, it, alone)
-                busy[phase] = (b, desc, now, tokens)
+                busy[phase] = (b, desc, now, tokens, (time.perf_counter() - t_l) * 1e3, alone)
                 self.calls.append(("next", phase, now, desc))
             if busy[nx.PHASE_PREFILL] is None and busy[nx.PHASE_DECODE] is None:
-                if self.sched.summary()["n_finished"] == n_total:
+                if n_visible == n_total and self.sched.summary()["n_finished"] == n_total:
                     break
-                now = time.perf_counter() - t0 + skipped
-                later = [a for a in arrivals if a > now]
-                if later:
-                    skipped += later[0] - now
+                if n_visible < n_total:       # nothing in flight and nothing to start: jump to the next arrival
+                    skipped += max(0.0, arrivals[n_visible] - (time.perf_counter() - t0 + skipped))
             if time.perf_counter() - t0 > max_wall_s:
                 raise RuntimeError("decoupled run exceeded its wall-clock limit")
         self.ctx.sync()

@@ -263,10 +263,10 @@ def test_cfg4_decoupled_loops_cut_time_between_tokens(nx, rate, horizon):
                   f"{rep['decode_steps']} decode steps of {rep['decode_mean_gpu_ms']:.1f} ms (GPU clock); longest decode step "
                   f"{rep['decode_max_gpu_ms']:.1f} ms on the GPU, {rep['decode_max_wall_ms']:.1f} ms launch to commit", flush=True)
             slow = sorted(run.phase_records[nx.PHASE_DECODE], key=lambda r: r[0] - r[1])[:5]
-            print("[cfg4 measured] slowest decode steps (start s, wall ms, gpu ms, reqs): " +
-                  ", ".join(f"({r[0]:.3f}, {(r[1] - r[0]) * 1e3:.1f}, {r[2]:.1f}, {r[3]})" for r in slow), flush=True)
-            print("[cfg4 measured] prefill steps (start s, wall ms, gpu ms, tokens): " +
-                  ", ".join(f"({r[0]:.3f}, {(r[1] - r[0]) * 1e3:.1f}, {r[2]:.1f}, {r[3]})" for r in run.phase_records[nx.PHASE_PREFILL][:12]), flush=True)
+            print("[cfg4 measured] slowest decode steps (start s, wall ms, gpu ms, reqs, launch ms, alone): " +
+                  ", ".join(f"({r[0]:.3f}, {(r[1] - r[0]) * 1e3:.1f}, {r[2]:.1f}, {r[3]}, {r[4]:.1f}, {r[5]})" for r in slow), flush=True)
+            print("[cfg4 measured] prefill steps (start s, wall ms, gpu ms, tokens, launch ms, alone): " +
+                  ", ".join(f"({r[0]:.3f}, {(r[1] - r[0]) * 1e3:.1f}, {r[2]:.1f}, {r[3]}, {r[4]:.1f}, {r[5]})" for r in run.phase_records[nx.PHASE_PREFILL]), flush=True)
         run.close()
         del run
         torch.cuda.empty_cache()
