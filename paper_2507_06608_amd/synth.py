@@ -232,6 +232,22 @@ def config(idx: int, seed: int = 0, kv_device: str = "cpu") -> Workload:
     raise ValueError(f"no configuration {idx}")
 
 
+def fused_single_batch(w: Workload) -> PrefillBatch:
+    """The two sub-batches as ONE chunked-prefill batch, the way an engine without phase separation runs them
+    (Sec. 2.4): every decode request becomes a one-token chunk over a prefix of its context length, appended after
+    the prefill requests.  Rows of the result: the prefill tokens, then one row per decode request."""
+    p, d = w.prefill, w.decode
+    width = max(p.page_table.shape[1], d.page_table.shape[1])
+
+    def pad(t):
+        out = np.full((t.shape[0], width), -1, np.int32)
+        out[:, :t.shape[1]] = t
+        return out
+    cu = np.concatenate([p.cu_chunk, p.cu_chunk[-1] + 1 + np.arange(d.n_reqs, dtype=np.int32)]).astype(np.int32)
+    return PrefillBatch(torch.cat([p.x, d.x], 0), cu, np.concatenate([p.prefix_len, d.ctx_len]).astype(np.int32),
+                        np.concatenate([pad(p.page_table), pad(d.page_table)], 0))
+
+
 def subset_for_oracle(w: Workload, prefill_reqs: List[int], decode_reqs: List[int]):
     """Cut a workload down to some of its requests, with page ids renumbered
     into a small pool, so that the oracle can evaluate sampled requests of a

@@ -455,3 +455,33 @@ def test_cfg5_full_depth_80_layers_resident(nx):
     assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16))
     assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
     ctx.close()
+
+
+@pytest.mark.parametrize("idx", [1, 2])
+def test_fused_single_batch_baseline_matches_the_two_phases(nx, oracle, idx):
+    """The engine without phase separation (Sec. 2.4, the system the paper measures against): the decode requests
+    ride in the prefill batch as one-token chunks, every GEMM sees all tokens at once and the weights are read once.
+    Same mathematics as the two phases, so the oracle's two-phase result is the reference: config 1 in full, the
+    benchmark configuration on sampled rows."""
+    _announce(f"fused single batch, config {idx}")
+    wl = synth.config(idx, seed=0, kv_device="cuda:0" if idx > 1 else "cpu")
+    w = synth.make_weights(wl.shape, 0)
+    fused = synth.fused_single_batch(wl)
+    ctx = nx.Nexus(wl.shape, max_prefill_tokens=fused.n_tokens, max_prefill_reqs=fused.n_reqs, max_decode_reqs=1,
+                   max_positions=int((fused.prefix_len + fused.chunk_len).max()), n_layers=1)
+    ctx.load_layer(0, w)
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    before = ctx.kv_export(kv)
+    fb = nx.DevPrefill(fused, ctx.device)
+    ctx.prefill_chunk(fb, kv)
+    ctx.sync()
+    T = wl.prefill.n_tokens
+    yp, yd, kv_after = fb.y[:T].clone(), fb.y[T:].clone(), ctx.kv_export(kv)
+    if idx == 1:
+        ref = run_oracle(oracle, wl, w)
+        assert_close("fused: prefill rows", f32(yp), ref["y_p"])
+        assert_close("fused: decode rows", f32(yd), ref["y_d"])
+        check_pools("fused", wl, kv_after, ref, expected_touched(wl), before)
+    else:
+        _check_sampled(oracle, "fused cfg2", wl, w, yp, yd, kv_after, n_pre=24)
+    ctx.close()
