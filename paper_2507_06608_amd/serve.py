@@ -101,6 +101,12 @@ class TraceRunner:
         db = self._decode_batch(it) if len(it.decode_req) else None
         self.side.synchronize()
         layers = (0, self.n_layers)
+        if self.split is not None:
+            # an iteration with one phase only takes every CU (both layouts stay alive, switching costs nothing)
+            if pb is not None and db is not None:
+                self.ctx.set_cu_split(*self.split)
+            else:
+                self.ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
         t0 = time.perf_counter()
         if pb is not None and db is not None:
             self.ctx.mixed_step(pb, db, self.kv, layers=layers)
