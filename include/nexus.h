@@ -275,14 +275,17 @@ typedef struct {
  * (Eq. 5-6).  Decode attention moves its bytes at the bandwidth left by prefill: with P_attn the fraction of
  * prefill's time spent in attention (Eq. 8), decode gets m_d / (m_d + m_p1) of B during it and m_d / (m_d + m_p2)
  * otherwise (m_d, m_p1, m_p2: bytes of decode attention, prefill attention, prefill dense operators), Eq. 9.
- * share == total means the phase is alone (no contention).  1 <= share <= total, else NEXUS_EINVAL.
+ * At share == total the other phase is taken at its floor of one step for the contention term (Alg. 1 reads its
+ * reference latency from this same function at R = 100, where Eq. 8 has no value; a model whose other phase has
+ * no operators has no contention at any share).  1 <= share <= total, else NEXUS_EINVAL.
  */
 int nexus_cost_latency(const nexus_cost_model *model, int phase, int share, int total, double *seconds);
 
 /*
  * AdjustPartition of Alg. 1 for the prioritised `target_phase`: starting from the current split, the target gives
  * up steps until the other phase's modelled latency is within its budget (alpha x prefill's, beta x decode's
- * latency alone on the whole GPU, Sec. 4.1.2), then takes steps back while the budget still holds.  Both phases
+ * latency on every step of the GPU as nexus_cost_latency gives it, Sec. 4.1.2), then takes steps back while the
+ * budget still holds.  Both phases
  * keep at least one step.  Outputs: the new prefill share and (if non-null) the number of model evaluations.
  */
 int nexus_adjust_partition(const nexus_cost_model *model, int target_phase, int cur_prefill_share, int total,

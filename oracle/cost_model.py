@@ -65,7 +65,7 @@ def p_attn(model: Model, r_p: float) -> float:
 
 def decode_bandwidth(model: Model, r_p: float) -> float:
     """The bandwidth left to decode attention while prefill runs on the share r_p.  r_p = 0 means there is no
-    prefill at all (reading: the ideal latency of a phase that owns the GPU has no contention term)."""
+    prefill at all (decode by itself gets the whole bandwidth)."""
     if r_p <= 0.0:
         return model.B
     m_d = sum(o.m for o in model.decode if o.kind == ATTENTION)
@@ -90,10 +90,14 @@ def decode_latency(model: Model, r_d: float, r_p: float) -> float:
 
 def cost_model(model: Model, phase: int, share: int, total: int) -> float:
     """CostModel(phase, R) of Alg. 1 with shares counted in `total` equal steps (the paper uses total = 100).
-    The other phase holds the remaining total - share steps."""
+    The other phase holds the remaining total - share steps.
+    reading: Alg. 1 obtains the reference latency T^opt from this same function at R = 100, where the other phase
+    would hold nothing and Eq. 8 has no value; the other phase then sits at its floor of one step (no partition
+    gives it less), so T^opt of decode carries the same kind of contention term as the latencies it is compared
+    with."""
     if phase == PREFILL:
         return prefill_latency(model, share / total)
-    return decode_latency(model, share / total, (total - share) / total)
+    return decode_latency(model, share / total, max(total - share, 1) / total)
 
 
 def adjust_partition(model: Model, target: int, r_p_cur: int, total: int, alpha: float, beta: float) -> Tuple[int, int]:

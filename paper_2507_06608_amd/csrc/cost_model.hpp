@@ -70,9 +70,10 @@ public:
         return total;
     }
 
-    // CostModel(phase, R) of Alg. 1; the other phase holds the remaining steps.
+    // CostModel(phase, R) of Alg. 1; the other phase holds the remaining steps, and never less than one: Alg. 1
+    // takes its reference latency from this function at R = total, where Eq. 8 would otherwise have no value.
     double phase_time(int phase, int share, int total) const {
-        const double r = (double)share / total, rest = (double)(total - share) / total;
+        const double r = (double)share / total, rest = (double)std::max(total - share, 1) / total;
         return phase == NEXUS_PHASE_PREFILL ? prefill_time(r) : decode_time(r, rest);
     }
 

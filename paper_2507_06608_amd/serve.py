@@ -188,6 +188,11 @@ class DecoupledRunner(TraceRunner):
         self.borrow_idle_cus = kwargs.pop("borrow_idle_cus", True)
         super().__init__(*args, **kwargs)
         assert self.split is not None, "independent phase loops need a partitioned layout"
+        # the partition controller (Alg. 1), off unless enable_controller() is called
+        self.calibration = None
+        self.ctrl = dict(alpha=1.3, beta=1.1, delta=2, kv_switch=0.7, total=32)
+        self.switches: List[tuple] = []  # (time_s, old prefill CUs, new prefill CUs, host ms spent switching)
+        self._last_shape = {}            # phase -> the quantities of its last batch the cost model needs
         self.calls: List[tuple] = []     # (op, phase, time, batch) in call order, for replay against another scheduler
         self.phase_records = {nx.PHASE_PREFILL: [], nx.PHASE_DECODE: []}   # (start_s, end_s, gpu_ms, tokens, host ms spent launching, ran alone)
 
@@ -209,6 +214,35 @@ class DecoupledRunner(TraceRunner):
         self.side.synchronize()
         self.ctx.decode_step(b, self.kv, layers=layers)
         return b, list(zip(it.decode_req.tolist(), it.decode_ctx.tolist())), len(it.decode_req)
+
+    def enable_controller(self, calibration, **params):
+        """Repartition at run time: whenever a prefill batch is about to start next to a live decode pool, the
+        library's controller is asked for the split (decode-prioritised above the KV-usage switch point,
+        prefill-prioritised below, changes smaller than delta steps suppressed) and the stream pair is re-created
+        if it answers with a new one.  The switch is synchronous: it waits for the decode step in flight."""
+        self.calibration = calibration
+        self.ctrl.update(params)
+
+    def _batch_shape(self, phase: int, it):
+        if phase == nx.PHASE_PREFILL:
+            pre, n = it.prefill_prefix.astype(np.float64), it.prefill_chunk.astype(np.float64)
+            return dict(tokens=float(n.sum()), pairs=float((n * pre + n * (n + 1) / 2).sum()), kv=float((pre + n).sum()))
+        return dict(reqs=float(len(it.decode_req)), kv=float((it.decode_ctx.astype(np.float64) + 1).sum()))
+
+    def _maybe_repartition(self, now: float, kv_usage: float):
+        p, d = self._last_shape.get(nx.PHASE_PREFILL), self._last_shape.get(nx.PHASE_DECODE)
+        if self.calibration is None or p is None or d is None:
+            return
+        alg_p, alg_d = nx.cost_describe(self.shape, self.n_layers, p["tokens"], p["pairs"], p["kv"], d["reqs"], d["kv"])
+        model = self.calibration.model(alg_p, alg_d)
+        c = self.ctrl
+        cur = self.split[0] // 8
+        new = model.partition_controller(kv_usage, c["kv_switch"], cur, c["total"], c["alpha"], c["beta"], c["delta"])
+        if new != cur:
+            t_l = time.perf_counter()
+            self.ctx.set_cu_split(8 * new, 256 - 8 * new)     # waits for what is in flight on the old pair
+            self.switches.append((now, 8 * cur, 8 * new, (time.perf_counter() - t_l) * 1e3))
+            self.split = (8 * new, 256 - 8 * new)
 
     def run_decoupled(self, arrivals: Sequence[float], max_wall_s: float = 120.0):
         """Runs until every submitted request has finished.  `arrivals`: the arrival times that were submitted
@@ -246,6 +280,11 @@ class DecoupledRunner(TraceRunner):
                     it = self.sched.next_phase(phase, now)
                     if len(it.prefill_req) if phase == nx.PHASE_PREFILL else len(it.decode_req):
                         work[phase] = it
+            for phase, it in work.items():
+                self._last_shape[phase] = self._batch_shape(phase, it)
+            if nx.PHASE_PREFILL in work and (busy[nx.PHASE_DECODE] is not None or nx.PHASE_DECODE in work):
+                it = work[nx.PHASE_PREFILL]
+                self._maybe_repartition(now, it.kv_used_pages / it.kv_total_pages)
             for phase, it in work.items():
                 alone = busy[1 - phase] is None and (1 - phase) not in work
                 t_l = time.perf_counter()

@@ -28,8 +28,10 @@ MUTATIONS = [
      "cost_model(model, other, total - r, total) > slack * t_opt"),
     ("buffer zone includes delta itself", "abs(r_new - r_p_cur) < delta", "abs(r_new - r_p_cur) <= delta"),
     ("mode switch at the threshold goes the wrong way", "DECODE if kv_u > kv_switch else PREFILL", "DECODE if kv_u >= kv_switch else PREFILL"),
-    ("decode share mistaken for the prefill share", "return decode_latency(model, share / total, (total - share) / total)",
-     "return decode_latency(model, (total - share) / total, share / total)"),
+    ("decode share mistaken for the prefill share", "return decode_latency(model, share / total, max(total - share, 1) / total)",
+     "return decode_latency(model, max(total - share, 1) / total, share / total)"),
+    ("reference latency of decode taken without any contention", "return decode_latency(model, share / total, max(total - share, 1) / total)",
+     "return decode_latency(model, share / total, (total - share) / total)"),
 ]
 
 

@@ -1,8 +1,6 @@
 """Validation of the partition cost model (Sec. 4.1) against measurements on the GPU: the per-operator saturation
 curves are extracted from traced kernel times of each phase alone on varying CU shares (as the paper prescribes),
 and the calibrated model's predictions are compared with the measured concurrent step and the measured choice."""
-import time
-
 import numpy as np
 import pytest
 import torch
@@ -23,34 +21,6 @@ def nx():
 PEAK_FLOPS, PEAK_BW = 2.5e15, 8.0e12
 TOTAL = 32  # one step = one CU in each of the 8 XCDs
 
-# traced kernel families that make up each of the five modelled operators (QKV, attention, O, gate/up, down);
-# the two RMSNorm launches share one id and are split between QKV and gate/up
-PREFILL_OPS = (("gemm_qkv", "rope_append"), ("attn_prefill", "attn_merge"), ("gemm_o",), ("gemm_gate_up",), ("gemm_down", "splitk_reduce"))
-DECODE_OPS = (("gemm_qkv", "rope_append"), ("attn_decode", "attn_merge"), ("gemm_o",), ("gemm_gate_up",), ("gemm_down", "splitk_reduce"))
-
-
-def op_times(ctx, phase, run, groups, reps=6):
-    per_kernel = {}
-    for k in {k for g in groups for k in g} | {"rmsnorm"}:
-        ctx.trace_begin(phase, k)
-        for _ in range(reps):
-            run()
-        ms, n = ctx.trace_read()
-        per_kernel[k] = ms * 1e-3 * n / reps
-    t = [sum(per_kernel[k] for k in g) for g in groups]
-    t[0] += per_kernel["rmsnorm"] / 2
-    t[3] += per_kernel["rmsnorm"] / 2
-    # the gaps between dependent launches belong to the phase but to no kernel: spread them over the operators in
-    # proportion, so that the operator times add up to the phase as it runs untraced
-    ctx.sync()
-    t0 = time.perf_counter()
-    for _ in range(4 * reps):
-        run()
-    ctx.sync()
-    phase_s = (time.perf_counter() - t0) / (4 * reps)
-    scale = phase_s / sum(t)
-    return [v * scale for v in t]
-
 
 def test_calibrated_model_against_measured_splits(nx):
     print("[gpu test] cost model calibration and validation", flush=True)
@@ -66,30 +36,10 @@ def test_calibrated_model_against_measured_splits(nx):
     kv_d = float((d.ctx_len + 1).sum())
     alg_p, alg_d = nx.cost_describe(wl.shape, 1, p.n_tokens, pairs, kv_p, d.n_reqs, kv_d)
 
-    shares = list(range(4, TOTAL, 4)) + [TOTAL]
-    meas = {nx.PHASE_PREFILL: [], nx.PHASE_DECODE: []}
-    for s in shares:
-        for phase, groups, run in ((nx.PHASE_PREFILL, PREFILL_OPS, lambda: ctx.prefill_chunk(pb, kv)),
-                                   (nx.PHASE_DECODE, DECODE_OPS, lambda: ctx.decode_step(db, kv))):
-            if s == TOTAL:
-                ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
-            elif phase == nx.PHASE_PREFILL:
-                ctx.set_cu_split(8 * s, 256 - 8 * s)
-            else:
-                ctx.set_cu_split(256 - 8 * s, 8 * s)
-            for _ in range(3):
-                run()
-            ctx.sync()
-            meas[phase].append(op_times(ctx, phase, run, groups))
-    rs = [s / TOTAL for s in shares]
-
-    def calibrated(alg, rows):
-        ops = []
-        for i, (flops, nbytes, _, _, kind) in enumerate(alg):
-            c, r_sat, lam = nx.cost_fit(rs, [row[i] for row in rows], PEAK_FLOPS)
-            ops.append((c, nbytes, r_sat, lam, kind))
-        return ops
-    ops_p, ops_d = calibrated(alg_p, meas[nx.PHASE_PREFILL]), calibrated(alg_d, meas[nx.PHASE_DECODE])
+    from paper_2507_06608_amd.calibrate import calibrate
+    cal = calibrate(ctx, kv, pb, db, alg_p, alg_d)
+    ops_p = [(f * k, m, r, l, kind) for (f, m, _, _, kind), (k, r, l) in zip(alg_p, cal.prefill_fit)]
+    ops_d = [(f * k, m, r, l, kind) for (f, m, _, _, kind), (k, r, l) in zip(alg_d, cal.decode_fit)]
     for name, ops in (("prefill", ops_p), ("decode", ops_d)):
         print(f"[cost model] {name} operators (effective GFLOP, R_sat, lambda): " +
               ", ".join(f"({o[0] / 1e9:.1f}, {o[2]:.3f}, {o[3]:+.2f})" for o in ops), flush=True)

@@ -280,3 +280,130 @@ def test_cfg4_decoupled_loops_cut_time_between_tokens(nx, rate, horizon):
         # shortest-prompt-first does not lose to arrival order on mean TTFT (Sec. 6.5 reports a large gain under
         # heavier queueing than this trace produces)
         assert out["decoupled, 160/96"]["ttft_mean"] <= 1.05 * out["decoupled, 160/96, FCFS prefill"]["ttft_mean"]
+
+
+def _calibrate_runner(nx, run, chunk, prefix, decode_ctx, layers):
+    """Cost-model calibration on the runner's own context and KV pool, before the trace starts (the batch's page
+    tables index into the runner's pool; whatever it writes there is overwritten before any request reads it)."""
+    from paper_2507_06608_amd.calibrate import calibrate
+    wl = synth.make_workload("calibration", run.shape, 0, chunk_lens=[chunk], prefix_lens=[prefix], decode_ctx=decode_ctx,
+                             kv_device="cuda:0")
+    assert wl.n_pages <= run.kv.n_pages
+    pb, db = nx.DevPrefill(wl.prefill, run.ctx.device), nx.DevDecode(wl.decode, run.ctx.device)
+    p, d = wl.prefill, wl.decode
+    pairs = float(sum(int(n) * int(pre) + int(n) * (int(n) + 1) // 2 for n, pre in zip(p.chunk_len, p.prefix_len)))
+    alg_p, alg_d = nx.cost_describe(run.shape, layers[1] - layers[0], p.n_tokens, pairs, float((p.prefix_len + p.chunk_len).sum()),
+                                    d.n_reqs, float((d.ctx_len + 1).sum()))
+    cal = calibrate(run.ctx, run.kv, pb, db, alg_p, alg_d, layers=layers)
+    run.ctx.set_cu_split(*run.split)
+    return cal
+
+
+def test_runtime_repartitioning_keeps_results_and_decisions(nx, oracle):
+    """The controller of Alg. 1 in the loop, forced to act often (buffer zone of one step, a KV pool whose usage
+    crosses the switch point back and forth): the stream pair is re-created in mid-trace several times, and every
+    output row still matches the oracle replay, every decision the oracle's loop."""
+    from paper_2507_06608_amd.serve import DecoupledRunner
+    print("[case] decoupled loop with runtime repartitioning, tiny", flush=True)
+    shape = synth.SHAPES["tiny"]
+    rng = np.random.default_rng(8)
+    trace, t = [], 0.0
+    for _ in range(20):
+        t += float(rng.exponential(0.004))
+        trace.append((t, int(min(900, max(1, rng.lognormal(np.log(250.0), 0.8)))), int(rng.integers(4, 40))))
+    budget, cap, n_pages, gamma, max_prefill = 128, 4, 200, 15.0, 4
+    w = synth.make_weights(shape, 3)
+    run = DecoupledRunner(shape, 1, lambda l: w, policy=nx.PREFILL_SPF, token_budget=budget, max_decode_reqs=cap,
+                          n_pages=n_pages, gamma=gamma, max_prefill_reqs=max_prefill, max_positions=1024, split=(128, 128),
+                          seed=1, pool_rows=4096)
+    cal = _calibrate_runner(nx, run, 128, 256, [200, 300, 400, 500], (0, 1))
+    run.enable_controller(cal, delta=1, kv_switch=0.35)
+    run.keep_outputs = True
+    run.submit(trace)
+    run.run_decoupled([a for a, _, _ in trace], max_wall_s=90.0)
+    assert run.sched.summary()["n_finished"] == len(trace)
+    print(f"[repartition] {len(run.switches)} switches: " + ", ".join(f"{a}->{b} CUs at {t * 1e3:.0f} ms ({ms:.1f} ms)" for t, a, b, ms in run.switches), flush=True)
+    assert len(run.switches) >= 2
+
+    ref = _oracle_loop(sch.SPF, trace, budget, cap, shape.page_size, n_pages, gamma, max_prefill)
+    for op, phase, t_call, desc in run.calls:
+        if op == "next":
+            got = ref.next_prefill(t_call) if phase == nx.PHASE_PREFILL else ref.next_decode(t_call)
+            assert got == desc, (op, phase, t_call)
+        else:
+            (ref.commit_prefill if phase == nx.PHASE_PREFILL else ref.commit_decode)(t_call)
+    np.testing.assert_array_equal(run.sched.samples(0), ref.ttft())
+    m, ow = oracle_model(oracle, shape), oracle_weights(w)
+    x_pool = f32(run.x_pool)
+    replay = {rid: _replay_request(oracle, m, ow, x_pool, rid, p, o, run.pool_rows) for rid, (a, p, o) in enumerate(trace)}
+    n_rows = 0
+    for phase, desc, y in run.outputs:
+        if phase == nx.PHASE_PREFILL:
+            off = 0
+            for rid, prefix, n in desc:
+                assert_close(f"prefill req {rid} [{prefix}:{prefix + n})", f32(y[off:off + n]), replay[rid][0][prefix:prefix + n])
+                off += n
+                n_rows += n
+        else:
+            for j, (rid, ctx) in enumerate(desc):
+                assert_close(f"decode req {rid} ctx {ctx}", f32(y[j]), replay[rid][1][ctx - trace[rid][1]])
+                n_rows += 1
+    assert n_rows == sum(p + o - 1 for _, p, o in trace)
+    run.close()
+
+
+def test_cfg4_partition_controller_in_the_loop(nx):
+    """The 48-layer stack with the controller of Alg. 1 choosing the split at run time (alpha = 1.3, beta = 1.1, KV
+    switch point at 70 % of the pool, buffer zone of 2 of 32 steps), against the fixed 160/96 split on the same
+    trace and pool.  The cost model is calibrated on 4 of the layers before the trace starts."""
+    from paper_2507_06608_amd.serve import DecoupledRunner
+    print("[case] cfg4 with the partition controller in the loop", flush=True)
+    shape = synth.SHAPES["qwen25_14b"]
+    n_pages = 5120
+    free, _ = torch.cuda.mem_get_info(0)
+    need = shape.n_layers * (2 * shape.params_per_layer + n_pages * shape.page_size * shape.kv_dim * 4) + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of free device memory, {free >> 30} GiB available")
+    trace = synth.poisson_trace(1, rate=12.0, horizon_s=3.0, output_cap=384)
+    arrivals = [a for a, _, _ in trace]
+    g = torch.Generator(device="cuda:0")
+
+    def weights(l):
+        g.manual_seed(1000 + l)
+        std = synth.weight_std(shape)
+
+        def mat(r, c):
+            return (torch.randn((r, c), generator=g, device="cuda:0") * std).to(torch.bfloat16)
+
+        def gain():
+            return (1.0 + torch.randn(shape.hidden, generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
+        return {"attn_norm_g": gain(), "w_qkv": mat(shape.n_qkv, shape.hidden), "w_o": mat(shape.hidden, shape.q_dim),
+                "ffn_norm_g": gain(), "w_gate_up": mat(2 * shape.ffn, shape.hidden), "w_down": mat(shape.hidden, shape.ffn)}
+
+    out = {}
+    for name, dynamic in (("fixed 160/96", False), ("controller", True)):
+        run = DecoupledRunner(shape, shape.n_layers, weights, policy=nx.PREFILL_SPF, token_budget=1024, max_decode_reqs=128,
+                              n_pages=n_pages, gamma=15.0, max_prefill_reqs=8, seed=2, split=(160, 96))
+        if dynamic:
+            rng = np.random.default_rng(3)
+            cal = _calibrate_runner(nx, run, 1024, 2048, rng.integers(500, 2500, size=24).tolist(), (0, 4))
+            print("[controller] prefill operators (work factor, R_sat, lambda): " + ", ".join(f"({k:.2f}, {r:.3f}, {l:+.2f})" for k, r, l in cal.prefill_fit), flush=True)
+            print("[controller] decode operators (work factor, R_sat, lambda): " + ", ".join(f"({k:.2f}, {r:.3f}, {l:+.2f})" for k, r, l in cal.decode_fit), flush=True)
+            run.enable_controller(cal)
+        run.submit(trace)
+        run.run_decoupled(arrivals, max_wall_s=150.0)
+        rep = run.report_decoupled()
+        assert rep["n_finished"] == len(trace)
+        out[name] = rep
+        print(f"[controller] {name}: TTFT mean {rep['ttft_mean'] * 1e3:.0f} ms p95 {rep['ttft_p95'] * 1e3:.0f} ms | TBT mean "
+              f"{rep['tbt_mean'] * 1e3:.1f} ms p95 {rep['tbt_p95'] * 1e3:.1f} ms p99 {rep['tbt_p99'] * 1e3:.1f} ms | {rep['tokens_per_s']:.0f} tokens/s; "
+              f"prefill steps {rep['prefill_mean_gpu_ms']:.1f} ms, decode steps {rep['decode_mean_gpu_ms']:.1f} ms", flush=True)
+        if dynamic:
+            print(f"[controller] {len(run.switches)} switches: " + ", ".join(f"{a}->{b} CUs at {t:.2f} s ({ms:.1f} ms)" for t, a, b, ms in run.switches), flush=True)
+            assert 1 <= len(run.switches) <= 12          # it acts, and the buffer zone keeps it from flapping
+        run.close()
+        del run
+        torch.cuda.empty_cache()
+    # the controller keeps decode within its slack or prefill within its own: neither metric may fall apart
+    assert out["controller"]["tbt_p95"] <= 1.5 * out["fixed 160/96"]["tbt_p95"]
+    assert out["controller"]["ttft_mean"] <= 1.5 * out["fixed 160/96"]["ttft_mean"]
