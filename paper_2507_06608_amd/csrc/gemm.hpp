@@ -40,6 +40,7 @@ struct GemmArgs {
     float *partial;        // [S][T][N]
     int n_tblk;            // token blocks in the grid
     int n_xcd;             // XCDs the launch is spread over (tile-order remap), >= 1
+    int group_f;           // feature blocks per tile group (tile-order remap inside an XCD), >= 1
 };
 
 constexpr int kGemmBK = 64;  // unit of the split-K bookkeeping: ksteps_per_split counts 64-wide k steps
@@ -168,8 +169,20 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wf = w % WF, wt = w / WF;
     int nblk = gridDim.x, bid = blockIdx.x;
+    // Workgroups are dealt to the XCDs round-robin: give every XCD a contiguous range of tiles, ...
     if (a.n_xcd > 1 && nblk % a.n_xcd == 0) bid = (bid % a.n_xcd) * (nblk / a.n_xcd) + bid / a.n_xcd;
-    const int tb = bid % a.n_tblk, fb = bid / a.n_tblk;
+    // ... and walk that range in groups of group_f feature blocks, feature block fastest: the tiles resident on an
+    // XCD at one time then form a group_f x (residents / group_f) rectangle, whose operands (group_f weight blocks +
+    // the rectangle's token blocks) are fetched into that XCD's L2 once instead of once per tile.
+    int tb, fb;
+    {
+        const int G = a.group_f > 0 ? a.group_f : 1;
+        const int per_group = G * a.n_tblk, g = bid / per_group, r = bid - g * per_group;
+        const int n_fblk = nblk / a.n_tblk;
+        int gf = n_fblk - g * G;
+        if (gf > G) gf = G;
+        fb = g * G + r % gf, tb = r / gf;
+    }
     const int ft0 = fb * FS, tt0 = tb * TS;
     const int z = blockIdx.z;
     const int ktile0 = z * a.ksteps_per_split * 4;  // ksteps_per_split counts 64-wide steps = 4 k-tiles

@@ -274,20 +274,25 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
     // Ring geometry and tile extent may follow the CU share (they do not change any element's summation order; the
     // split factor S, which does, is problem-only).  256 x 256 tiles do about 15% more flops per CU-second than
     // 128 x 128 (half the LDS and L2 traffic per flop) but quantise worse: one per CU against two.  Measured at
-    // K = 4096 on MI355X: a round of 256-tiles takes 127 us, a round of 128-tiles (two per CU) 75 us; the estimate
+    // K = 4096 on MI355X: a round of 256-tiles takes 132 us, a round of 128-tiles (two per CU) 75 us; the estimate
     // below reproduced the measured times of all four projection GEMMs at 512 and 8192 tokens within 5%.
     int variant = p.variant, FS = p.FS, TS = p.TS;
     if (variant == GV_P128 && p.S == 1 && c->allow_p256) {
         const long n128 = (long)((a.n_ttiles + 3) / 4) * ((n_ftiles + 3) / 4);
         const long n256 = (long)((a.n_ttiles + 7) / 8) * ((n_ftiles + 7) / 8);
         const long est128 = (n128 + 2 * r.cus - 1) / (2 * r.cus) * 75;
-        const long est256 = (n256 + r.cus - 1) / r.cus * 127;
+        const long est256 = (n256 + r.cus - 1) / r.cus * 132;
         if (est256 < est128) variant = GV_P256, FS = 8, TS = 8;
     }
     const int last_ksteps = Kp / kGemmBK - (p.S - 1) * p.ksteps_per_split;  // the shortest k range of the grid
     if (last_ksteps < kStreamDepth) variant = variant == GV_S64 ? GV_R64 : variant == GV_S32 ? GV_R32 : variant;
     a.n_tblk = (a.n_ttiles + TS - 1) / TS;
     a.n_xcd = r.n_xcd;
+    // Tiles resident on one XCD at a time form a 4 x (residents / 4) rectangle instead of a row of token blocks:
+    // at 8192 tokens the L2 hit rate of a row is 56% (every tile streams its own token block past the shared weight
+    // block), and the rectangle is 7% (256-tiles) to 25% (128-tiles) faster; below ~2048 tokens a row already
+    // wraps into a rectangle and the order makes no measurable difference.
+    a.group_f = 4;
     const int n_fblk = (n_ftiles + FS - 1) / FS;
     dim3 grid(a.n_tblk * n_fblk, 1, p.S);
     if (p.S > 1 && (size_t)p.S * r.T * N_packed > ws.partial_elems)
