@@ -100,6 +100,7 @@ def main():
     ap.add_argument("--split", default="auto", help="'auto' (profile and choose) or PREFILL_CUS/DECODE_CUS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-fused", action="store_true", help="skip the naive fused single-batch step (keeps a kernel trace to the two phases)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) to calibrate rocprofv3 byte counters")
     args = ap.parse_args()
@@ -157,24 +158,26 @@ def main():
     # decode requests as one-token chunks (weights read once, but the decode rows go through the chunked-prefill
     # attention kernel, which wastes 31 of its 32 query rows on them).  Reported for the record, not as the baseline
     # to beat: that is the serialized step.
-    fused = synth.fused_single_batch(wl)
-    fctx = binding.Nexus(wl.shape, max_prefill_tokens=fused.n_tokens, max_prefill_reqs=fused.n_reqs, max_decode_reqs=1,
-                         max_positions=int((fused.prefix_len + fused.chunk_len).max()), n_layers=1)
-    fctx.load_layer(0, weights)
-    fb = binding.DevPrefill(fused, fctx.device)
-    for _ in range(args.warmup):
-        fctx.prefill_chunk(fb, kv)
-    torch.cuda.synchronize()
-    t = time.perf_counter()
-    n_f = max(10, args.steps // 4)
-    for _ in range(n_f):
-        fctx.prefill_chunk(fb, kv)
-    torch.cuda.synchronize()
-    fused_ms = (time.perf_counter() - t) / n_f * 1e3
-    fused_res = {"ms_per_step": fused_ms, "tokens_per_s": work["tokens"] / fused_ms * 1e3, "decode_latency_ms": fused_ms}
-    log(f"[bench] fused single batch: {fused_res}")
-    fctx.close()
-    del fb, fctx
+    fused_res = None
+    if not args.no_fused:
+        fused = synth.fused_single_batch(wl)
+        fctx = binding.Nexus(wl.shape, max_prefill_tokens=fused.n_tokens, max_prefill_reqs=fused.n_reqs, max_decode_reqs=1,
+                             max_positions=int((fused.prefix_len + fused.chunk_len).max()), n_layers=1)
+        fctx.load_layer(0, weights)
+        fb = binding.DevPrefill(fused, fctx.device)
+        for _ in range(args.warmup):
+            fctx.prefill_chunk(fb, kv)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        n_f = max(10, args.steps // 4)
+        for _ in range(n_f):
+            fctx.prefill_chunk(fb, kv)
+        torch.cuda.synchronize()
+        fused_ms = (time.perf_counter() - t) / n_f * 1e3
+        fused_res = {"ms_per_step": fused_ms, "tokens_per_s": work["tokens"] / fused_ms * 1e3, "decode_latency_ms": fused_ms}
+        log(f"[bench] fused single batch: {fused_res}")
+        fctx.close()
+        del fb, fctx
 
     # ---- sweep of the CU split
     sweep = []
