@@ -174,17 +174,20 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
             // Register 4b + j is row 8b + 4g + j: page b / 2, slot 8(b%2) + 4g + j, which holds token
             // 8g + 4(b%2) + j.  So registers 8p .. 8p+7 are tokens 8g .. 8g+7 of page p, in order.
             const bool need_mask = key0 + kAttnTile - 1 > wave_min_pos;
-            float mx = m_run;
+            // The running maximum is kept in scaled units (score * log2(e) / sqrt(hd)); the scale is positive, so
+            // the maximum is taken over the raw scores and scaled once, and the scaling of every score is folded
+            // into the exponent's fused multiply-add.
+            float mraw = -INFINITY;
+            if (need_mask) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float v = s[e] * a.scale_log2e;
-                if (need_mask) {
+                for (int e = 0; e < 16; ++e) {
                     const int key = key0 + 16 * (e >> 3) + 8 * g + (e & 7);
-                    v = key <= pos ? v : -INFINITY;
+                    s[e] = key <= pos ? s[e] : -INFINITY;
                 }
-                s[e] = v;
-                mx = fmaxf(mx, v);
             }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mraw = fmaxf(mraw, s[e]);
+            float mx = fmaxf(m_run, mraw * a.scale_log2e);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             // a row may see no key at all in this split's range yet: keep the arithmetic finite
             const float mref = mx == -INFINITY ? 0.f : mx;
@@ -193,15 +196,19 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
             float rs = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(s[e] - mref);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], a.scale_log2e, -mref));
                 s[e] = p;
                 rs += p;
             }
             l_run = l_run * alpha + rs;
+            // After the first few tiles the maximum rarely moves and alpha is exactly 1 in every lane: the 16 RT
+            // multiplications of the rescale are then skipped (multiplying by 1.0 changes no bit).
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-            for (int i = 0; i < RT; ++i)
+                for (int i = 0; i < RT; ++i)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+                    for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+            }
             // V slots at or past kmax may hold anything (even NaN): their probability is exactly 0, but 0 * NaN is
             // not, so the last tile zeroes them as it reads them.
             const bool v_tail = key0 + kAttnTile > kmax;
