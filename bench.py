@@ -266,8 +266,12 @@ def main():
                     "cus": chosen, "frac_of_cu_share": ach / (PEAK_BF16_TFLOPS * chosen / n_cus)}
         by = work["decode_bytes"][k]
         ach = by / (ms * 1e-3) / 1e9
+        # besides the published peak: what this many CUs can read at all (about 50 GB/s per CU on this chip, measured
+        # with a plain streaming kernel; the whole chip saturates near 5.7-6.0 TB/s for 4 KiB blocks)
+        share_ceiling = min(50.0 * (n_cus - chosen), 5850.0)
         return {"kernel": f"{phase}.{k}", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None, "ms_per_launch": ms, "cus": n_cus - chosen}
+                "frac": ach / PEAK_HBM_GBS, "traffic": None, "ms_per_launch": ms, "cus": n_cus - chosen,
+                "measured_read_ceiling_of_these_cus": share_ceiling, "frac_of_that_ceiling": ach / share_ceiling}
 
     roofline = roof(dom[0], dom[1], dom_ms)
     # the other side of the target: best prefill GEMM against MFMA peak, decode attention against HBM peak
