@@ -206,6 +206,20 @@ int nexus_decode_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexu
                       const nexus_kv_cache *kv);
 
 /*
+ * The step of an engine WITHOUT phase separation (Sec. 2.4, the chunked-prefill engines the paper measures
+ * against), for comparison: one batch in which the last n_decode_reqs requests are decode requests written as
+ * one-token chunks (chunk length 1, prefix_len = context length, x = the new token's input).  Every projection and
+ * norm runs once over all rows, so the weights are read once per step; the chunk rows take the chunked-prefill
+ * attention kernel and the decode rows the decode attention kernel.  Runs on the prefill stream of the current
+ * layout (select the unpartitioned layout for the baseline proper); output row order = batch row order.
+ * max_decode_ctx: largest (context length + 1) among the decode requests.  Limits: the batch within the prefill
+ * limits of the context, n_decode_reqs within max_decode_reqs.  Must not overlap a decode phase of the same context
+ * (it borrows that phase's attention workspace).
+ */
+int nexus_fused_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_prefill_batch *batch,
+                     int32_t n_decode_reqs, int32_t max_decode_ctx, const nexus_kv_cache *kv);
+
+/*
  * Completion of the last nexus_prefill_chunk / nexus_decode_step of a phase (nexus_phase), without waiting for the
  * other phase: the two calls are asynchronous and, on a partitioned layout, run on different streams, so a caller
  * may keep one loop per phase (Sec. 5) -- launch a phase, poll it, launch its next step -- as long as the two

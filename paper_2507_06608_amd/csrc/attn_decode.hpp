@@ -31,6 +31,12 @@ struct AttnDecodeArgs {
     float *part_o;   // [B][Hkv][max_spans][G][hd]
     float *part_ml;  // [B][Hkv][max_spans][G][2]  (running max in the log2 domain, sum)
     f16_t *out;      // merge output: half, P32 [B rows][Hq*hd]
+    // Decode requests riding in a chunked-prefill batch (the fused single-batch step): their queries sit in the
+    // prefill layout -- P32, every request on a 32-row boundary, request j of the decode part in the row tile that
+    // follows the tiles of the n_lead leading requests -- and their outputs go to rows out_row0 + j.  lead_cu is
+    // null for the plain decode phase (q row-major [B][Hq*hd], output row j).
+    const int32_t *lead_cu;  // cu_chunk of the batch the requests ride in
+    int n_lead, out_row0;
 };
 
 template <int HD, int G>
@@ -65,11 +71,20 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void attn_decode_kernel(AttnDeco
         if ((unsigned)my_page >= (unsigned)a.n_pages) my_page = 0;
     }
 
+    int q_row = 0;
+    if (a.lead_cu) {
+        int tiles = j;
+        for (int i = 0; i < a.n_lead; ++i) tiles += (a.lead_cu[i + 1] - a.lead_cu[i] + 31) >> 5;
+        q_row = tiles * 32;
+    }
     bf16x8 qf[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
         u32x4 v = {0, 0, 0, 0};
-        if (col < G) v = *(const u32x4 *)(a.q + (size_t)j * a.Hq * HD + (size_t)(kvh * G + col) * HD + (kk * 4 + g4) * 8);
+        if (col < G) {
+            const int k = (kvh * G + col) * HD + (kk * 4 + g4) * 8;
+            v = *(const u32x4 *)(a.q + (a.lead_cu ? p32_offset(q_row, k, a.Hq * HD) : (size_t)j * a.Hq * HD + k));
+        }
         qf[kk] = *(bf16x8 *)&v;
     }
     f32x4 o_acc[RT];
@@ -231,7 +246,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnDecodeArgs a) {
     }
     const float inv = 1.0f / denom;
     const int QKp = a.Hq * HD;
-    f16_t *dst = a.out + p32_offset(j, hq * HD + lane * EPL, QKp);
+    f16_t *dst = a.out + p32_offset(a.out_row0 + j, hq * HD + lane * EPL, QKp);
     if (EPL == 2) {
         *(uint32_t *)dst = packh2(acc[0] * inv, acc[EPL - 1] * inv);
     } else {

@@ -247,6 +247,8 @@ struct PhaseRun {
     int phase;  // NEXUS_PHASE_*
     hipStream_t s;
     int n_xcd;
+    int fused_decode = 0;      // > 0: the last fused_decode requests of pb are decode requests (one-token chunks)
+    int fused_max_ctx = 0;     // largest context + 1 among them
     int cus;  // CUs the phase's stream may run on
     int T;
     const nexus_prefill_batch *pb;
@@ -357,12 +359,12 @@ static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
         a.tiles_per_req = (r.pb->max_chunk + 32 * SPB - 1) / (32 * SPB);                                             \
         {                                                                                                            \
             Tracer tr(c, r.phase, NEXUS_K_ATTN_PREFILL, r.s);                                                        \
-            hipLaunchKernelGGL(kern, dim3(r.pb->n_reqs * a.tiles_per_req, c->m.n_kv_heads, a.n_splits), dim3(64 * GG * SPB), smem, r.s, a); \
+            hipLaunchKernelGGL(kern, dim3(a.n_reqs * a.tiles_per_req, c->m.n_kv_heads, a.n_splits), dim3(64 * GG * SPB), smem, r.s, a); \
         }                                                                                                            \
         HIP_TRY(hipGetLastError());                                                                                  \
         if (a.n_splits > 1) {                                                                                        \
             Tracer tr(c, r.phase, NEXUS_K_ATTN_MERGE, r.s);                                                          \
-            hipLaunchKernelGGL((attn_prefill_merge_kernel<HD, SPB>), dim3(r.T * c->m.n_q_heads), dim3(64), 0, r.s, a); \
+            hipLaunchKernelGGL((attn_prefill_merge_kernel<HD, SPB>), dim3((r.T - r.fused_decode) * c->m.n_q_heads), dim3(64), 0, r.s, a); /* decode rows of a fused batch are not this kernel's */ \
         }                                                                                                            \
         break;                                                                                                       \
     }
@@ -444,12 +446,25 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
     if (prefill) {
         AttnPrefillArgs a{};
         a.q = ws.q, a.out = ws.attn, a.cu_chunk = r.pb->cu_chunk, a.prefix_len = r.pb->prefix_len, a.page_table = r.pb->page_table;
-        a.n_reqs = r.pb->n_reqs, a.max_pages = r.pb->max_pages;
+        a.n_reqs = r.pb->n_reqs - r.fused_decode, a.max_pages = r.pb->max_pages;
         a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads;
         a.scale_log2e = scale_log2e;
         a.n_splits = plan_attn_splits(r.T, m.n_q_heads, r.pb->max_total_len);
         a.part_o = ws.part_o, a.part_ml = ws.part_ml, a.T = r.T;
-        NX_TRY(m.head_dim == 128 ? launch_attn_prefill<128>(r, a) : launch_attn_prefill<64>(r, a));
+        if (a.n_reqs > 0) NX_TRY(m.head_dim == 128 ? launch_attn_prefill<128>(r, a) : launch_attn_prefill<64>(r, a));
+        if (r.fused_decode) {
+            // the decode requests at the tail of the batch take the decode attention kernel: same queries (prefill
+            // layout), same pools (their new K/V was appended by the rotary kernel above), outputs into the same
+            // attention buffer; the span partials use the decode phase's workspace
+            const int lead = r.pb->n_reqs - r.fused_decode;
+            AttnDecodeArgs d{};
+            d.q = ws.q, d.ctx_len = r.pb->prefix_len + lead, d.page_table = r.pb->page_table + (size_t)lead * r.pb->max_pages;
+            d.n_reqs = r.fused_decode, d.max_pages = r.pb->max_pages, d.max_spans = (r.fused_max_ctx + kSpan - 1) / kSpan;
+            d.k_pool = k_pool, d.v_pool = v_pool, d.n_pages = r.kv->n_pages, d.Hq = m.n_q_heads, d.Hkv = m.n_kv_heads;
+            d.scale_log2e = scale_log2e, d.part_o = c->ws[NEXUS_PHASE_DECODE].part_o, d.part_ml = c->ws[NEXUS_PHASE_DECODE].part_ml;
+            d.out = ws.attn, d.lead_cu = r.pb->cu_chunk, d.n_lead = lead, d.out_row0 = r.pb->n_tokens - r.fused_decode;
+            NX_TRY(m.head_dim == 128 ? launch_attn_decode<128>(r, d) : launch_attn_decode<64>(r, d));
+        }
     } else {
         AttnDecodeArgs a{};
         a.q = ws.q, a.ctx_len = r.db->ctx_len, a.page_table = r.db->page_table, a.n_reqs = r.db->n_reqs;
@@ -867,6 +882,22 @@ int nexus_decode_step(nexus_ctx *c, int lb, int le, const nexus_decode_batch *db
     NX_TRY(check_decode(c, db));
     DeviceGuard dg(c->device);
     return run_single_phase(c, make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le);
+}
+
+int nexus_fused_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *batch, int32_t n_decode_reqs, int32_t max_decode_ctx,
+                     const nexus_kv_cache *kv) {
+    NX_TRY(check_layers(c, lb, le));
+    NX_TRY(check_kv(c, kv, le));
+    NX_TRY(check_prefill(c, batch));
+    if (n_decode_reqs < 0 || n_decode_reqs > batch->n_reqs) return fail(NEXUS_EINVAL, "%d decode requests in a batch of %d", n_decode_reqs, batch->n_reqs);
+    if (n_decode_reqs > c->lim.max_decode_reqs) return fail(NEXUS_ESHAPE, "%d decode requests exceed limit %d", n_decode_reqs, c->lim.max_decode_reqs);
+    if (n_decode_reqs > 0 && (max_decode_ctx <= 0 || max_decode_ctx > c->lim.max_positions || max_decode_ctx > batch->max_total_len))
+        return fail(NEXUS_EINVAL, "max_decode_ctx %d outside (0, min(max_positions %d, max_total_len %d)]", max_decode_ctx, c->lim.max_positions, batch->max_total_len);
+    if ((int64_t)batch->max_pages * kPage < max_decode_ctx) return fail(NEXUS_EINVAL, "page table rows (%d pages) cannot hold max_decode_ctx %d", batch->max_pages, max_decode_ctx);
+    DeviceGuard dg(c->device);
+    PhaseRun r = make_run(c, NEXUS_PHASE_PREFILL, batch, nullptr, kv);
+    r.fused_decode = n_decode_reqs, r.fused_max_ctx = max_decode_ctx;
+    return run_single_phase(c, r, lb, le);
 }
 
 int nexus_phase_query(nexus_ctx *c, int phase) {

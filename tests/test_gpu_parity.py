@@ -485,3 +485,68 @@ def test_fused_single_batch_baseline_matches_the_two_phases(nx, oracle, idx):
     else:
         _check_sampled(oracle, "fused cfg2", wl, w, yp, yd, kv_after, n_pre=24)
     ctx.close()
+
+
+@pytest.mark.parametrize("idx", [1, 2])
+def test_fused_step_with_both_attention_kernels(nx, oracle, idx):
+    """The fused single-batch step proper: one pass of every projection over all rows (weights read once), chunk rows
+    through the chunked-prefill attention, decode rows through the decode attention.  Reference: the oracle's
+    two-phase result.  Also bit-identical to itself on a CU share (the fused step is a prefill-stream phase)."""
+    _announce(f"fused step, config {idx}")
+    wl = synth.config(idx, seed=0, kv_device="cuda:0" if idx > 1 else "cpu")
+    w = synth.make_weights(wl.shape, 0)
+    fused = synth.fused_single_batch(wl)
+    d = wl.decode
+
+    def run(split):
+        ctx = nx.Nexus(wl.shape, max_prefill_tokens=fused.n_tokens, max_prefill_reqs=fused.n_reqs, max_decode_reqs=d.n_reqs,
+                       max_positions=int((fused.prefix_len + fused.chunk_len).max()), n_layers=1)
+        ctx.load_layer(0, w)
+        kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+        before = ctx.kv_export(kv)
+        fb = nx.DevPrefill(fused, ctx.device)
+        ctx.set_cu_split(*split)
+        ctx.fused_step(fb, d.n_reqs, int(d.ctx_len.max()) + 1, kv)
+        ctx.sync()
+        out = (fb.y.clone(), ctx.kv_export(kv), before)
+        ctx.close()
+        return out
+
+    y, kv_after, before = run((nx.CUS_ALL, nx.CUS_ALL))
+    T = wl.prefill.n_tokens
+    yp, yd = y[:T], y[T:]
+    if idx == 1:
+        ref = run_oracle(oracle, wl, w)
+        assert_close("fused step: prefill rows", f32(yp), ref["y_p"])
+        assert_close("fused step: decode rows", f32(yd), ref["y_d"])
+        check_pools("fused step", wl, kv_after, ref, expected_touched(wl), before)
+    else:
+        _check_sampled(oracle, "fused step cfg2", wl, w, yp, yd, kv_after, n_pre=24)
+    y2, kv2, _ = run((160, 96))
+    assert torch.equal(y2.view(torch.int16), y.view(torch.int16))
+    for a, b in zip(kv2, kv_after):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_fused_step_of_decode_requests_only_and_argument_errors(nx, oracle):
+    _announce("fused step, decode only")
+    wl = synth.config(1, seed=0)
+    w = synth.make_weights(wl.shape, 0)
+    d = wl.decode
+    only = synth.PrefillBatch(d.x, np.arange(d.n_reqs + 1, dtype=np.int32), d.ctx_len.astype(np.int32), d.page_table)
+    ctx = nx.Nexus(wl.shape, max_prefill_tokens=d.n_reqs, max_prefill_reqs=d.n_reqs, max_decode_reqs=d.n_reqs,
+                   max_positions=int(d.ctx_len.max()) + 1, n_layers=1)
+    ctx.load_layer(0, w)
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    fb = nx.DevPrefill(only, ctx.device)
+    ctx.fused_step(fb, d.n_reqs, int(d.ctx_len.max()) + 1, kv)
+    ctx.sync()
+    ref = run_oracle(oracle, wl, w, do_prefill=False)
+    assert_close("fused step, decode only", f32(fb.y), ref["y_d"])
+    with pytest.raises(nx.NexusError):
+        ctx.fused_step(fb, d.n_reqs + 1, 10, kv)
+    with pytest.raises(nx.NexusError):
+        ctx.fused_step(fb, d.n_reqs, 0, kv)
+    with pytest.raises(nx.NexusError):
+        ctx.fused_step(fb, d.n_reqs, 1 << 20, kv)
+    ctx.close()
