@@ -322,8 +322,8 @@ def main():
 def serving_trace(log):
     """The trace-driven configuration (14B-shaped stack of 48 layers, Poisson arrivals, lognormal prompt and
     output lengths, 1024-token chunks, SPF prefill queue, FCFS decode pool of 128) on the measured clock until every
-    request has finished: coupled iterations on the unpartitioned GPU against independent phase loops on a 160/96
-    split.  Latencies in milliseconds on the loop's own clock."""
+    request has finished: coupled iterations on the unpartitioned GPU (prefill then decode, or both as one fused
+    batch) against independent phase loops on a 160/96 split.  Latencies in milliseconds on the loop's own clock."""
     import torch
 
     from paper_2507_06608_amd import binding, synth
@@ -351,8 +351,9 @@ def serving_trace(log):
     res = {"workload": f"qwen25_14b x {shape.n_layers} layers, Poisson {rate}/s for {horizon} s ({len(trace)} requests), "
                        "prompts lognormal(median 1024, sigma 0.8) <= 8192, outputs lognormal(median 256, sigma 0.7) <= 384",
            "unit": "ms"}
-    for name, cls, split in (("coupled_unpartitioned", TraceRunner, None), ("independent_loops_160_96", DecoupledRunner, (160, 96))):
-        run = cls(shape, shape.n_layers, weights, split=split, **common)
+    for name, cls, split, fused in (("coupled_unpartitioned", TraceRunner, None, False), ("coupled_fused_single_batch", TraceRunner, None, True),
+                                    ("independent_loops_160_96", DecoupledRunner, (160, 96), False)):
+        run = cls(shape, shape.n_layers, weights, split=split, fused=fused, **common)
         run.submit(trace)
         if cls is DecoupledRunner:
             run.run_decoupled(arrivals, max_wall_s=150.0)

@@ -45,9 +45,12 @@ class TraceRunner:
     def __init__(self, shape: ModelShape, n_layers: int, weights_for_layer, *, policy: int, token_budget: int,
                  max_decode_reqs: int, n_pages: int, gamma: float = 15.0, max_prefill_reqs: int = 8,
                  max_positions: int = 10240, split: Optional[Tuple[int, int]] = None, seed: int = 0,
-                 pool_rows: int = 16384, page_order=None, device: int = 0):
+                 pool_rows: int = 16384, page_order=None, device: int = 0, fused: bool = False):
         self.shape, self.n_layers = shape, n_layers
-        self.ctx = nx.Nexus(shape, max_prefill_tokens=token_budget, max_prefill_reqs=max_prefill_reqs,
+        # fused: coupled iterations run as ONE batch (the engine without phase separation), so the prefill side of
+        # the context must hold the decode requests as well
+        extra = max_decode_reqs if fused else 0
+        self.ctx = nx.Nexus(shape, max_prefill_tokens=token_budget + extra, max_prefill_reqs=max_prefill_reqs + extra,
                             max_decode_reqs=max_decode_reqs, max_positions=max_positions, device=device, n_layers=n_layers)
         for l in range(n_layers):
             self.ctx.load_layer(l, weights_for_layer(l))
@@ -67,6 +70,7 @@ class TraceRunner:
         # for a running phase and hold the next one back.  The loop's own copies and gathers go to a side stream.
         self.side = torch.cuda.Stream(device=self.ctx.device)
         self.pool_rows = pool_rows
+        self.fused = fused
         self.records: List[IterationRecord] = []
         self.keep_outputs = False
         self.outputs = []          # (iteration, y_prefill, y_decode) when keep_outputs
@@ -107,8 +111,26 @@ class TraceRunner:
                 self.ctx.set_cu_split(*self.split)
             else:
                 self.ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
+        fb = None
+        if self.fused and pb is not None and db is not None:
+            # one chunked-prefill batch whose last requests are the decode requests, as one-token chunks
+            with torch.cuda.stream(self.side):
+                width = max(it.prefill_page_table.shape[1], it.decode_page_table.shape[1])
+
+                def pad(t):
+                    out = np.full((t.shape[0], width), -1, np.int32)
+                    out[:, :t.shape[1]] = t
+                    return out
+                n_p = int(it.prefill_cu_chunk[-1])
+                cu = np.concatenate([it.prefill_cu_chunk, n_p + 1 + np.arange(len(it.decode_req), dtype=np.int32)]).astype(np.int32)
+                fb = nx.DevPrefill(PrefillBatch(torch.cat([pb.x, db.x], 0), cu,
+                                                np.concatenate([it.prefill_prefix, it.decode_ctx]).astype(np.int32),
+                                                np.concatenate([pad(it.prefill_page_table), pad(it.decode_page_table)], 0)), self.ctx.device)
+            self.side.synchronize()
         t0 = time.perf_counter()
-        if pb is not None and db is not None:
+        if fb is not None:
+            self.ctx.fused_step(fb, len(it.decode_req), int(it.decode_ctx.max()) + 1, self.kv, layers=layers)
+        elif pb is not None and db is not None:
             self.ctx.mixed_step(pb, db, self.kv, layers=layers)
         elif pb is not None:
             self.ctx.prefill_chunk(pb, self.kv, layers=layers)
@@ -116,6 +138,8 @@ class TraceRunner:
             self.ctx.decode_step(db, self.kv, layers=layers)
         self.ctx.sync()
         step_ms = (time.perf_counter() - t0) * 1e3
+        if fb is not None:
+            pb.y, db.y = fb.y[:pb.x.shape[0]], fb.y[pb.x.shape[0]:]
         if end_s is None:
             end_s = now_s + step_ms * 1e-3
         self.sched.commit(end_s)

@@ -45,13 +45,13 @@ def _replay_request(oracle, m, ow, x_pool, rid, prompt, output, pool_rows):
     return y_prefill, y_decode
 
 
-@pytest.mark.parametrize("shape_name,split", [("tiny", (128, 128)), ("tiny", None)])
-def test_one_layer_loop_against_oracle_replay(nx, oracle, shape_name, split):
+@pytest.mark.parametrize("shape_name,split,fused", [("tiny", (128, 128), False), ("tiny", None, False), ("tiny", None, True)])
+def test_one_layer_loop_against_oracle_replay(nx, oracle, shape_name, split, fused):
     """A short trace through one layer: prompts of several chunks, a decode pool of 4 that makes requests wait, a KV
     pool small enough to block admissions.  Decisions must equal the oracle's loop; every prefill row and every
     decode row the GPU produced must match the oracle's replay of that request."""
     from paper_2507_06608_amd.serve import TraceRunner
-    print(f"[case] one-layer loop, {shape_name}, split {split}", flush=True)
+    print(f"[case] one-layer loop, {shape_name}, split {split}, fused {fused}", flush=True)
     shape = synth.SHAPES[shape_name]
     rng = np.random.default_rng(5)
     trace, t = [], 0.0
@@ -62,7 +62,7 @@ def test_one_layer_loop_against_oracle_replay(nx, oracle, shape_name, split):
     w = synth.make_weights(shape, 3)
     run = TraceRunner(shape, 1, lambda l: w, policy=nx.PREFILL_SPF, token_budget=budget, max_decode_reqs=cap,
                       n_pages=n_pages, gamma=gamma, max_prefill_reqs=max_prefill, max_positions=1024, split=split, seed=1,
-                      pool_rows=4096, page_order=rng.permutation(n_pages))
+                      pool_rows=4096, page_order=rng.permutation(n_pages), fused=fused)
     run.keep_outputs = True
     run.submit(trace)
     ref = _oracle_loop(sch.SPF, trace, budget, cap, shape.page_size, n_pages, gamma, max_prefill)
@@ -243,12 +243,17 @@ def test_cfg4_decoupled_loops_cut_time_between_tokens(nx, rate, horizon):
     common = dict(policy=nx.PREFILL_SPF, token_budget=1024, max_decode_reqs=128, n_pages=n_pages, gamma=15.0,
                   max_prefill_reqs=8, seed=2)
     out = {}
-    modes = [("coupled, unpartitioned", TraceRunner, None, nx.PREFILL_SPF), ("coupled, 160/96", TraceRunner, (160, 96), nx.PREFILL_SPF),
+    modes = [("coupled, unpartitioned", TraceRunner, None, nx.PREFILL_SPF), ("coupled, fused single batch", "fused", None, nx.PREFILL_SPF),
+             ("coupled, 160/96", TraceRunner, (160, 96), nx.PREFILL_SPF),
              ("decoupled, 160/96", DecoupledRunner, (160, 96), nx.PREFILL_SPF)]
     if rate > 4.0:
         modes.append(("decoupled, 160/96, FCFS prefill", DecoupledRunner, (160, 96), nx.PREFILL_FCFS))
     for name, cls, split, policy in modes:
         common["policy"] = policy
+        if cls == "fused":
+            cls, common["fused"] = TraceRunner, True
+        else:
+            common.pop("fused", None)
         run = cls(shape, shape.n_layers, weights, split=split, **common)
         run.submit(trace)
         if cls is DecoupledRunner:
