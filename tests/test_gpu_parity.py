@@ -136,6 +136,28 @@ def test_ragged_and_gqa_shapes(nx, oracle, name, shape, chunks, prefixes, ctx):
     g["ctx"].close()
 
 
+def test_maximum_context_length(nx, oracle):
+    """The longest context a prefill workgroup can address (2048 pages = 32768 positions): a 64-token chunk that
+    ends exactly there, a decode request whose new token is the 32768th, and one position more is refused."""
+    _announce("maximum context")
+    sh = EXTRA_SHAPES["gqa4"]
+    wl = synth.make_workload("max context", sh, 5, chunk_lens=[64], prefix_lens=[32768 - 64], decode_ctx=[32767, 0, 20000])
+    w = synth.make_weights(sh, 5)
+    ref = run_oracle(oracle, wl, w)
+    g = _gpu_run(nx, wl, w, "mixed", split=(128, 128))
+    assert_close("y_prefill", f32(g["y_p"]), ref["y_p"])
+    assert_close("y_decode", f32(g["y_d"]), ref["y_d"])
+    check_pools("max context", wl, g["kv"], ref, expected_touched(wl), g["before"])
+    g["ctx"].close()
+    over = synth.make_workload("one too many", sh, 5, chunk_lens=[64], prefix_lens=[32768 - 63], decode_ctx=[10])
+    ctx = nx.context_for(over)
+    ctx.load_layer(0, w)
+    kv = ctx.make_kv(over.k_pool, over.v_pool)
+    with pytest.raises(nx.NexusError):
+        ctx.prefill_chunk(nx.DevPrefill(over.prefill, ctx.device), kv)
+    ctx.close()
+
+
 def test_unwritten_cache_slots_may_hold_nan(nx, oracle):
     """Slots past a request's length are never read: fill every slot the step neither reads nor writes with NaN."""
     _announce("NaN in unread slots")

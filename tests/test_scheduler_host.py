@@ -194,3 +194,36 @@ def test_phase_tick_call_order_errors():
     with pytest.raises(nx.NexusError):
         s.next_phase(nx.PHASE_DECODE, 1.0)           # coupled iteration open
     s.commit(2.0)
+
+
+def test_spf_against_fcfs_under_queueing_on_the_virtual_clock():
+    """The ablation of Sec. 6.5 in its host-only form: the trace-driven configuration's length mix at an arrival
+    rate that keeps the prefill queue non-empty (the budget of 1024 tokens per 50 ms iteration serves ~14 requests/s
+    of this mix; 14/s are offered for 60 s).  Shortest-prompt-first halves the mean TTFT and cuts the median almost
+    fivefold; the library and the oracle agree on every sample."""
+    from paper_2507_06608_amd import synth
+    trace = synth.poisson_trace(7, rate=14.0, horizon_s=60.0, output_cap=64)
+    res = {}
+    for name, policy in (("fcfs", sch.FCFS), ("spf", sch.SPF)):
+        lib_s = nx.Scheduler(policy, 1024, 128, 16, 1 << 16, gamma=15.0, max_prefill_reqs=8)
+        ora = sch.Loop(policy, 1024, 128, 16, 1 << 16, gamma=15.0, max_prefill_reqs=8)
+        for a, p, o in trace:
+            lib_s.submit(a, p, o)
+            ora.submit(a, p, o)
+        i = 0
+        while any(r.finish_time is None for r in ora.reqs):
+            lib_s.next(i * 0.05)
+            ora.next(i * 0.05)
+            lib_s.commit((i + 1) * 0.05)
+            ora.commit((i + 1) * 0.05)
+            i += 1
+            assert i < 100000
+        np.testing.assert_array_equal(lib_s.samples(0), ora.ttft())
+        res[name] = lib_s.summary()
+        print(f"[spf vs fcfs] {name}: TTFT mean {res[name]['ttft_mean']:.3f} s, p50 {res[name]['ttft_p50']:.3f}, p95 {res[name]['ttft_p95']:.3f}, "
+              f"p99 {res[name]['ttft_p99']:.3f}, max {res[name]['ttft_max']:.3f} ({i} iterations)")
+    assert res["spf"]["ttft_mean"] < 0.6 * res["fcfs"]["ttft_mean"]
+    assert res["spf"]["ttft_p50"] < 0.5 * res["fcfs"]["ttft_p50"]
+    # the price: the longest prompts wait for the queue to thin out (gamma = 15 tokens per second of age moves an
+    # 8192-token prompt ahead of a 1000-token one only after eight minutes); everything is served once it does
+    assert res["spf"]["ttft_max"] > res["fcfs"]["ttft_max"] and res["spf"]["n_finished"] == len(trace)
