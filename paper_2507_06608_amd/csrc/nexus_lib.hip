@@ -133,6 +133,9 @@ enum GemmVariant {
                   //   with several such tiles per CU of the share (same per-element summation order as GV_P128)
     GV_S64,       // gemm_stream_kernel, 128 features x 64 tokens, 4 waves: decode batches of 33..64
     GV_S32,       // gemm_stream_kernel, 128 features x 32 tokens, 4 waves: decode batches of at most 32
+    GV_S64W,      // gemm_stream_kernel, 256 features x 64 tokens (two feature strips per wave): on a small CU share
+                  //   every workgroup re-reads the activations through the same per-CU load path as the weights, and
+                  //   twice the features per activation byte is worth more than twice the workgroups
     GV_R64,       // gemm_dl_kernel with the extent of GV_S64 / GV_S32: k ranges shorter than the streaming
     GV_R32,       //   kernel's pipeline (hidden sizes below 128)
     GV_COUNT
@@ -208,6 +211,7 @@ static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipSt
         case GV_P256: return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI>(a, grid, s);
         case GV_S64: return launch_gemm_stream_t<1, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S32: return launch_gemm_stream_t<1, 1, 4, 4, kStreamDepth, EPI>(a, grid, s);
+        case GV_S64W: return launch_gemm_stream_t<2, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_R64: return launch_gemm_t<4, 2, 2, 2, 4, 4, EPI, false>(a, grid, s);
         default: return launch_gemm_t<4, 1, 4, 1, 4, 4, EPI, false>(a, grid, s);
     }
@@ -286,8 +290,11 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
         const long est256 = (n256 + r.cus - 1) / r.cus * 132;
         if (est256 < est128) variant = GV_P256, FS = 8, TS = 8;
     }
+    // Measured on 64 of the 256 CUs (T = 64): gate/up 113 -> 98 us, down 55 -> 48, O 21.6 -> 18.9 with the wide
+    // variant, QKV (too few workgroups left) 27 -> 30; on 96 CUs and more the narrow one wins or ties.
+    if (variant == GV_S64 && r.cus <= 64 && (long)((n_ftiles + 7) / 8) * p.S >= 2L * r.cus - r.cus / 4) variant = GV_S64W, FS = 8;
     const int last_ksteps = Kp / kGemmBK - (p.S - 1) * p.ksteps_per_split;  // the shortest k range of the grid
-    if (last_ksteps < kStreamDepth) variant = variant == GV_S64 ? GV_R64 : variant == GV_S32 ? GV_R32 : variant;
+    if (last_ksteps < kStreamDepth) variant = (variant == GV_S64 || variant == GV_S64W) ? (FS = 4, GV_R64) : variant == GV_S32 ? GV_R32 : variant;
     a.n_tblk = (a.n_ttiles + TS - 1) / TS;
     a.n_xcd = r.n_xcd;
     // Tiles resident on one XCD at a time form a 4 x (residents / 4) rectangle instead of a row of token blocks:
