@@ -28,20 +28,25 @@ def _oracle_loop(policy, trace, budget, cap, ps, n_pages, gamma, max_prefill):
 
 
 def _replay_request(oracle, m, ow, x_pool, rid, prompt, output, pool_rows):
-    """Layer outputs of one request from its synthetic inputs alone: the prompt in one shot (chunked prefill equals
-    one-shot prefill), then its decode steps in order."""
+    """Outputs of the layer stack for one request from its synthetic inputs alone: the prompt in one shot (chunked
+    prefill equals one-shot prefill), then its decode steps in order.  ow: one layer's weights or a list of them."""
     from paper_2507_06608_amd.serve import token_rows
+    ows = ow if isinstance(ow, list) else [ow]
     n_pages = sch.pages_for(prompt + output - 1, m.page_size)
-    kp = np.zeros((n_pages, m.n_kv_heads, m.page_size, m.head_dim), np.float32)
-    vp = np.zeros_like(kp)
+    kps = [np.zeros((n_pages, m.n_kv_heads, m.page_size, m.head_dim), np.float32) for _ in ows]
+    vps = [np.zeros_like(kps[0]) for _ in ows]
     table = np.arange(n_pages, dtype=np.int32)[None, :]
-    xp = x_pool[token_rows(rid, 0, prompt, pool_rows)]
-    y_prefill = oracle.layer_prefill(m, ow, xp, np.array([0, prompt], np.int32), np.array([0], np.int32), table, kp, vp)
+    x = x_pool[token_rows(rid, 0, prompt, pool_rows)]
+    for l, w in enumerate(ows):
+        x = oracle.layer_prefill(m, w, x, np.array([0, prompt], np.int32), np.array([0], np.int32), table, kps[l], vps[l])
+    y_prefill = x
     y_decode = []
     for j in range(output - 1):
         ctx = prompt + j
-        xd = x_pool[token_rows(rid, ctx, 1, pool_rows)]
-        y_decode.append(oracle.layer_decode(m, ow, xd, np.array([ctx], np.int32), table, kp, vp)[0])
+        x = x_pool[token_rows(rid, ctx, 1, pool_rows)]
+        for l, w in enumerate(ows):
+            x = oracle.layer_decode(m, w, x, np.array([ctx], np.int32), table, kps[l], vps[l])
+        y_decode.append(x[0])
     return y_prefill, y_decode
 
 
@@ -150,12 +155,13 @@ def test_cfg4_trace_48_layers_200_iterations(nx):
     assert ref.prefill_tokens > 0 and ref.decode_tokens > 0
 
 
-def test_decoupled_phase_loops_one_layer_against_oracle(nx, oracle):
+@pytest.mark.parametrize("n_layers", [1, 2])
+def test_decoupled_phase_loops_one_layer_against_oracle(nx, oracle, n_layers):
     """The two phases ticking independently on their own streams.  The order of ticks depends on how long the GPU
     takes, so the decisions are checked by replaying the logged calls, with their times, on the oracle's loop; the
     outputs do not depend on timing at all and are checked row by row against the oracle replay of each request."""
     from paper_2507_06608_amd.serve import DecoupledRunner
-    print("[case] decoupled one-layer loop, tiny", flush=True)
+    print(f"[case] decoupled loop, tiny, {n_layers} layer(s)", flush=True)
     shape = synth.SHAPES["tiny"]
     rng = np.random.default_rng(6)
     trace, t = [], 0.0
@@ -163,8 +169,8 @@ def test_decoupled_phase_loops_one_layer_against_oracle(nx, oracle):
         t += float(rng.exponential(0.002))
         trace.append((t, int(min(900, max(1, rng.lognormal(np.log(250.0), 0.8)))), int(rng.integers(1, 25))))
     budget, cap, n_pages, gamma, max_prefill = 128, 4, 170, 15.0, 4
-    w = synth.make_weights(shape, 3)
-    run = DecoupledRunner(shape, 1, lambda l: w, policy=nx.PREFILL_SPF, token_budget=budget, max_decode_reqs=cap,
+    ws = [synth.make_weights(shape, 3, layer=l) for l in range(n_layers)]
+    run = DecoupledRunner(shape, n_layers, lambda l: ws[l], policy=nx.PREFILL_SPF, token_budget=budget, max_decode_reqs=cap,
                           n_pages=n_pages, gamma=gamma, max_prefill_reqs=max_prefill, max_positions=1024, split=(128, 128),
                           seed=1, pool_rows=4096, page_order=rng.permutation(n_pages))
     run.keep_outputs = True
@@ -191,7 +197,7 @@ def test_decoupled_phase_loops_one_layer_against_oracle(nx, oracle):
     print(f"[decoupled] {len(run.calls)} scheduler calls, {overlapped} ticks launched while the other phase was in flight", flush=True)
     assert overlapped > 0
 
-    m, ow = oracle_model(oracle, shape), oracle_weights(w)
+    m, ow = oracle_model(oracle, shape), [oracle_weights(w) for w in ws]
     x_pool = f32(run.x_pool)
     replay = {rid: _replay_request(oracle, m, ow, x_pool, rid, p, o, run.pool_rows) for rid, (a, p, o) in enumerate(trace)}
     n_rows = 0
