@@ -364,9 +364,10 @@ static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
             done = true;                                                                                             \
         }                                                                                                            \
         a.tiles_per_req = (r.pb->max_chunk + 32 * SPB - 1) / (32 * SPB);                                             \
+        if ((long)a.n_reqs * a.tiles_per_req > 65535) return fail(NEXUS_ESHAPE, "prefill attention grid too large (%d requests x %d tiles)", a.n_reqs, a.tiles_per_req); \
         {                                                                                                            \
             Tracer tr(c, r.phase, NEXUS_K_ATTN_PREFILL, r.s);                                                        \
-            hipLaunchKernelGGL(kern, dim3(a.n_reqs * a.tiles_per_req, c->m.n_kv_heads, a.n_splits), dim3(64 * GG * SPB), smem, r.s, a); \
+            hipLaunchKernelGGL(kern, dim3(c->m.n_kv_heads, a.n_reqs * a.tiles_per_req, a.n_splits), dim3(64 * GG * SPB), smem, r.s, a); \
         }                                                                                                            \
         HIP_TRY(hipGetLastError());                                                                                  \
         if (a.n_splits > 1) {                                                                                        \
