@@ -12,7 +12,7 @@ What it follows, in the paper's order and notation:
 * Alg. 1: the two-phase greedy adjustment and the buffer zone.
 
 Nothing here is imported by the product; only tests/ and the GPU validation test call it.  Readings taken where
-the paper leaves a choice are marked "reading" below and listed in the design doc.
+the paper leaves a choice are marked "reading" below.
 """
 from __future__ import annotations
 

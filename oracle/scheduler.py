@@ -12,7 +12,7 @@ What it follows:
 * Sec. 6.1 metrics: TTFT (arrival to first token), TBT (time between consecutive tokens of a request),
   normalised latency (end-to-end latency over the number of output tokens).
 
-Readings taken where the paper leaves a choice (marked "reading"; listed in the design doc):
+Readings taken where the paper leaves a choice (marked "reading" where they occur in the code):
 
 * Alg. 2 scores `remaining`, Eq. 10 the prompt length: `remaining` is used (they agree until a request has been
   partly prefilled).  Age is in seconds, gamma in tokens per second.  Ties: earlier arrival, then lower id.
