@@ -110,11 +110,13 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void attn_decode_kernel(AttnDeco
         const bf16_t *vp = a.v_pool + ((size_t)(g4 < 2 ? pageA : pageB) * a.Hkv + kvh) * BLK + ((g4 & 1) * HD + col) * 8;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            r.k1[kk] = *(const u32x4 *)(kp + kk * 512);
-            r.k2[kk] = *(const u32x4 *)(kp + kk * 512 + 64);
+            // K/V pages are read once per kv head: non-temporal loads, so the stream does not evict what the prefill
+            // phase shares through L2
+            r.k1[kk] = __builtin_nontemporal_load((const u32x4 *)(kp + kk * 512));
+            r.k2[kk] = __builtin_nontemporal_load((const u32x4 *)(kp + kk * 512 + 64));
         }
 #pragma unroll
-        for (int i = 0; i < RT; ++i) r.v[i] = *(const u32x4 *)(vp + i * 128);
+        for (int i = 0; i < RT; ++i) r.v[i] = __builtin_nontemporal_load((const u32x4 *)(vp + i * 128));
     };
     auto compute_pair = [&](PairRegs &r, int pp) {
         f32x4 s1 = {0, 0, 0, 0}, s2 = {0, 0, 0, 0};

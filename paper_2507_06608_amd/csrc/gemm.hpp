@@ -401,7 +401,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_stream_kernel(GemmArgs a) {
 #pragma unroll
         for (int i = 0; i < FW; ++i)
 #pragma unroll
-            for (int kt = 0; kt < BKT; ++kt) wr[D][i][kt] = *(const f16x8 *)(wb[i] + koff + kt * 1024);
+            for (int kt = 0; kt < BKT; ++kt)  // every weight byte is used once: streaming (non-temporal) loads leave the caches to the other phase
+                wr[D][i][kt] = __builtin_nontemporal_load((const f16x8 *)(wb[i] + koff + kt * 1024));
     };
 
     f32x16 acc[FW][TW];
