@@ -135,12 +135,14 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     auto issue = [&](int tile) {
         if (w >= LW) return;
         char *dst = smem + (tile % NST) * STAGE;
+        // the tile's two page ids, read once
+        const int page_a = tile * 2 < pages_valid ? s_pt[tile * 2] : 0;
+        const int page_b = tile * 2 + 1 < pages_valid ? s_pt[tile * 2 + 1] : 0;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int u = w + LW * i;
             const int which = u / UPB;
-            const int lp = tile * 2 + (which & 1);
-            const int page = lp < pages_valid ? s_pt[lp] : 0;
+            const int page = (which & 1) ? page_b : page_a;
             const char *src = (const char *)((which < 2 ? a.k_pool : a.v_pool) + ((size_t)page * a.Hkv + kvh) * (kPage * HD)) +
                               (u % UPB) * 1024 + lane * 16;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
@@ -169,11 +171,23 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
             for (int e = 0; e < 16; ++e) s[e] = 0.f;
             // operand A row (lane % 32): page row / 16, slot row % 16 (slots are rows as they stand); k-slot group g
             const char *kp = sK + (col >> 4) * BLK + (col & 15) * 16 + g * 256;
+            // All operand reads of the tile are issued up front, into registers of their own: the K fragments so that
+            // the QK^T chain waits for LDS once and not before every instruction, the V fragments so that their
+            // latency passes under the softmax.
+            bf16x8 kf[KK];
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                bf16x8 kf = *(const bf16x8 *)(kp + kk * 512);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
-            }
+            for (int kk = 0; kk < KK; ++kk) kf[kk] = *(const bf16x8 *)(kp + kk * 512);
+            // V block [2 token groups][hd][8]: lane (col, g) reads hd row 32 i + col of token group g
+            u32x4 vf[2][RT];
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int i = 0; i < RT; ++i) vf[pg][i] = *(const u32x4 *)(sV + pg * BLK + (g * HD + col) * 16 + i * 512);
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
+            // keep that order: the scheduler otherwise sinks each read next to its use and waits for it there
+            __builtin_amdgcn_sched_group_barrier(0x100, KK + 2 * RT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, KK, 0);
             // Register 4b + j is row 8b + 4g + j: page b / 2, slot 8(b%2) + 4g + j, which holds token
             // 8g + 4(b%2) + j.  So registers 8p .. 8p+7 are tokens 8g .. 8g+7 of page p, in order.
             const bool need_mask = key0 + kAttnTile - 1 > wave_min_pos;
@@ -214,25 +228,25 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
             }
             // V slots at or past kmax may hold anything (even NaN): their probability is exactly 0, but 0 * NaN is
             // not, so the last tile zeroes them as it reads them.
-            const bool v_tail = key0 + kAttnTile > kmax;
+            if (key0 + kAttnTile > kmax) {  // uniform: the last tile of the block only
+#pragma unroll
+                for (int pg = 0; pg < 2; ++pg) {
+                    const int left = kmax - (key0 + 16 * pg + 8 * g);  // tokens of this group that are valid
+#pragma unroll
+                    for (int i = 0; i < RT; ++i)
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (e >= left) vf[pg][i][e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                }
+            }
 #pragma unroll
             for (int pg = 0; pg < 2; ++pg) {
                 bf16x8 pf;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[8 * pg + e];
-                // V block [2 token groups][hd][8]: lane (col, g) reads hd row 32 i + col of token group g
-                const char *vp = sV + pg * BLK + (g * HD + col) * 16;
-                const int left = kmax - (key0 + 16 * pg + 8 * g);  // tokens of this group that are valid
 #pragma unroll
-                for (int i = 0; i < RT; ++i) {
-                    u32x4 vf = *(const u32x4 *)(vp + i * 512);
-                    if (v_tail) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (e >= left) vf[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    }
-                    o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf, pf, o_acc[i], 0, 0, 0);
-                }
+                for (int i = 0; i < RT; ++i)
+                    o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf[pg][i], pf, o_acc[i], 0, 0, 0);
             }
         }
     }
