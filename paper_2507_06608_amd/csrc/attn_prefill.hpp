@@ -95,6 +95,16 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     attn_split_range(n_kv_tiles, a.n_splits, z, t_begin, t_end);
     if (t_begin >= t_end) return;  // the merge kernel applies the same rule and never reads this split
 
+    // A SIMD holds two of these wavefronts (one of each resident workgroup), and each alternates between a matrix
+    // phase (QK^T, PV) and a vector phase (softmax) of about the same length.  At equal priority the two fall into
+    // step -- both in the same phase, one unit idle -- and stay there; with the wavefront in the odd hardware slot
+    // always served first, the other one fills the unit it leaves free and the phases interleave.
+    {
+        unsigned hw_id;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
+        if (hw_id & 1) __builtin_amdgcn_s_setprio(2);
+    }
+
     // Page ids of the request, staged once.  Ids out of range become page 0: every load then has a valid address
     // (and every wavefront issues the same number of loads per tile); what such a page delivers is masked out.
     for (int i = tid; i < pages_valid; i += 64 * NW) {
@@ -205,7 +215,7 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
 #pragma unroll
             for (int e = 0; e < 16; ++e) mraw = fmaxf(mraw, s[e]);
             float mx = fmaxf(m_run, mraw * a.scale_log2e);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = xor32_max(mx);
             // a row may see no key at all in this split's range yet: keep the arithmetic finite
             const float mref = mx == -INFINITY ? 0.f : mx;
             const float alpha = __builtin_amdgcn_exp2f(m_run - mref);

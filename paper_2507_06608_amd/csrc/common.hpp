@@ -72,4 +72,13 @@ __host__ __device__ __forceinline__ int kslot(int tok) { return (tok & 3) | ((to
 __host__ __device__ __forceinline__ int kblk_offset(int tok, int i) { return ((i >> 3) * kPage + kslot(tok)) * 8 + (i & 7); }
 __host__ __device__ __forceinline__ int vblk_offset(int tok, int i, int hd) { return ((tok >> 3) * hd + i) * 8 + (tok & 7); }
 
+// max over the lane pair (l, l ^ 32) in both lanes: the half-wave swap instruction of gfx950 puts the low halves
+// of its two operands into one result and the high halves into the other, without the LDS round trip of a
+// generic shuffle.
+__device__ __forceinline__ float xor32_max(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 }  // namespace nexus
