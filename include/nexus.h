@@ -185,7 +185,9 @@ int nexus_kv_export(nexus_ctx *ctx, const nexus_kv_cache *kv, int layer, void *k
  * Selects the CU share of each phase: prefill_cus + decode_cus <= nexus_cu_count(), both positive multiples of
  * 8.  The chip is eight accelerator dies (XCDs) with an L2 each; every XCD gives each phase the same number of
  * its CUs (a queue's CU mask must keep at least one CU in every XCD, and workgroups are dealt to XCDs
- * round-robin whatever the mask).  The two phases then run on two streams whose CU masks are disjoint.  Only
+ * round-robin whatever the mask).  Inside an XCD the workgroups are likewise dealt evenly to its 4 shader engines,
+ * so a share runs at full speed only when it is a multiple of 32 (4 per XCD); other multiples of 8 are accepted and
+ * run at the speed of the next lower multiple of 32.  The two phases then run on two streams whose CU masks are disjoint.  Only
  * one partitioned stream pair exists at a time: selecting a different split synchronises and destroys the
  * current pair and creates the new one (about 12 ms; more than one pair alive made some pairs dispatch the
  * decode kernels late on MI355X).  (NEXUS_CUS_ALL, NEXUS_CUS_ALL) selects the unpartitioned layout: one unmasked

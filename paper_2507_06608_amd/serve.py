@@ -214,7 +214,11 @@ class DecoupledRunner(TraceRunner):
         assert self.split is not None, "independent phase loops need a partitioned layout"
         # the partition controller (Alg. 1), off unless enable_controller() is called
         self.calibration = None
-        self.ctrl = dict(alpha=1.3, beta=1.1, delta=2, kv_switch=0.7, total=32)
+        # The controller moves the split in steps of 32 CUs (4 per XCD, one per shader engine of every XCD): workgroups
+        # are dealt to the shader engines evenly whatever the CU mask, so a share that leaves one engine a CU short
+        # runs no faster than the next lower multiple of 32 (measured on MI355X: decode on 72, 80 and 88 CUs takes
+        # the time it takes on 64).
+        self.ctrl = dict(alpha=1.3, beta=1.1, delta=1, kv_switch=0.7, total=8)
         self.switches: List[tuple] = []  # (time_s, old prefill CUs, new prefill CUs, host ms spent switching)
         self._last_shape = {}            # phase -> the quantities of its last batch the cost model needs
         self.calls: List[tuple] = []     # (op, phase, time, batch) in call order, for replay against another scheduler
@@ -260,13 +264,15 @@ class DecoupledRunner(TraceRunner):
         alg_p, alg_d = nx.cost_describe(self.shape, self.n_layers, p["tokens"], p["pairs"], p["kv"], d["reqs"], d["kv"])
         model = self.calibration.model(alg_p, alg_d)
         c = self.ctrl
-        cur = self.split[0] // 8
+        n_cus = self.ctx.cu_count
+        step = n_cus // c["total"]
+        cur = self.split[0] // step
         new = model.partition_controller(kv_usage, c["kv_switch"], cur, c["total"], c["alpha"], c["beta"], c["delta"])
         if new != cur:
             t_l = time.perf_counter()
-            self.ctx.set_cu_split(8 * new, 256 - 8 * new)     # waits for what is in flight on the old pair
-            self.switches.append((now, 8 * cur, 8 * new, (time.perf_counter() - t_l) * 1e3))
-            self.split = (8 * new, 256 - 8 * new)
+            self.ctx.set_cu_split(step * new, n_cus - step * new)     # waits for what is in flight on the old pair
+            self.switches.append((now, self.split[0], step * new, (time.perf_counter() - t_l) * 1e3))
+            self.split = (step * new, n_cus - step * new)
 
     def run_decoupled(self, arrivals: Sequence[float], max_wall_s: float = 120.0):
         """Runs until every submitted request has finished.  `arrivals`: the arrival times that were submitted

@@ -412,7 +412,7 @@ def test_cfg4_partition_controller_in_the_loop(nx):
         if dynamic:
             print(f"[controller] {len(run.switches)} switches: " + ", ".join(f"{a}->{b} CUs at {t:.2f} s ({ms:.1f} ms)" for t, a, b, ms in run.switches), flush=True)
             assert 1 <= len(run.switches) <= 60          # it acts, and the buffer zone bounds how often
-            assert all(abs(a - b) >= 16 for _, a, b, _ in run.switches)      # never by less than delta = 2 steps of 8 CUs
+            assert all(abs(a - b) >= 32 and b % 32 == 0 for _, a, b, _ in run.switches)      # whole steps of 32 CUs
         run.close()
         del run
         torch.cuda.empty_cache()
