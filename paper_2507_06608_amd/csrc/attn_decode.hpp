@@ -28,7 +28,7 @@ struct AttnDecodeArgs {
     const bf16_t *k_pool, *v_pool;
     int n_pages, Hq, Hkv;
     float scale_log2e;
-    float *part_o;   // [B][Hkv][max_spans][G][hd]
+    f16_t *part_o;   // [B][Hkv][max_spans][G][hd]: each span's output normalised by its own sum, half
     float *part_ml;  // [B][Hkv][max_spans][G][2]  (running max in the log2 domain, sum)
     f16_t *out;      // merge output: half, P32 [B rows][Hq*hd]
     // Decode requests riding in a chunked-prefill batch (the fused single-batch step): their queries sit in the
@@ -194,11 +194,14 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void attn_decode_kernel(AttnDeco
     if (col >= G) return;
     // register e of o_acc[i] is hd = 16 i + 4 g4 + e
     const size_t item = ((size_t)j * a.Hkv + kvh) * a.max_spans + span;
-    float *po = a.part_o + (item * G + col) * HD;
+    // stored normalised (an average of value rows, inside half's range whenever the values are) and in half: half
+    // the bytes of an fp32 partial, at a rounding 4x finer than the bf16 the values came in; a span is never empty
+    const float inv_l = 1.0f / l_run;
+    f16_t *po = a.part_o + (item * G + col) * HD;
 #pragma unroll
     for (int i = 0; i < RT; ++i) {
-        float4 o = {o_acc[i][0], o_acc[i][1], o_acc[i][2], o_acc[i][3]};
-        *(float4 *)(po + 16 * i + 4 * g4) = o;
+        uint2 o = {packh2(o_acc[i][0] * inv_l, o_acc[i][1] * inv_l), packh2(o_acc[i][2] * inv_l, o_acc[i][3] * inv_l)};
+        *(uint2 *)(po + 16 * i + 4 * g4) = o;
     }
     if (g4 == 0) {
         float2 ml = {m_run, l_run};
@@ -206,8 +209,8 @@ __global__ __launch_bounds__(kDecWaves * 64, 2) void attn_decode_kernel(AttnDeco
     }
 }
 
-// Merge of the span results of one (request, query head): o = sum_s 2^(m_s - m) o_s / sum_s 2^(m_s - m) l_s,
-// spans taken in order.  One wavefront per (request, query head); output in P32 order for the O projection.
+// Merge of the span results of one (request, query head): with w_s = 2^(m_s - m) l_s and o_s the span's normalised
+// output, o = sum_s w_s o_s / sum_s w_s, spans taken in order.  One wavefront per (request, query head); output in P32 order for the O projection.
 template <int HD, int G>
 __global__ __launch_bounds__(64) void attn_merge_kernel(AttnDecodeArgs a) {
     const int j = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq;
@@ -230,19 +233,31 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnDecodeArgs a) {
         for (int o = 32; o > 0; o >>= 1) cm = fmaxf(cm, __shfl_xor(cm, o));
         const float m_new = fmaxf(m, cm);
         const float rescale = exp2f(m - m_new);  // 0 on the first chunk (m = -inf), spans are never empty
-        const float wgt = s < n_spans ? exp2f(ml.x - m_new) : 0.f;
-        float part = wgt * ml.y;
+        const float wl = s < n_spans ? exp2f(ml.x - m_new) * ml.y : 0.f;  // weight of the span's normalised output
+        float part = wl;
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
         denom = denom * rescale + part;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] *= rescale;
         const int cnt = min(64, n_spans - base);
-        for (int k = 0; k < cnt; ++k) {
-            const float wk = __shfl(wgt, k);
-            const float *po = a.part_o + ((item0 + base + k) * G + col) * HD + lane * EPL;
+        // eight spans' rows at a time, fetched by loads that do not wait on one another; summed in span order
+        for (int k0 = 0; k0 < cnt; k0 += 8) {
+            uint32_t pv[8];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] += wk * po[e];
+            for (int u = 0; u < 8; ++u) {
+                pv[u] = 0;
+                if (k0 + u < cnt) {
+                    const f16_t *po = a.part_o + ((item0 + base + k0 + u) * G + col) * HD + lane * EPL;
+                    pv[u] = EPL == 2 ? *(const uint32_t *)po : (uint32_t)po[0];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float wk = __shfl(wl, (k0 + u) & 63);  // rows past cnt were read as zero
+                acc[0] += wk * h2f((f16_t)(pv[u] & 0xffffu));
+                if (EPL == 2) acc[EPL - 1] += wk * h2f((f16_t)(pv[u] >> 16));
+            }
         }
         m = m_new;
     }

@@ -32,8 +32,8 @@ struct AttnPrefillArgs {
     int n_pages, Hq, Hkv;
     float scale_log2e;  // log2(e) / sqrt(hd)
     int n_splits;       // gridDim.z
-    float *part_o;      // [n_splits][T][Hq][hd]   (n_splits > 1)
-    float *part_ml;     // [n_splits][T][Hq][2]
+    f16_t *part_o;      // [n_splits][T][Hq][hd]   (n_splits > 1): each split's output normalised by its own sum, half
+    float *part_ml;     // [n_splits][T][Hq][2]    its running max (log2 domain) and sum
     int T;
 };
 
@@ -266,13 +266,18 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     const int trow = c0 + local;
     // o_acc[i][4b + j] is hd = 32 i + 8 b + 4 g + j
     if (a.n_splits > 1) {
-        float *po = a.part_o + (((size_t)z * a.T + trow) * a.Hq + hq) * HD;
+        // The partial output is stored normalised (an average of value rows, so within half's range whenever the
+        // values are) and in half: half the bytes of an fp32 partial on the way out and into the merge, at a
+        // rounding 4x finer than the bf16 the values came in.  A row that saw no key in this split stores zeros.
+        const float inv_l = l_run > 0.f ? 1.0f / l_run : 0.f;
+        f16_t *po = a.part_o + (((size_t)z * a.T + trow) * a.Hq + hq) * HD;
 #pragma unroll
         for (int i = 0; i < RT; ++i)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                float4 x = {o_acc[i][4 * b + 0], o_acc[i][4 * b + 1], o_acc[i][4 * b + 2], o_acc[i][4 * b + 3]};
-                *(float4 *)(po + 32 * i + 8 * b + 4 * g) = x;
+                uint2 x = {packh2(o_acc[i][4 * b + 0] * inv_l, o_acc[i][4 * b + 1] * inv_l),
+                           packh2(o_acc[i][4 * b + 2] * inv_l, o_acc[i][4 * b + 3] * inv_l)};
+                *(uint2 *)(po + 32 * i + 8 * b + 4 * g) = x;
             }
         if (g == 0) {
             float2 ml = {m_run, l_run};
@@ -290,11 +295,20 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
         }
 }
 
-// Merge of the key-range splits of one (token, query head): o = sum_z 2^(m_z - m) o_z / sum_z 2^(m_z - m) l_z with
-// the splits taken in order.  One wavefront per (token, head); a split is read only if the main kernel ran it.
+// Merge of the key-range splits of one (token, query head): with w_z = 2^(m_z - m) l_z and o_z the split's normalised
+// output, o = sum_z w_z o_z / sum_z w_z, the splits taken in order.  One wavefront per (token, head); a split is read only if the main kernel ran it.
+constexpr int kAttnMaxSplits = 8;   // upper bound of the key-range split count (the merge unrolls over it)
+
+// One wavefront per (token, group of 512 / HD consecutive query heads): a lane owns 8 consecutive head dimensions of
+// one head, i.e. one 16-byte piece of each split's row and of the output row.
 template <int HD, int SPB>
 __global__ __launch_bounds__(64) void attn_prefill_merge_kernel(AttnPrefillArgs a) {
-    const int t = blockIdx.x / a.Hq, hq = blockIdx.x % a.Hq, lane = threadIdx.x;
+    constexpr int LPH = HD / 8;      // lanes per head
+    constexpr int HPW = 64 / LPH;    // heads per wavefront
+    const int lane = threadIdx.x;
+    const int groups = (a.Hq + HPW - 1) / HPW;
+    const int t = blockIdx.x / groups;
+    const int hq = (blockIdx.x % groups) * HPW + lane / LPH, d0 = (lane % LPH) * 8;
     int r = 0;
     while (r + 1 < a.n_reqs && a.cu_chunk[r + 1] <= t) ++r;
     const int c0 = a.cu_chunk[r], n_r = a.cu_chunk[r + 1] - c0, local = t - c0;
@@ -302,32 +316,45 @@ __global__ __launch_bounds__(64) void attn_prefill_merge_kernel(AttnPrefillArgs 
     int blk_last = (lt + 1) * 32 * SPB;
     if (blk_last > n_r) blk_last = n_r;
     const int n_kv_tiles = (a.prefix_len[r] + blk_last + kAttnTile - 1) / kAttnTile;
-    float m = -INFINITY;
-    for (int z = 0; z < a.n_splits; ++z) {
-        int b, e;
-        attn_split_range(n_kv_tiles, a.n_splits, z, b, e);
-        if (b < e) m = fmaxf(m, a.part_ml[(((size_t)z * a.T + t) * a.Hq + hq) * 2]);
+    if (hq >= a.Hq) return;
+    // Every split's statistics, then every split's row, are fetched by loads that do not depend on one another
+    // (the loops are unrolled over the largest split count): two memory latencies per output row, not one per split.
+    float mz[kAttnMaxSplits], lz[kAttnMaxSplits];
+#pragma unroll
+    for (int z = 0; z < kAttnMaxSplits; ++z) {
+        int b = 0, e = 0;
+        if (z < a.n_splits) attn_split_range(n_kv_tiles, a.n_splits, z, b, e);
+        float2 ml = {-INFINITY, 0.f};
+        if (b < e) ml = *(const float2 *)(a.part_ml + (((size_t)z * a.T + t) * a.Hq + hq) * 2);
+        mz[z] = ml.x, lz[z] = ml.y;
     }
-    constexpr int EPL = HD / 64;
-    float acc[EPL], denom = 0.f;
+    float m = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
-    for (int z = 0; z < a.n_splits; ++z) {
-        int b, e;
-        attn_split_range(n_kv_tiles, a.n_splits, z, b, e);
-        if (b >= e) continue;
-        const size_t item = ((size_t)z * a.T + t) * a.Hq + hq;
-        const float2 ml = *(const float2 *)(a.part_ml + item * 2);
-        const float wgt = exp2f(ml.x - m);  // split 0 always holds key 0, so m is finite
-        denom += wgt * ml.y;
-        const float *po = a.part_o + item * HD + lane * EPL;
+    for (int z = 0; z < kAttnMaxSplits; ++z) m = fmaxf(m, mz[z]);  // split 0 always holds key 0, so m is finite
+    u32x4 pz[kAttnMaxSplits];
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] += wgt * po[i];
+    for (int z = 0; z < kAttnMaxSplits; ++z) {
+        pz[z] = u32x4{0, 0, 0, 0};
+        if (lz[z] > 0.f) pz[z] = *(const u32x4 *)(a.part_o + (((size_t)z * a.T + t) * a.Hq + hq) * HD + d0);
+    }
+    float acc[8], denom = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int z = 0; z < kAttnMaxSplits; ++z) {  // in split order
+        const float wl = lz[z] > 0.f ? exp2f(mz[z] - m) * lz[z] : 0.f;
+        denom += wl;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += wl * h2f((f16_t)(pz[z][i] & 0xffffu));
+            acc[2 * i + 1] += wl * h2f((f16_t)(pz[z][i] >> 16));
+        }
     }
     const float inv = 1.0f / denom;
-    f16_t *dst = a.out + p32_offset(t, hq * HD + lane * EPL, a.Hq * HD);
-    if (EPL == 2) *(uint32_t *)dst = packh2(acc[0] * inv, acc[EPL - 1] * inv);
-    else dst[0] = f2h(acc[0] * inv);
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = packh2(acc[2 * i] * inv, acc[2 * i + 1] * inv);
+    *(u32x4 *)(a.out + p32_offset(t, hq * HD + d0, a.Hq * HD)) = o;  // 8 consecutive k are contiguous in that layout
 }
 
 }  // namespace nexus

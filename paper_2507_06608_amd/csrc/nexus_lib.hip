@@ -346,7 +346,7 @@ static int plan_attn_splits(int n_tokens, int n_q_heads, int max_total_len) {
     int S = (2048 + wave_tasks / 2) / wave_tasks;
     const int tiles = (max_total_len + kAttnTile - 1) / kAttnTile;
     S = std::min(S, tiles / 8);  // at least 8 key tiles per split
-    return std::max(1, std::min(S, 8));
+    return std::max(1, std::min(S, kAttnMaxSplits));
 }
 
 template <int HD>
@@ -372,7 +372,7 @@ static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
         HIP_TRY(hipGetLastError());                                                                                  \
         if (a.n_splits > 1) {                                                                                        \
             Tracer tr(c, r.phase, NEXUS_K_ATTN_MERGE, r.s);                                                          \
-            hipLaunchKernelGGL((attn_prefill_merge_kernel<HD, SPB>), dim3((r.T - r.fused_decode) * c->m.n_q_heads), dim3(64), 0, r.s, a); /* decode rows of a fused batch are not this kernel's */ \
+            hipLaunchKernelGGL((attn_prefill_merge_kernel<HD, SPB>), dim3((r.T - r.fused_decode) * ((c->m.n_q_heads * HD + 511) / 512)), dim3(64), 0, r.s, a); /* decode rows of a fused batch are not this kernel's */ \
         }                                                                                                            \
         break;                                                                                                       \
     }
@@ -458,7 +458,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
         a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads;
         a.scale_log2e = scale_log2e;
         a.n_splits = plan_attn_splits(r.T, m.n_q_heads, r.pb->max_total_len);
-        a.part_o = ws.part_o, a.part_ml = ws.part_ml, a.T = r.T;
+        a.part_o = (f16_t *)ws.part_o, a.part_ml = ws.part_ml, a.T = r.T;
         if (a.n_reqs > 0) NX_TRY(m.head_dim == 128 ? launch_attn_prefill<128>(r, a) : launch_attn_prefill<64>(r, a));
         if (r.fused_decode) {
             // the decode requests at the tail of the batch take the decode attention kernel: same queries (prefill
@@ -469,7 +469,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
             d.q = ws.q, d.ctx_len = r.pb->prefix_len + lead, d.page_table = r.pb->page_table + (size_t)lead * r.pb->max_pages;
             d.n_reqs = r.fused_decode, d.max_pages = r.pb->max_pages, d.max_spans = (r.fused_max_ctx + kSpan - 1) / kSpan;
             d.k_pool = k_pool, d.v_pool = v_pool, d.n_pages = r.kv->n_pages, d.Hq = m.n_q_heads, d.Hkv = m.n_kv_heads;
-            d.scale_log2e = scale_log2e, d.part_o = c->ws[NEXUS_PHASE_DECODE].part_o, d.part_ml = c->ws[NEXUS_PHASE_DECODE].part_ml;
+            d.scale_log2e = scale_log2e, d.part_o = (f16_t *)c->ws[NEXUS_PHASE_DECODE].part_o, d.part_ml = c->ws[NEXUS_PHASE_DECODE].part_ml;
             d.out = ws.attn, d.lead_cu = r.pb->cu_chunk, d.n_lead = lead, d.out_row0 = r.pb->n_tokens - r.fused_decode;
             NX_TRY(m.head_dim == 128 ? launch_attn_decode<128>(r, d) : launch_attn_decode<64>(r, d));
         }
@@ -478,7 +478,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
         a.q = ws.q, a.ctx_len = r.db->ctx_len, a.page_table = r.db->page_table, a.n_reqs = r.db->n_reqs;
         a.max_pages = r.db->max_pages, a.max_spans = (r.db->max_ctx + kSpan - 1) / kSpan;
         a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.Hq = m.n_q_heads, a.Hkv = m.n_kv_heads;
-        a.scale_log2e = scale_log2e, a.part_o = ws.part_o, a.part_ml = ws.part_ml, a.out = ws.attn;
+        a.scale_log2e = scale_log2e, a.part_o = (f16_t *)ws.part_o, a.part_ml = ws.part_ml, a.out = ws.attn;
         NX_TRY(m.head_dim == 128 ? launch_attn_decode<128>(r, a) : launch_attn_decode<64>(r, a));
     }
     // x1 = x + attn W_o^T, h2 = RMSNorm(x1): when the projection is split along K its reduction, the residual add
@@ -643,14 +643,14 @@ static int alloc_phase_ws(nexus_ctx *c, int phase, int maxT, int max_reqs) {
             const int S = plan_attn_splits(T, m.n_q_heads, c->lim.max_positions);
             if (S > 1) items = std::max(items, (size_t)S * T * m.n_q_heads);
         }
-        NX_TRY(dev_alloc(&w.part_o, items * m.head_dim, false));
+        NX_TRY(dev_alloc(&w.part_o, (items * m.head_dim + 1) / 2, false));  // half elements
         NX_TRY(dev_alloc(&w.part_ml, items * 2, false));
     } else {
         NX_TRY(dev_alloc(&w.q, (size_t)maxT * c->q_dim, true));
         w.max_spans = (c->lim.max_positions + kSpan - 1) / kSpan;
         const int G = m.n_q_heads / m.n_kv_heads;
         const size_t items = (size_t)maxT * m.n_kv_heads * w.max_spans * G;
-        NX_TRY(dev_alloc(&w.part_o, items * m.head_dim, false));
+        NX_TRY(dev_alloc(&w.part_o, (items * m.head_dim + 1) / 2, false));  // half elements
         NX_TRY(dev_alloc(&w.part_ml, items * 2, false));
     }
     NX_TRY(dev_alloc(&w.attn, p32_elems(Tp, c->q_dim), true));
