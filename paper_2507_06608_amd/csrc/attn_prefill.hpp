@@ -68,7 +68,8 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int32_t *s_pt = (int32_t *)(smem + NST * STAGE);
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar branches
     const int hg = w % G, strip = w / G;
     const int g = lane >> 5, col = lane & 31;
     // The kv head is the fastest grid index: workgroups are dealt to the 8 XCDs round-robin, so with 8 kv heads
@@ -105,14 +106,6 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
         if (hw_id & 1) __builtin_amdgcn_s_setprio(2);
     }
 
-    // Page ids of the request, staged once.  Ids out of range become page 0: every load then has a valid address
-    // (and every wavefront issues the same number of loads per tile); what such a page delivers is masked out.
-    for (int i = tid; i < pages_valid; i += 64 * NW) {
-        const int page = pt[i];
-        s_pt[i] = (unsigned)page < (unsigned)a.n_pages ? page : 0;
-    }
-    __syncthreads();
-
     const int st = lt * SPB + strip;               // this wave's 32-token strip inside the request
     const bool wave_active = st * 32 < n_r;
     const int local = st * 32 + col;
@@ -133,6 +126,17 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
 #pragma unroll
             for (int e = 0; e < 8; ++e) qf[kk][e] = (__bf16)0.f;
     }
+
+    // Page ids of the request, staged once.  Ids out of range become page 0: every load then has a valid address
+    // (and every wavefront issues the same number of loads per tile); what such a page delivers is masked out.
+    for (int i = tid; i < pages_valid; i += 64 * NW) {
+        const int page = pt[i];
+        s_pt[i] = (unsigned)page < (unsigned)a.n_pages ? page : 0;
+    }
+    // The query loads above are waited for here, once: inside the loop only the tile loads are then in flight,
+    // and the counted waits on them are the only vector-memory waits the loop needs.
+    wait_vmcnt_attn<0>();
+    __syncthreads();
 
     f32x16 o_acc[RT];
 #pragma unroll
@@ -160,106 +164,128 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
         }
     };
 
+    // The loop is software-pipelined over the key tiles.  Iteration t: (barrier: tile t has landed) -> issue the K
+    // operand reads of tile t -> softmax and PV of tile t - 1 (scores and V operands are in registers since the
+    // previous iteration) -> issue the V operand reads of tile t -> QK^T of tile t.  The LDS latency of the K reads
+    // passes under the softmax, that of the V reads under the QK^T chain, and a wavefront alternates between one
+    // block of 2 KK matrix instructions and one block of vector instructions, which the other wavefront of its
+    // SIMD (see the priority above) fills with the opposite block.
+    f32x16 s;
+    bf16x8 kf[KK];
+    u32x4 vf[2][RT];
+    // softmax of the scores in s (tile `tile`) and O^T += V^T P^T with the V operands in vf
+    auto softmax_pv = [&](int tile) {
+        const int key0 = tile * kAttnTile;
+        // Register 4b + j of s is row 8b + 4g + j: page b / 2, slot 8(b%2) + 4g + j, which holds token
+        // 8g + 4(b%2) + j.  So registers 8p .. 8p+7 are tokens 8g .. 8g+7 of page p, in order.
+        const bool need_mask = key0 + kAttnTile - 1 > wave_min_pos;
+        // The running maximum is kept in scaled units (score * log2(e) / sqrt(hd)); the scale is positive, so
+        // the maximum is taken over the raw scores and scaled once, and the scaling of every score is folded
+        // into the exponent's fused multiply-add.
+        float mraw = -INFINITY;
+        if (need_mask) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = key0 + 16 * (e >> 3) + 8 * g + (e & 7);
+                s[e] = key <= pos ? s[e] : -INFINITY;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mraw = fmaxf(mraw, s[e]);
+        float mx = fmaxf(m_run, mraw * a.scale_log2e);
+        mx = xor32_max(mx);
+        // a row may see no key at all in this split's range yet: keep the arithmetic finite
+        const float mref = mx == -INFINITY ? 0.f : mx;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - mref);
+        m_run = mx;
+        float rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], a.scale_log2e, -mref));
+            s[e] = p;
+            rs += p;
+        }
+        l_run = l_run * alpha + rs;
+        // After the first few tiles the maximum rarely moves and alpha is exactly 1 in every lane: the 16 RT
+        // multiplications of the rescale are then skipped (multiplying by 1.0 changes no bit).
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
+        }
+        // V slots at or past kmax may hold anything (even NaN): their probability is exactly 0, but 0 * NaN is
+        // not, so the last tile zeroes them.
+        if (key0 + kAttnTile > kmax) {  // uniform: the last tile of the block only
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg) {
+                const int left = kmax - (key0 + 16 * pg + 8 * g);  // tokens of this group that are valid
+#pragma unroll
+                for (int i = 0; i < RT; ++i)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e >= left) vf[pg][i][e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+            }
+        }
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+            bf16x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[8 * pg + e];
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+                o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf[pg][i], pf, o_acc[i], 0, 0, 0);
+        }
+    };
+
 #pragma unroll
     for (int i = 0; i < NST - 1; ++i)
         if (t_begin + i < t_end) issue(t_begin + i);
+    bool pending = false;  // s and vf hold a tile whose softmax and PV are still to come
     for (int tile = t_begin; tile < t_end; ++tile) {
         // loads issued after those of this tile and allowed to stay in flight: min(NST - 2, tiles left after it)
         const int later = t_end - 1 - tile;
         if (later >= NST - 2) wait_vmcnt_attn<(NST - 2) * LPW>();
         else if (later == 1) wait_vmcnt_attn<LPW>();
         else wait_vmcnt_attn<0>();
-        __builtin_amdgcn_s_barrier();  // everyone's part of this tile has landed; everyone is done with tile - 1
+        // Everyone's part of this tile has landed, and everyone has the operands of tile - 1 in registers (its K
+        // went through QK^T, the reads of its V were waited for below): the stage of tile - 1 may be refilled.
+        __builtin_amdgcn_s_barrier();
         if (tile + NST - 1 < t_end) issue(tile + NST - 1);
-        const int key0 = tile * kAttnTile;
         // rows of this wave see keys up to prefix + st*32 + 31; tiles entirely past that contribute nothing
-        if (wave_active && key0 <= wave_min_pos + 31) {
-            const char *sK = smem + (tile % NST) * STAGE;
-            const char *sV = sK + 2 * BLK;
-            f32x16 s;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[e] = 0.f;
+        const bool act = wave_active && tile * kAttnTile <= wave_min_pos + 31;
+        const char *sK = smem + (tile % NST) * STAGE;
+        if (act) {
             // operand A row (lane % 32): page row / 16, slot row % 16 (slots are rows as they stand); k-slot group g
             const char *kp = sK + (col >> 4) * BLK + (col & 15) * 16 + g * 256;
-            // All operand reads of the tile are issued up front, into registers of their own: the K fragments so that
-            // the QK^T chain waits for LDS once and not before every instruction, the V fragments so that their
-            // latency passes under the softmax.
-            bf16x8 kf[KK];
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) kf[kk] = *(const bf16x8 *)(kp + kk * 512);
+        }
+        if (pending) softmax_pv(tile - 1);
+        pending = act;
+        if (act) {
             // V block [2 token groups][hd][8]: lane (col, g) reads hd row 32 i + col of token group g
-            u32x4 vf[2][RT];
+            const char *sV = sK + 2 * BLK;
 #pragma unroll
             for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
                 for (int i = 0; i < RT; ++i) vf[pg][i] = *(const u32x4 *)(sV + pg * BLK + (g * HD + col) * 16 + i * 512);
 #pragma unroll
+            for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
             for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
-            // keep that order: the scheduler otherwise sinks each read next to its use and waits for it there
-            __builtin_amdgcn_sched_group_barrier(0x100, KK + 2 * RT, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, KK, 0);
-            // Register 4b + j is row 8b + 4g + j: page b / 2, slot 8(b%2) + 4g + j, which holds token
-            // 8g + 4(b%2) + j.  So registers 8p .. 8p+7 are tokens 8g .. 8g+7 of page p, in order.
-            const bool need_mask = key0 + kAttnTile - 1 > wave_min_pos;
-            // The running maximum is kept in scaled units (score * log2(e) / sqrt(hd)); the scale is positive, so
-            // the maximum is taken over the raw scores and scaled once, and the scaling of every score is folded
-            // into the exponent's fused multiply-add.
-            float mraw = -INFINITY;
-            if (need_mask) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = key0 + 16 * (e >> 3) + 8 * g + (e & 7);
-                    s[e] = key <= pos ? s[e] : -INFINITY;
-                }
-            }
-#pragma unroll
-            for (int e = 0; e < 16; ++e) mraw = fmaxf(mraw, s[e]);
-            float mx = fmaxf(m_run, mraw * a.scale_log2e);
-            mx = xor32_max(mx);
-            // a row may see no key at all in this split's range yet: keep the arithmetic finite
-            const float mref = mx == -INFINITY ? 0.f : mx;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - mref);
-            m_run = mx;
-            float rs = 0.f;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], a.scale_log2e, -mref));
-                s[e] = p;
-                rs += p;
-            }
-            l_run = l_run * alpha + rs;
-            // After the first few tiles the maximum rarely moves and alpha is exactly 1 in every lane: the 16 RT
-            // multiplications of the rescale are then skipped (multiplying by 1.0 changes no bit).
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-                for (int i = 0; i < RT; ++i)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
-            }
-            // V slots at or past kmax may hold anything (even NaN): their probability is exactly 0, but 0 * NaN is
-            // not, so the last tile zeroes them as it reads them.
-            if (key0 + kAttnTile > kmax) {  // uniform: the last tile of the block only
-#pragma unroll
-                for (int pg = 0; pg < 2; ++pg) {
-                    const int left = kmax - (key0 + 16 * pg + 8 * g);  // tokens of this group that are valid
-#pragma unroll
-                    for (int i = 0; i < RT; ++i)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (e >= left) vf[pg][i][e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                }
-            }
-#pragma unroll
-            for (int pg = 0; pg < 2; ++pg) {
-                bf16x8 pf;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[8 * pg + e];
-#pragma unroll
-                for (int i = 0; i < RT; ++i)
-                    o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf[pg][i], pf, o_acc[i], 0, 0, 0);
-            }
+            // The V reads go out right behind the first instruction of the chain: the wait the compiler puts in
+            // front of the chain (for the K operands, long landed) then does not cover them, and the rest of the
+            // chain covers their latency.
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * RT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, KK - 1, 0);
+            // the V operands must be in registers before the next barrier lets their stage be refilled
+            __builtin_amdgcn_sched_barrier(0);   // (after the chain, where the wait costs nothing)
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) alone
         }
     }
+    if (pending) softmax_pv(t_end - 1);
 
     if (!tok_ok) return;
     l_run += __shfl_xor(l_run, 32);  // both lanes of a column are valid together
