@@ -365,7 +365,7 @@ def test_runtime_repartitioning_keeps_results_and_decisions(nx, oracle):
 
 def test_cfg4_partition_controller_in_the_loop(nx):
     """The 48-layer stack with the controller of Alg. 1 choosing the split at run time (alpha = 1.3, beta = 1.1, KV
-    switch point at 70 % of the pool, buffer zone of 2 of 32 steps), against the fixed 160/96 split on the same
+    switch point at 70 % of the pool, the split moving in 8 steps of 32 CUs with a buffer zone of one), against the fixed 160/96 split on the same
     trace and pool.  The cost model is calibrated on 4 of the layers before the trace starts."""
     from paper_2507_06608_amd.serve import DecoupledRunner
     print("[case] cfg4 with the partition controller in the loop", flush=True)
