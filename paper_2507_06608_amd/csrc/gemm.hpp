@@ -334,8 +334,9 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
 }
 
 // ---- weight-streaming GEMM of a decode batch -------------------------------------------------------------------
-// With at most 64 tokens every weight byte is used once, so the GEMM is a sweep over the weights (Sec. 2.3: decode
-// is bound by memory traffic) and its speed on a share of the chip is set by the bytes each CU keeps in flight:
+// With at most 128 tokens every weight byte is used once (by up to four MFMAs), so the GEMM is a sweep over the
+// weights (Sec. 2.3: decode is bound by memory traffic) and its speed on a share of the chip is set by the bytes
+// each CU keeps in flight:
 // one CU draws at most about 50 GB/s from HBM and needs on the order of 100 KiB outstanding to get there.  An LDS
 // ring cannot hold that much beside its resident stages, and nothing here is shared between wavefronts anyway:
 // each wavefront owns FW feature strips and all tokens.  So the weights bypass LDS: the P32 tile order makes a

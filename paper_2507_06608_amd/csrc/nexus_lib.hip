@@ -124,9 +124,9 @@ static int dev_alloc(T **p, size_t elems, bool zero) {
 // ---------------------------------------------------------------------------------------------- GEMM planning
 // Tile shapes (features x tokens), wavefronts, k per stage, ring depth.  Measured on MI355X: 128x128 tiles with
 // several workgroups per CU beat 256x256 at the token counts of a prefill chunk (and quantise far better on a CU
-// share); a decode batch (<= 64 tokens) streams the weights once and wants many small workgroups whose rings
-// together keep about 100 KiB per CU in flight: one CU draws at most about 50 GB/s from HBM, so a decode share of
-// the chip is bound by per-CU bytes in flight, not by the HBM interface.
+// share); a batch of at most 128 tokens (a decode batch, a short chunk) streams the weights once and wants many
+// small workgroups whose rings together keep about 100 KiB per CU in flight: one CU draws at most about 50 GB/s
+// from HBM, so a decode share of the chip is bound by per-CU bytes in flight, not by the HBM interface.
 enum GemmVariant {
     GV_P128 = 0,  // gemm_dl_kernel, 128 x 128, 4 waves, 32-wide stages, 64 KiB ring: two workgroups per CU
     GV_P256,      // gemm_dl_kernel, 256 x 256, 8 waves, 128 KiB ring: half the LDS and L2 traffic per flop, for GEMMs
@@ -136,6 +136,9 @@ enum GemmVariant {
     GV_S64W,      // gemm_stream_kernel, 256 features x 64 tokens (two feature strips per wave): on a small CU share
                   //   every workgroup re-reads the activations through the same per-CU load path as the weights, and
                   //   twice the features per activation byte is worth more than twice the workgroups
+    GV_S128,      // gemm_stream_kernel, 128 features x 128 tokens, 4 waves: batches of 65..128 tokens (a full decode
+                  //   pool, a short prefill chunk), still closer to a sweep over the weights than to a tiled GEMM
+    GV_S128W,     // gemm_stream_kernel, 256 features x 128 tokens, 8 waves sharing the activation tiles
     GV_R64,       // gemm_dl_kernel with the extent of GV_S64 / GV_S32: k ranges shorter than the streaming
     GV_R32,       //   kernel's pipeline (hidden sizes below 128)
     GV_COUNT
@@ -158,12 +161,14 @@ static GemmPlan plan_gemm(int T, int n_ftiles, int Kp) {
         p.variant = GV_S32, p.FS = 4, p.TS = 1, min_ksteps = 8;
     } else if (T <= 64) {
         p.variant = GV_S64, p.FS = 4, p.TS = 2, min_ksteps = 8;
+    } else if (T <= 128) {
+        p.variant = GV_S128, p.FS = 4, p.TS = 4, min_ksteps = 8;
     } else {
         p.variant = GV_P128, p.FS = 4, p.TS = 4, min_ksteps = 16;
     }
     const int blocks = ((n_ftiles + p.FS - 1) / p.FS) * ((nt + p.TS - 1) / p.TS);
     int S = 1;
-    if (T <= 64) {
+    if (p.variant != GV_P128) {
         while (S < 8 && blocks * S < (3 * kChipCUs) / 4) S *= 2;
     } else if (blocks < (3 * kChipCUs) / 4) {
         S = std::min(4, (kChipCUs + blocks / 2) / blocks);
@@ -212,6 +217,8 @@ static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipSt
         case GV_S64: return launch_gemm_stream_t<1, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S32: return launch_gemm_stream_t<1, 1, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S64W: return launch_gemm_stream_t<2, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
+        case GV_S128: return launch_gemm_stream_t<1, 4, 4, 4, kStreamDepth, EPI>(a, grid, s);
+        case GV_S128W: return launch_gemm_stream_t<1, 4, 8, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_R64: return launch_gemm_t<4, 2, 2, 2, 4, 4, EPI, false>(a, grid, s);
         default: return launch_gemm_t<4, 1, 4, 1, 4, 4, EPI, false>(a, grid, s);
     }
@@ -293,8 +300,18 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
     // Measured on 64 of the 256 CUs (T = 64): gate/up 113 -> 98 us, down 55 -> 48, O 21.6 -> 18.9 with the wide
     // variant, QKV (too few workgroups left) 27 -> 30; on 96 CUs and more the narrow one wins or ties.
     if (variant == GV_S64 && r.cus <= 64 && (long)((n_ftiles + 7) / 8) * p.S >= 2L * r.cus - r.cus / 4) variant = GV_S64W, FS = 8;
+    // 65..128 tokens, measured on config 4's decode batch (128 tokens) on 256 / 96 CUs, 128-feature against 256-feature
+    // workgroups: QKV 23 / 44 us against 29 / 46, gate/up 62 / 132 against 80 / 137, O 24 / 37 against 21 / 32, down
+    // 45 / 73 against 36 / 61 (the 128 x 128-tile kernel this replaces: 26 / 48, 74 / 147, 23 / 32, 49 / 71).  The
+    // wide workgroup wins where the narrow grid would be far more workgroups than the chip has CUs (the deeply split
+    // O and down projections); the rule looks at the problem only.
+    if (variant == GV_S128 && (long)((n_ftiles + 3) / 4) * p.S > kChipCUs + kChipCUs / 8) variant = GV_S128W, FS = 8;
     const int last_ksteps = Kp / kGemmBK - (p.S - 1) * p.ksteps_per_split;  // the shortest k range of the grid
-    if (last_ksteps < kStreamDepth) variant = (variant == GV_S64 || variant == GV_S64W) ? (FS = 4, GV_R64) : variant == GV_S32 ? GV_R32 : variant;
+    if (last_ksteps < kStreamDepth)
+        variant = (variant == GV_S64 || variant == GV_S64W) ? (FS = 4, GV_R64)
+                  : variant == GV_S32                       ? GV_R32
+                  : (variant == GV_S128 || variant == GV_S128W) ? (FS = 4, GV_P128)
+                                                            : variant;
     a.n_tblk = (a.n_ttiles + TS - 1) / TS;
     a.n_xcd = r.n_xcd;
     // Tiles resident on one XCD at a time form a 4 x (residents / 4) rectangle instead of a row of token blocks:
