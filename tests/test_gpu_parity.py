@@ -113,6 +113,9 @@ RAGGED = [
     ("gqa8 hd128", "gqa8", [50], [70], [90, 300]),
     ("gqa5 hd128", "gqa5", [70], [3], [77, 129]),
     ("gqa2 hd64", "gqa2", [40, 40], [0, 8], [64, 10]),
+    # both phases in the 65..128-token range of the weight-streaming GEMM, with a ragged last 32-token tile
+    ("tiny 100-token chunk, 70 decodes", "tiny", [100], [28], [3 + 5 * i for i in range(70)]),
+    ("gqa4 128 decodes", "gqa4", [70, 58], [10, 0], [1 + 3 * i for i in range(128)]),
 ]
 EXTRA_SHAPES = {
     "gqa4": synth.ModelShape("gqa4", 512, 8, 2, 128, 1376, 500000.0),
