@@ -349,9 +349,16 @@ static int run_rmsnorm(const PhaseRun &r, const void *x, const bf16_t *g, f16_t 
     nexus_ctx *c = r.c;
     const int d = c->m.hidden;
     Tracer tr(c, r.phase, NEXUS_K_RMSNORM, r.s);
-    if (d <= 2048) hipLaunchKernelGGL((rmsnorm_kernel<1, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps, pp);
-    else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_kernel<2, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps, pp);
-    else hipLaunchKernelGGL((rmsnorm_kernel<4, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, p32_kp(d), c->m.rms_eps, pp);
+    const int Kp = p32_kp(d);
+    if (r.T >= 1024) {  // problem-only choice (the two kernels sum the squares in different orders)
+        const dim3 grid((r.T + kRmsWaves - 1) / kRmsWaves), block(64 * kRmsWaves);
+        if (d <= 1024) hipLaunchKernelGGL((rmsnorm_wave_kernel<2, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
+        else if (d <= 2048) hipLaunchKernelGGL((rmsnorm_wave_kernel<4, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
+        else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_wave_kernel<8, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
+        else hipLaunchKernelGGL((rmsnorm_wave_kernel<16, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
+    } else if (d <= 2048) hipLaunchKernelGGL((rmsnorm_kernel<1, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, Kp, c->m.rms_eps, pp);
+    else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_kernel<2, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, Kp, c->m.rms_eps, pp);
+    else hipLaunchKernelGGL((rmsnorm_kernel<4, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, Kp, c->m.rms_eps, pp);
     HIP_TRY(hipGetLastError());
     return NEXUS_OK;
 }
