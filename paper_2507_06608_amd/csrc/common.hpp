@@ -92,4 +92,37 @@ __device__ __forceinline__ int xcd_run_index(int b, int n) {
     return b;
 }
 
+// Sum of the S fp32 slices of a split-K GEMM at one 8-element (or 4-element) position, slices added in order.  The
+// loads of all slices are issued before the first addition (the loop is unrolled over the largest split count with
+// the absent slices predicated off): one memory latency for the sum, not one per slice.
+constexpr int kMaxSlices = 8;
+__device__ __forceinline__ void sum_slices8(const float *first, size_t slice_stride, int S, float (&o)[8]) {
+    float4 a[kMaxSlices][2];
+#pragma unroll
+    for (int s = 0; s < kMaxSlices; ++s)
+        if (s < S) {
+            const float4 *p = (const float4 *)(first + (size_t)s * slice_stride);
+            a[s][0] = p[0], a[s][1] = p[1];
+        }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMaxSlices; ++s)
+        if (s < S) {
+            o[0] += a[s][0].x, o[1] += a[s][0].y, o[2] += a[s][0].z, o[3] += a[s][0].w;
+            o[4] += a[s][1].x, o[5] += a[s][1].y, o[6] += a[s][1].z, o[7] += a[s][1].w;
+        }
+}
+__device__ __forceinline__ void sum_slices4(const float *first, size_t slice_stride, int S, float (&o)[4]) {
+    float4 a[kMaxSlices];
+#pragma unroll
+    for (int s = 0; s < kMaxSlices; ++s)
+        if (s < S) a[s] = *(const float4 *)(first + (size_t)s * slice_stride);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMaxSlices; ++s)
+        if (s < S) o[0] += a[s].x, o[1] += a[s].y, o[2] += a[s].z, o[3] += a[s].w;
+}
+
 }  // namespace nexus

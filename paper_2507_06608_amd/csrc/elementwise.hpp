@@ -35,14 +35,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x
                 v[c][0] = a0.x, v[c][1] = a0.y, v[c][2] = a0.z, v[c][3] = a0.w;
                 v[c][4] = a1.x, v[c][5] = a1.y, v[c][6] = a1.z, v[c][7] = a1.w;
             } else if (IN == RMS_IN_PARTIAL) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
-                for (int s = 0; s < pp.S; ++s) {
-                    const float4 *row = (const float4 *)(pp.partial + ((size_t)s * pp.T + t) * d);
-                    float4 a0 = row[2 * ci], a1 = row[2 * ci + 1];
-                    v[c][0] += a0.x, v[c][1] += a0.y, v[c][2] += a0.z, v[c][3] += a0.w;
-                    v[c][4] += a1.x, v[c][5] += a1.y, v[c][6] += a1.z, v[c][7] += a1.w;
-                }
+                sum_slices8(pp.partial + (size_t)t * d + 8 * ci, (size_t)pp.T * d, pp.S, v[c]);
                 uint4 u = ((const uint4 *)(pp.res + (size_t)t * d))[ci];
                 uint32_t wds[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
@@ -135,20 +128,11 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
         }
     } else {
 #pragma unroll
-        for (int c = 0; c < MAXC; ++c)
+        for (int c = 0; c < MAXC; ++c) {
+            const int ci = lane + c * 64;
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
-        for (int s = 0; s < pp.S; ++s) {
-            const float4 *row = (const float4 *)(pp.partial + ((size_t)s * pp.T + t) * d);
-#pragma unroll
-            for (int c = 0; c < MAXC; ++c) {
-                const int ci = lane + c * 64;
-                if (ci < nchunk) {
-                    const float4 a0 = row[2 * ci], a1 = row[2 * ci + 1];
-                    v[c][0] += a0.x, v[c][1] += a0.y, v[c][2] += a0.z, v[c][3] += a0.w;
-                    v[c][4] += a1.x, v[c][5] += a1.y, v[c][6] += a1.z, v[c][7] += a1.w;
-                }
-            }
+            if (ci < nchunk) sum_slices8(pp.partial + (size_t)t * d + 8 * ci, (size_t)pp.T * d, pp.S, v[c]);
         }
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
@@ -259,14 +243,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
     const int width = qd + 2 * kvd;
     auto load8 = [&](int col, float (&o)[8]) {
         if (a.partial) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = 0.f;
-            for (int s = 0; s < a.S; ++s) {
-                const float4 *p = (const float4 *)(a.partial + ((size_t)s * a.T + t) * width + col);
-                const float4 a0 = p[0], a1 = p[1];
-                o[0] += a0.x, o[1] += a0.y, o[2] += a0.z, o[3] += a0.w;
-                o[4] += a1.x, o[5] += a1.y, o[6] += a1.z, o[7] += a1.w;
-            }
+            sum_slices8(a.partial + (size_t)t * width + col, (size_t)a.T * width, a.S, o);
             if (a.bias) {
                 const uint4 b = *(const uint4 *)(a.bias + col);
                 const uint32_t bw[4] = {b.x, b.y, b.z, b.w};

@@ -510,23 +510,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ReduceArgs a) {
         // packed rows: strip s holds gate features [16s, 16s+16) in rows 0..15, the matching up features in 16..31
         const int strip = n >> 5;
         if (n & 16) return;
-        float gsum[4] = {0, 0, 0, 0}, usum[4] = {0, 0, 0, 0};
-        for (int s = 0; s < a.S; ++s) {
-            const float *p = a.partial + ((size_t)s * a.T + t) * a.N + n;
-            float4 gv = *(const float4 *)p, uv = *(const float4 *)(p + 16);
-            gsum[0] += gv.x, gsum[1] += gv.y, gsum[2] += gv.z, gsum[3] += gv.w;
-            usum[0] += uv.x, usum[1] += uv.y, usum[2] += uv.z, usum[3] += uv.w;
-        }
+        float gsum[4], usum[4];
+        sum_slices4(a.partial + (size_t)t * a.N + n, (size_t)a.T * a.N, a.S, gsum);
+        sum_slices4(a.partial + (size_t)t * a.N + n + 16, (size_t)a.T * a.N, a.S, usum);
         const int f = strip * 16 + (n & 15);
         uint2 o = {packh2(silu_f(gsum[0]) * usum[0], silu_f(gsum[1]) * usum[1]),
                    packh2(silu_f(gsum[2]) * usum[2], silu_f(gsum[3]) * usum[3])};
         *(uint2 *)(a.out_p32 + p32_offset(t, f, a.out_Kp)) = o;
     } else {
-        float v[4] = {0, 0, 0, 0};
-        for (int s = 0; s < a.S; ++s) {
-            float4 pv = *(const float4 *)(a.partial + ((size_t)s * a.T + t) * a.N + n);
-            v[0] += pv.x, v[1] += pv.y, v[2] += pv.z, v[3] += pv.w;
-        }
+        float v[4];
+        sum_slices4(a.partial + (size_t)t * a.N + n, (size_t)a.T * a.N, a.S, v);
         if constexpr (EPI == EPI_ROWMAJOR) {
             if (a.bias) {
                 uint2 bb = *(const uint2 *)(a.bias + n);

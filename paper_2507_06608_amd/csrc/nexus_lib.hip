@@ -321,6 +321,7 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
     a.group_f = 4;
     const int n_fblk = (n_ftiles + FS - 1) / FS;
     dim3 grid(a.n_tblk * n_fblk, 1, p.S);
+    if (p.S > kMaxSlices) return fail(NEXUS_ESTATE, "internal: %d split-K slices, the reductions unroll over %d", p.S, kMaxSlices);
     if (p.S > 1 && (size_t)p.S * r.T * N_packed > ws.partial_elems)
         return fail(NEXUS_ESTATE, "split-K workspace too small (%d x %d x %d)", p.S, r.T, N_packed);
     {
