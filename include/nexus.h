@@ -60,8 +60,9 @@ typedef struct {
  * the operands of the four projection GEMMs (normalised activations, attention output, SwiGLU activation and
  * the packed weights) are IEEE half, which the matrix unit runs at the bf16 rate with 8x smaller operand
  * rounding (half holds every bf16 weight of magnitude >= 2^-14 exactly); accumulators, softmax and norm
- * statistics and the residual stream between attention and feed-forward are fp32.  Activations feeding a GEMM
- * must stay inside half's range (|v| < 65504).
+ * statistics and the residual stream between attention and feed-forward are fp32 (where the keys of a request are
+ * split over several workgroups, each part's output is normalised by its own softmax sum and held in half until the
+ * parts are merged in fp32).  Activations feeding a GEMM must stay inside half's range (|v| < 65504).
  */
 
 /* Upper bounds that size the context's workspace; step calls beyond them fail with NEXUS_ESHAPE. */
