@@ -463,6 +463,16 @@ int nexus_debug_fetch(nexus_ctx *ctx, int phase, int which, int32_t n_tokens, vo
  */
 int nexus_debug_cu_probe(nexus_ctx *ctx, int phase, int n_blocks, int32_t *out_counts);
 
+/*
+ * The order in which the token-per-workgroup kernels (RMSNorm, rotary + append) visit the n tokens of a batch:
+ * workgroup b handles token nexus_debug_token_order(b, n) (the long-batch RMSNorm, four tokens per workgroup, applies
+ * it to its groups of four).  Workgroups are dealt to the 8 XCDs round-robin and
+ * neighbouring tokens share cache lines in what those kernels write, so inside every aligned group of 256 (64)
+ * workgroups the workgroups of one XCD take 32 (8) consecutive tokens; a tail that fills no whole group keeps its
+ * order.  A permutation of [0, n) for every n.  Host only; returns a negative status for b outside [0, n).
+ */
+int nexus_debug_token_order(int b, int n);
+
 #ifdef __cplusplus
 }
 #endif

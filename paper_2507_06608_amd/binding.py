@@ -31,7 +31,7 @@ EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "n
            "nexus_kv_import", "nexus_kv_export", "nexus_set_cu_split",
            "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_profile_split",
            "nexus_choose_split", "nexus_trace_begin", "nexus_trace_read", "nexus_debug_fetch",
-           "nexus_debug_cu_probe", "nexus_cost_latency", "nexus_adjust_partition", "nexus_partition_controller",
+           "nexus_debug_cu_probe", "nexus_debug_token_order", "nexus_cost_latency", "nexus_adjust_partition", "nexus_partition_controller",
            "nexus_cost_fit", "nexus_cost_describe",
            "nexus_sched_create", "nexus_sched_destroy", "nexus_sched_submit", "nexus_sched_next", "nexus_sched_commit",
            "nexus_sched_request", "nexus_sched_summarize", "nexus_sched_samples", "nexus_sched_next_phase",

@@ -86,7 +86,7 @@ __device__ __forceinline__ float xor32_max(float x) {
 // from partial writes out of 8 different L2s.  This permutation of [0, n) gives each XCD runs of 32 (or, for short
 // grids, 8) consecutive items instead: inside every aligned group of 256 (64) blocks, the blocks of one XCD take
 // consecutive items.  The tail that fills no whole group keeps its order.
-__device__ __forceinline__ int xcd_run_index(int b, int n) {
+__host__ __device__ __forceinline__ int xcd_run_index(int b, int n) {
     if ((b | 255) < n) return (b & ~255) | ((b & 7) << 5) | ((b >> 3) & 31);
     if ((b | 63) < n) return (b & ~63) | ((b & 7) << 3) | ((b >> 3) & 7);
     return b;

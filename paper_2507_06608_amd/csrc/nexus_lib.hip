@@ -629,6 +629,11 @@ extern "C" {
 
 const char *nexus_last_error(void) { return g_err; }
 
+int nexus_debug_token_order(int b, int n) {
+    if (n <= 0 || b < 0 || b >= n) return fail(NEXUS_EINVAL, "token order: index %d outside [0, %d)", b, n);
+    return xcd_run_index(b, n);
+}
+
 int nexus_cu_count(nexus_ctx *c) { return c ? c->n_cus : fail(NEXUS_EINVAL, "null context"); }
 
 void nexus_destroy(nexus_ctx *c) {

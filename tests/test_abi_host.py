@@ -86,3 +86,24 @@ def test_monotone_curves_pick_the_papers_operating_points(binding):
     assert binding.choose_split(t_p, t_d, t_s, 1.0, 1.0, 0, 1.3, 1.1) == 3      # 4/8: largest share with t_d <= 1.1
     assert binding.choose_split(t_p, t_d, t_s, 1.0, 1.0, 1, 1.3, 1.1) == 6      # only 7/8 keeps t_p <= 1.3
     assert binding.choose_split(t_p, t_d, t_s, 1.0, 1.0, 2, 1.3, 1.1) == int(np.argmin(t_s))
+
+
+def test_token_order_of_the_per_token_kernels_is_a_permutation_in_xcd_runs(binding):
+    """Workgroup b -> token: a permutation of [0, n) for every n (a token skipped or visited twice would go unnoticed
+    by nothing but parity), and in whole groups the 8 XCDs (workgroup index modulo 8) get runs of consecutive tokens."""
+    lib = binding.lib()
+    order = lambda n: [lib.nexus_debug_token_order(b, n) for b in range(n)]
+    for n in list(range(1, 140)) + [255, 256, 257, 320, 511, 512, 513, 1000, 8192]:
+        o = order(n)
+        assert sorted(o) == list(range(n)), n
+        full256, full64 = n // 256 * 256, n // 64 * 64
+        assert o[full64:] == list(range(full64, n))                     # the tail keeps its order
+        for g0 in range(0, full256, 256):                                # 32 consecutive tokens per XCD
+            for x in range(8):
+                toks = sorted(o[b] for b in range(g0, g0 + 256) if b % 8 == x)
+                assert toks == list(range(g0 + 32 * x, g0 + 32 * x + 32))
+        for g0 in range(full256, full64, 64):                            # 8 consecutive tokens per XCD
+            for x in range(8):
+                toks = sorted(o[b] for b in range(g0, g0 + 64) if b % 8 == x)
+                assert toks == list(range(g0 + 8 * x, g0 + 8 * x + 8))
+    assert lib.nexus_debug_token_order(5, 5) < 0 and lib.nexus_debug_token_order(-1, 5) < 0
