@@ -199,6 +199,26 @@ def layer_prefill(m: Model, w: dict, x, cu_chunk, prefix_len, page_table, k_pool
     return (y, dbg) if debug else y
 
 
+def layer_prefill_rows(m: Model, w: dict, x, cu_chunk, prefix_len, page_table, k_pool, v_pool, rows):
+    """The chunked-prefill phase for the listed batch rows only: every token's K/V is appended (pools updated in
+    place), then the query projection, the attention and the rest of the layer run for `rows`.  Returns
+    [len(rows), hidden], row i being row rows[i] of layer_prefill's result."""
+    assert k_pool.dtype == np.float32 and k_pool.flags.c_contiguous
+    assert v_pool.dtype == np.float32 and v_pool.flags.c_contiguous
+    x, cu, pl, pt, rows = _f32(x), _i32(cu_chunk), _i32(prefix_len), _i32(page_table), _i32(rows)
+    n_reqs = len(pl)
+    T = int(cu[n_reqs])
+    assert x.shape == (T, m.hidden)
+    assert rows.ndim == 1 and (rows >= 0).all() and (rows < T).all()
+    y = np.empty((len(rows), m.hidden), np.float32)
+    cw, keep = _weights(w)
+    cm = m.c()
+    lib().oracle_layer_prefill_rows(C.byref(cm), C.byref(cw), _p(x), C.c_int(n_reqs), _p(cu), _p(pl), _p(pt),
+                                    C.c_int(pt.shape[1]), _p(k_pool), _p(v_pool), C.c_int(len(rows)), _p(rows), _p(y))
+    del keep
+    return y
+
+
 def layer_decode(m: Model, w: dict, x, ctx_len, page_table, k_pool, v_pool, debug: bool = False):
     """One layer over a decode sub-batch: request j's new token sits at position ctx_len[j]."""
     assert k_pool.dtype == np.float32 and k_pool.flags.c_contiguous

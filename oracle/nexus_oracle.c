@@ -352,6 +352,70 @@ ORACLE_API void oracle_layer_prefill(const oracle_model *m, const oracle_weights
     free(pos);
 }
 
+/*
+ * The chunked-prefill phase of one layer evaluated for a listed subset of the
+ * batch's rows only (Eq. 1-4, same steps as oracle_layer_prefill): the keys
+ * and values of EVERY token of the batch are projected, rotated and appended
+ * first (a listed row attends to all earlier rows of its chunk), then the
+ * query projection, the attention and everything after it run for the rows
+ * in rows[0..n_rows) alone.  y receives [n_rows][hidden] in the order of
+ * rows[].  Row t of the result equals row rows[t] of oracle_layer_prefill:
+ * every output row of the layer depends on the other rows only through the
+ * cache.  This is what lets a test afford the last rows of a long chunk.
+ */
+ORACLE_API void oracle_layer_prefill_rows(const oracle_model *m, const oracle_weights *w, const float *x, int n_reqs,
+                                          const int32_t *cu_chunk, const int32_t *prefix_len,
+                                          const int32_t *page_table, int max_pages, float *k_pool, float *v_pool,
+                                          int n_rows, const int32_t *rows, float *y)
+{
+    int d = m->hidden, hd = m->head_dim, Hq = m->n_q_heads, Hkv = m->n_kv_heads;
+    int qd = Hq * hd, kvd = Hkv * hd;
+    int T = cu_chunk[n_reqs];
+    int32_t *req = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    for (int r = 0; r < n_reqs; ++r)
+        for (int t = cu_chunk[r]; t < cu_chunk[r + 1]; ++t) {
+            req[t] = r;
+            pos[t] = prefix_len[r] + (t - cu_chunk[r]);
+        }
+    /* keys and values of all tokens: the k and v rows of W_qkv follow its Hq * hd query rows */
+    float *h = (float *)malloc(sizeof(float) * (size_t)T * d);
+    float *kv = (float *)malloc(sizeof(float) * (size_t)T * 2 * kvd);
+    oracle_rmsnorm(x, w->attn_norm_g, T, d, m->rms_eps, h);
+    oracle_linear(h, w->w_qkv + (size_t)qd * d, w->b_qkv ? w->b_qkv + qd : NULL, T, d, 2 * kvd, kv);
+    for (int t = 0; t < T; ++t) {
+        float *row = kv + (size_t)t * 2 * kvd;
+        oracle_rope(row, Hkv, hd, pos[t], m->rope_theta);
+        oracle_kv_append(m, k_pool, v_pool, page_table + (size_t)req[t] * max_pages, pos[t], row, row + kvd);
+    }
+    /* the listed rows: query, attention over the cache, rest of the layer */
+    float *xs = (float *)malloc(sizeof(float) * (size_t)n_rows * d);
+    float *hs = (float *)malloc(sizeof(float) * (size_t)n_rows * d);
+    float *q = (float *)malloc(sizeof(float) * (size_t)n_rows * qd);
+    float *a = (float *)malloc(sizeof(float) * (size_t)n_rows * qd);
+    for (int i = 0; i < n_rows; ++i) {
+        memcpy(xs + (size_t)i * d, x + (size_t)rows[i] * d, sizeof(float) * d);
+        memcpy(hs + (size_t)i * d, h + (size_t)rows[i] * d, sizeof(float) * d);
+    }
+    oracle_linear(hs, w->w_qkv, w->b_qkv, n_rows, d, qd, q);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < n_rows; ++i) {
+        int t = rows[i];
+        oracle_rope(q + (size_t)i * qd, Hq, hd, pos[t], m->rope_theta);
+        oracle_attention_paged(m, q + (size_t)i * qd, pos[t], k_pool, v_pool,
+                               page_table + (size_t)req[t] * max_pages, a + (size_t)i * qd, NULL);
+    }
+    post_attention(m, w, xs, a, n_rows, y, NULL);
+    free(req);
+    free(pos);
+    free(h);
+    free(kv);
+    free(xs);
+    free(hs);
+    free(q);
+    free(a);
+}
+
 /* Decode phase of one layer: request j contributes one token at position ctx_len[j]. */
 ORACLE_API void oracle_layer_decode(const oracle_model *m, const oracle_weights *w, const float *x, int n_reqs,
                                     const int32_t *ctx_len, const int32_t *page_table, int max_pages, float *k_pool,

@@ -30,6 +30,11 @@ MUTATIONS = [
     ("ffn norm uses the attention gain", "oracle_rmsnorm(x1, w->ffn_norm_g", "oracle_rmsnorm(x1, w->attn_norm_g"),
     ("keys cached before rotation", "oracle_rope(row + qd, Hkv, hd, tok_pos[t], m->rope_theta);", ""),
     ("bias dropped", "if (b) acc += (double)b[o];", ""),
+    ("row subset: keys projected with the query rows", "w->w_qkv + (size_t)qd * d, w->b_qkv ? w->b_qkv + qd : NULL", "w->w_qkv, w->b_qkv ? w->b_qkv + qd : NULL"),
+    ("row subset: bias of the keys taken from the queries", "w->b_qkv ? w->b_qkv + qd : NULL", "w->b_qkv"),
+    ("row subset: position of the i-th batch row instead of the listed row", "int t = rows[i];", "int t = i;"),
+    ("row subset: queries not rotated", "oracle_rope(q + (size_t)i * qd, Hq, hd, pos[t], m->rope_theta);", ""),
+    ("row subset: residual taken from the first rows", "memcpy(xs + (size_t)i * d, x + (size_t)rows[i] * d", "memcpy(xs + (size_t)i * d, x + (size_t)i * d"),
     ("prefill-prioritised constraint uses alpha", "(double)beta * t_d_min", "(double)alpha * t_d_min"),
 ]
 
