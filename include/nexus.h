@@ -21,7 +21,8 @@
  *     call that fails launches nothing.  The contents of device-side integer
  *     arrays (lengths, page ids) cannot be checked without a device-to-host
  *     copy; kernels skip page ids outside [0, n_pages) instead of
- *     dereferencing them.
+ *     dereferencing them.  nexus_set_debug_checks() turns on a mode that
+ *     makes that copy and validates the arrays before every step.
  *   - Step calls enqueue work and return; nexus_sync() (or a timing request)
  *     waits.  Calls on one context must not overlap from several threads.
  */
@@ -188,16 +189,29 @@ int nexus_kv_export(nexus_ctx *ctx, const nexus_kv_cache *kv, int layer, void *k
  * its CUs (a queue's CU mask must keep at least one CU in every XCD, and workgroups are dealt to XCDs
  * round-robin whatever the mask).  Inside an XCD the workgroups are likewise dealt evenly to its 4 shader engines,
  * so a share runs at full speed only when it is a multiple of 32 (4 per XCD); other multiples of 8 are accepted and
- * run at the speed of the next lower multiple of 32.  The two phases then run on two streams whose CU masks are disjoint.  Only
- * one partitioned stream pair exists at a time: selecting a different split synchronises and destroys the
- * current pair and creates the new one (about 12 ms; more than one pair alive made some pairs dispatch the
- * decode kernels late on MI355X).  (NEXUS_CUS_ALL, NEXUS_CUS_ALL) selects the unpartitioned layout: one unmasked
- * stream, the mixed step runs prefill then decode back to back (the serialized baseline of Sec. 3.1).
+ * run at the speed of the next lower multiple of 32.  The two phases then run on two streams whose CU masks are
+ * disjoint.  (NEXUS_CUS_ALL, NEXUS_CUS_ALL) selects the unpartitioned layout: one unmasked stream, the mixed step
+ * runs prefill then decode back to back (the serialized baseline of Sec. 3.1).
+ *
+ * A layout (its pair of CU-masked streams) is created the first time its split is selected or prepared (about
+ * 10 ms) and kept: selecting it again is a pointer switch on the host (microseconds), waits for nothing and
+ * launches nothing (Sec. 4.2: switching must not block the streams).  Work already enqueued on the previous layout
+ * keeps running there on its old CU share; each phase's next launch goes to the new layout and is ordered, by
+ * events, after the previous launch of the same phase (nexus_mixed_step: of both phases), so for the remainder of
+ * a step in flight the old and the new shares may overlap on some CUs.  Up to 8 partitioned layouts stay alive
+ * (every split in steps of 32 CUs is 7); selecting a ninth retires the least recently used one, which waits for
+ * that layout's work.
  * CU-masked streams are blocking streams in HIP's sense (the call that creates them takes no flags): work issued
  * on the NULL stream waits for them and holds them back.  A caller that overlaps its own copies or kernels with a
  * running phase must issue them on a non-blocking stream.
  */
 int nexus_set_cu_split(nexus_ctx *ctx, int prefill_cus, int decode_cus);
+/*
+ * Creates the layouts of n splits ahead of use (Sec. 5 creates every layout at initialisation) without selecting
+ * any: host arrays prefill_cus[n], decode_cus[n], each pair as for nexus_set_cu_split.  Fails with NEXUS_ESHAPE
+ * when more partitioned layouts are asked for than are kept alive.
+ */
+int nexus_prepare_cu_splits(nexus_ctx *ctx, int n, const int32_t *prefill_cus, const int32_t *decode_cus);
 
 /* ---- the step (layers [layer_begin, layer_end); output of layer l feeds layer l + 1) ----------------------- */
 
@@ -228,7 +242,10 @@ int nexus_fused_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus
  * may keep one loop per phase (Sec. 5) -- launch a phase, poll it, launch its next step -- as long as the two
  * phases touch different requests' pages.  nexus_phase_query returns 1 when that call's work has completed (or
  * none was made), 0 while it is running.  nexus_phase_wait blocks until it has and, if elapsed_ms is not NULL,
- * stores the time between the call's first and last kernel on the GPU's clock.
+ * stores the time between the call's first and last kernel on the GPU's clock.  Both also see a phase launched by
+ * nexus_mixed_step or nexus_fused_step (the elapsed time is then reported as -1: those calls bracket the step, not
+ * the phase).  A single-phase call is ordered after the previous launch of the same phase on whatever layout that
+ * ran, never after the other phase.
  */
 int nexus_phase_query(nexus_ctx *ctx, int phase);
 int nexus_phase_wait(nexus_ctx *ctx, int phase, float *elapsed_ms);
@@ -236,7 +253,8 @@ int nexus_phase_wait(nexus_ctx *ctx, int phase, float *elapsed_ms);
  * Both phases of one step.  With a partitioned layout they are enqueued on the two CU-masked streams after a
  * common fork event and run concurrently; with the unpartitioned layout they run back to back.  The two
  * sub-batches must touch disjoint requests and pages.  Steps of one context never overlap: each phase starts
- * after both phases of the previous nexus_mixed_step.  caller_stream (a hipStream_t) is made to precede the fork
+ * after the previous launch of BOTH phases of the context (mixed, single-phase or fused), whatever layout that
+ * ran on, so the split may be changed between two steps without synchronising.  caller_stream (a hipStream_t) is made to precede the fork
  * and to wait for both phases; with NULL the step is ordered after the context's previous work only, and the
  * caller synchronises with nexus_sync (inputs must be complete when the call is made).  timing may be NULL; when
  * given the call blocks until done.
@@ -427,6 +445,29 @@ int nexus_sched_summarize(const nexus_sched *s, nexus_sched_summary *out);
 /* Raw samples: kind 0 = TTFT (by request id), 1 = TBT (in commit order), 2 = normalised latency (by request id).
  * Writes up to cap doubles to host `out` (may be NULL with cap 0) and the total number available to *n. */
 int nexus_sched_samples(const nexus_sched *s, int kind, double *out, int32_t cap, int32_t *n);
+
+/* ---- validation of device-side integer inputs (debug mode) ------------------------------------------------ */
+
+/*
+ * on != 0: every step call (prefill chunk, decode step, mixed step, fused step) first copies its chunk offsets,
+ * prefix / context lengths and page tables to the host, waits for the copy, and checks them with
+ * nexus_validate_batches against the KV cache it was given; a violation fails the call with NEXUS_EINVAL before
+ * anything is launched.  The arrays must be complete when the call is made.  Costs a device-to-host round trip
+ * per step: a debugging aid, off by default (or NEXUS_DEBUG_CHECKS=1 in the environment at nexus_create).
+ */
+int nexus_set_debug_checks(nexus_ctx *ctx, int on);
+/*
+ * The check itself, host only (every pointer is HOST memory; a batch with zero requests is absent and its pointers
+ * may be NULL): chunk offsets are an exclusive prefix sum ending at n_prefill_tokens; lengths are non-negative and
+ * within max_chunk / max_total_len / max_ctx; every page a request touches (positions [0, prefix + chunk) or
+ * [0, ctx + 1)) lies in [0, n_pages) and inside its table row; a page that one request writes (the pages of the
+ * positions it appends) is touched by no other request of the step.  Returns NEXUS_OK or NEXUS_EINVAL with the
+ * offending request and entry in nexus_last_error().
+ */
+int nexus_validate_batches(int32_t n_pages, int32_t page_size, int32_t n_prefill_reqs, int32_t n_prefill_tokens,
+                           const int32_t *cu_chunk, const int32_t *prefix_len, const int32_t *prefill_page_table,
+                           int32_t prefill_max_pages, int32_t max_chunk, int32_t max_total_len, int32_t n_decode_reqs,
+                           const int32_t *ctx_len, const int32_t *decode_page_table, int32_t decode_max_pages, int32_t max_ctx);
 
 /* ---- measurement and test hooks ----------------------------------------------------------------------------- */
 

@@ -199,10 +199,12 @@ def layer_prefill(m: Model, w: dict, x, cu_chunk, prefix_len, page_table, k_pool
     return (y, dbg) if debug else y
 
 
-def layer_prefill_rows(m: Model, w: dict, x, cu_chunk, prefix_len, page_table, k_pool, v_pool, rows):
+def layer_prefill_rows(m: Model, w: dict, x, cu_chunk, prefix_len, page_table, k_pool, v_pool, rows,
+                       kv_store_bf16: bool = False):
     """The chunked-prefill phase for the listed batch rows only: every token's K/V is appended (pools updated in
     place), then the query projection, the attention and the rest of the layer run for `rows`.  Returns
-    [len(rows), hidden], row i being row rows[i] of layer_prefill's result."""
+    [len(rows), hidden], row i being row rows[i] of layer_prefill's result.  kv_store_bf16 rounds the appended K/V
+    to bf16 as a bf16 cache would (a measurement of that format's cost; parity gates use the exact default)."""
     assert k_pool.dtype == np.float32 and k_pool.flags.c_contiguous
     assert v_pool.dtype == np.float32 and v_pool.flags.c_contiguous
     x, cu, pl, pt, rows = _f32(x), _i32(cu_chunk), _i32(prefix_len), _i32(page_table), _i32(rows)
@@ -214,7 +216,8 @@ def layer_prefill_rows(m: Model, w: dict, x, cu_chunk, prefix_len, page_table, k
     cw, keep = _weights(w)
     cm = m.c()
     lib().oracle_layer_prefill_rows(C.byref(cm), C.byref(cw), _p(x), C.c_int(n_reqs), _p(cu), _p(pl), _p(pt),
-                                    C.c_int(pt.shape[1]), _p(k_pool), _p(v_pool), C.c_int(len(rows)), _p(rows), _p(y))
+                                    C.c_int(pt.shape[1]), _p(k_pool), _p(v_pool), C.c_int(len(rows)), _p(rows),
+                                    C.c_int(int(kv_store_bf16)), _p(y))
     del keep
     return y
 

@@ -363,10 +363,27 @@ ORACLE_API void oracle_layer_prefill(const oracle_model *m, const oracle_weights
  * every output row of the layer depends on the other rows only through the
  * cache.  This is what lets a test afford the last rows of a long chunk.
  */
+/* fp32 -> nearest bfloat16 (ties to even) -> fp32: what a cache that stores bf16 keeps of a value. */
+static float bf16_round(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return f; /* NaN */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/*
+ * kv_store_bf16 != 0 applies the storage format of a bf16 KV cache and nothing else: the rotated keys and the values
+ * are rounded to bf16 as they are stored.  It exists to MEASURE what that format alone costs against the exact
+ * layer (kv_store_bf16 == 0, which is what every parity gate compares with); no gate uses the rounded variant.
+ */
 ORACLE_API void oracle_layer_prefill_rows(const oracle_model *m, const oracle_weights *w, const float *x, int n_reqs,
                                           const int32_t *cu_chunk, const int32_t *prefix_len,
                                           const int32_t *page_table, int max_pages, float *k_pool, float *v_pool,
-                                          int n_rows, const int32_t *rows, float *y)
+                                          int n_rows, const int32_t *rows, int kv_store_bf16, float *y)
 {
     int d = m->hidden, hd = m->head_dim, Hq = m->n_q_heads, Hkv = m->n_kv_heads;
     int qd = Hq * hd, kvd = Hkv * hd;
@@ -386,6 +403,8 @@ ORACLE_API void oracle_layer_prefill_rows(const oracle_model *m, const oracle_we
     for (int t = 0; t < T; ++t) {
         float *row = kv + (size_t)t * 2 * kvd;
         oracle_rope(row, Hkv, hd, pos[t], m->rope_theta);
+        if (kv_store_bf16)
+            for (int i = 0; i < 2 * kvd; ++i) row[i] = bf16_round(row[i]);
         oracle_kv_append(m, k_pool, v_pool, page_table + (size_t)req[t] * max_pages, pos[t], row, row + kvd);
     }
     /* the listed rows: query, attention over the cache, rest of the layer */

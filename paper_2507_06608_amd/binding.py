@@ -35,7 +35,8 @@ EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "n
            "nexus_cost_fit", "nexus_cost_describe",
            "nexus_sched_create", "nexus_sched_destroy", "nexus_sched_submit", "nexus_sched_next", "nexus_sched_commit",
            "nexus_sched_request", "nexus_sched_summarize", "nexus_sched_samples", "nexus_sched_next_phase",
-           "nexus_sched_commit_phase", "nexus_phase_query", "nexus_phase_wait", "nexus_fused_step")
+           "nexus_sched_commit_phase", "nexus_phase_query", "nexus_phase_wait", "nexus_fused_step",
+           "nexus_prepare_cu_splits", "nexus_set_debug_checks", "nexus_validate_batches")
 
 
 class NexusError(RuntimeError):
@@ -122,6 +123,33 @@ def choose_split(t_p, t_d, t_step, t_p_all: float, t_d_all: float, policy: int, 
                                            policy, alpha, beta))
 
 
+def validate_batches(n_pages: int, page_size: int, prefill: Optional[PrefillBatch] = None, decode: Optional[DecodeBatch] = None,
+                     hints: Optional[dict] = None) -> None:
+    """Host-only validation of a step's integer inputs (numpy arrays); raises NexusError on the first violation.
+    hints may override max_chunk / max_total_len / max_ctx (default: the tightest values)."""
+    hints = hints or {}
+    i32 = lambda a: np.ascontiguousarray(a, np.int32)
+    args = [n_pages, page_size]
+    keep = []
+    if prefill is not None and prefill.n_reqs:
+        cu, pre, pt = i32(prefill.cu_chunk), i32(prefill.prefix_len), i32(prefill.page_table)
+        keep += [cu, pre, pt]
+        chunk = np.diff(cu)
+        args += [len(pre), hints.get("n_tokens", int(cu[-1])), cu.ctypes.data_as(C.c_void_p), pre.ctypes.data_as(C.c_void_p),
+                 pt.ctypes.data_as(C.c_void_p), pt.shape[1], hints.get("max_chunk", int(chunk.max())),
+                 hints.get("max_total_len", int((pre + chunk).max()))]
+    else:
+        args += [0, 0, None, None, None, 0, 0, 0]
+    if decode is not None and decode.n_reqs:
+        ctx, pt = i32(decode.ctx_len), i32(decode.page_table)
+        keep += [ctx, pt]
+        args += [len(ctx), ctx.ctypes.data_as(C.c_void_p), pt.ctypes.data_as(C.c_void_p), pt.shape[1],
+                 hints.get("max_ctx", int(ctx.max()) + 1)]
+    else:
+        args += [0, None, None, 0, 0]
+    _check(lib().nexus_validate_batches(*args))
+
+
 def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
 
@@ -167,7 +195,6 @@ class Nexus:
         self._ctx = C.c_void_p()
         torch.cuda.init()
         _check(lib().nexus_create(C.byref(desc), C.byref(lim), device, C.byref(self._ctx)))
-        self._kv_keep = None
 
     # -- lifetime
     def close(self):
@@ -212,7 +239,7 @@ class Nexus:
         torch.cuda.synchronize(self.device)
         for l in range(layers):
             _check(lib().nexus_kv_import(self._ctx, C.byref(kv), l, _ptr(kc), _ptr(vc), 0, n_pages))
-        self._kv_keep = (kp, vp)
+        kv.pools = (kp, vp)      # the descriptor owns its tensors: it stays valid as long as the caller holds it
         return kv
 
     def alloc_kv(self, n_pages: int, layers: int):
@@ -222,8 +249,9 @@ class Nexus:
         kp = torch.zeros(layers * per_layer, dtype=torch.bfloat16, device=self.device)
         vp = torch.zeros(layers * per_layer, dtype=torch.bfloat16, device=self.device)
         torch.cuda.synchronize(self.device)
-        self._kv_keep = (kp, vp)
-        return KVCache(kp.data_ptr(), vp.data_ptr(), per_layer * 2, n_pages)
+        kv = KVCache(kp.data_ptr(), vp.data_ptr(), per_layer * 2, n_pages)
+        kv.pools = (kp, vp)
+        return kv
 
     def kv_export(self, kv: KVCache, layer: int = 0):
         s = self.shape
@@ -236,6 +264,15 @@ class Nexus:
     # -- partitioning
     def set_cu_split(self, prefill_cus: int, decode_cus: int):
         _check(lib().nexus_set_cu_split(self._ctx, prefill_cus, decode_cus))
+
+    def prepare_cu_splits(self, splits: Sequence[tuple]):
+        """Creates the stream pairs of the given (prefill_cus, decode_cus) splits ahead of use."""
+        n = len(splits)
+        p, d = (C.c_int32 * n)(*[s[0] for s in splits]), (C.c_int32 * n)(*[s[1] for s in splits])
+        _check(lib().nexus_prepare_cu_splits(self._ctx, n, p, d))
+
+    def set_debug_checks(self, on: bool):
+        _check(lib().nexus_set_debug_checks(self._ctx, int(on)))
 
     # -- steps
     def prefill_chunk(self, pb: DevPrefill, kv: KVCache, layers=(0, 1)):

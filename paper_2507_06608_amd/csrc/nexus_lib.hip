@@ -16,7 +16,6 @@
 #include "attn_decode.hpp"
 #include "attn_prefill.hpp"
 #include "common.hpp"
-#include "cost_model.hpp"
 #include "elementwise.hpp"
 #include "gemm.hpp"
 #include "status.hpp"
@@ -69,7 +68,6 @@ struct Layout {
 // after the second) run the decode queue's kernels 20-35 us late each once its attention kernel has run while the
 // prefill queue is active -- the concurrent step then loses 10-50%.  No synthetic probe reproduced it, so the
 // library never keeps more than one pair: changing the split re-creates the two streams (about 12 ms).
-constexpr int kMaxMaskedLayouts = 1;
 
 struct TraceRec {
     hipEvent_t a, b;
@@ -89,9 +87,16 @@ struct nexus_ctx {
     Layout *cur = nullptr;
     long use_clock = 0;
     bool bits_xcd_major = false;  // CU-mask bit order (see make_mask)
-    hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr, ev_sd1 = nullptr;
-    hipEvent_t ev_ph0[2] = {nullptr, nullptr}, ev_ph1[2] = {nullptr, nullptr};  // start / end of the last single-phase call
+    hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr;
+    // ev_ph1[phase]: completion of the last launch that used the phase's workspace (single-phase call, mixed step or
+    // fused step), recorded on whatever stream it ran on; every later launch on another stream waits for it, so steps
+    // stay ordered across a change of layout.  ev_ph0[phase]: start of the last single-phase call.
+    hipEvent_t ev_ph0[2] = {nullptr, nullptr}, ev_ph1[2] = {nullptr, nullptr};
     bool ph_recorded[2] = {false, false};
+    bool ph_timed[2] = {false, false};               // ev_ph0 belongs to the same launch as ev_ph1
+    hipStream_t done_stream[2] = {nullptr, nullptr};  // stream ev_ph1[phase] was recorded on
+    int max_layouts = 8;                              // partitioned stream pairs kept alive (7 = every split in steps of 32 CUs)
+    bool debug_checks = false;                        // validate device-side lengths and page ids on the host before launching
     // tracing
     int trace_phase = -1, trace_kernel = -1;
     std::vector<TraceRec> trace_pool;
@@ -261,6 +266,7 @@ struct PhaseRun {
     int fused_decode = 0;      // > 0: the last fused_decode requests of pb are decode requests (one-token chunks)
     int fused_max_ctx = 0;     // largest context + 1 among them
     int cus;  // CUs the phase's stream may run on
+    PhaseWs *ws;  // the phase's workspace (the context's own, or one carved out of the static scratch array)
     int T;
     const nexus_prefill_batch *pb;
     const nexus_decode_batch *db;
@@ -273,7 +279,7 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
                     void *out, const void *res, const bf16_t *bias, int ld_out, f16_t *out_p32, int out_K,
                     int *deferred_S = nullptr) {
     nexus_ctx *c = r.c;
-    PhaseWs &ws = c->ws[r.phase];
+    PhaseWs &ws = *r.ws;
     const int Kp = p32_kp(K);
     const int n_ftiles = N_packed / 32;
     const GemmPlan p = plan_gemm(r.T, n_ftiles, Kp);
@@ -449,7 +455,7 @@ static int launch_attn_decode(const PhaseRun &r, const AttnDecodeArgs &a) {
 static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y_out) {
     nexus_ctx *c = r.c;
     const nexus_model_desc &m = c->m;
-    PhaseWs &ws = c->ws[r.phase];
+    PhaseWs &ws = *r.ws;
     const LayerW &L = c->layers[layer];
     const bool prefill = r.phase == NEXUS_PHASE_PREFILL;
     bf16_t *k_pool = (bf16_t *)((char *)r.kv->k_pool + (size_t)layer * r.kv->layer_stride_bytes);
@@ -525,7 +531,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
 }
 
 static int run_phase(const PhaseRun &r, int layer_begin, int layer_end) {
-    PhaseWs &ws = r.c->ws[r.phase];
+    PhaseWs &ws = *r.ws;
     const bf16_t *x = (const bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->x : r.db->x);
     bf16_t *y_final = (bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->y : r.db->y);
     for (int l = layer_begin; l < layer_end; ++l) {
@@ -579,6 +585,32 @@ static int check_decode(nexus_ctx *c, const nexus_decode_batch *b) {
     if ((int64_t)b->max_pages * kPage < b->max_ctx) return fail(NEXUS_EINVAL, "page table rows (%d pages) cannot hold max_ctx %d", b->max_pages, b->max_ctx);
     if (((uintptr_t)b->x | (uintptr_t)b->y) & 15) return fail(NEXUS_EINVAL, "x / y must be 16-byte aligned");
     return NEXUS_OK;
+}
+
+// Debug mode: the device-side integer arrays of a step are copied to the host and validated before anything is
+// launched.  The copy runs on the context's own stream and the call waits for it, so the arrays must be complete
+// when the step call is made.
+static int debug_validate(nexus_ctx *c, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv) {
+    if (!c->debug_checks) return NEXUS_OK;
+    std::vector<int32_t> cu, pre, ptp, ctx, ptd;
+    auto fetch = [&](std::vector<int32_t> &dst, const int32_t *src, size_t n) -> int {
+        dst.resize(n);
+        if (n) HIP_TRY(hipMemcpyAsync(dst.data(), src, n * sizeof(int32_t), hipMemcpyDeviceToHost, c->s_main));
+        return NEXUS_OK;
+    };
+    if (pb) {
+        NX_TRY(fetch(cu, pb->cu_chunk, (size_t)pb->n_reqs + 1));
+        NX_TRY(fetch(pre, pb->prefix_len, (size_t)pb->n_reqs));
+        NX_TRY(fetch(ptp, pb->page_table, (size_t)pb->n_reqs * pb->max_pages));
+    }
+    if (db) {
+        NX_TRY(fetch(ctx, db->ctx_len, (size_t)db->n_reqs));
+        NX_TRY(fetch(ptd, db->page_table, (size_t)db->n_reqs * db->max_pages));
+    }
+    HIP_TRY(hipStreamSynchronize(c->s_main));
+    return nexus_validate_batches(kv->n_pages, kPage, pb ? pb->n_reqs : 0, pb ? pb->n_tokens : 0, cu.data(), pre.data(), ptp.data(),
+                                  pb ? pb->max_pages : 0, pb ? pb->max_chunk : 0, pb ? pb->max_total_len : 0, db ? db->n_reqs : 0,
+                                  ctx.data(), ptd.data(), db ? db->max_pages : 0, db ? db->max_ctx : 0);
 }
 
 // ---------------------------------------------------------------------------------------------- CU masks
@@ -636,6 +668,12 @@ int nexus_debug_token_order(int b, int n) {
 
 int nexus_cu_count(nexus_ctx *c) { return c ? c->n_cus : fail(NEXUS_EINVAL, "null context"); }
 
+int nexus_set_debug_checks(nexus_ctx *c, int on) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    c->debug_checks = on != 0;
+    return NEXUS_OK;
+}
+
 void nexus_destroy(nexus_ctx *c) {
     if (!c) return;
     DeviceGuard dg(c->device);
@@ -652,7 +690,7 @@ void nexus_destroy(nexus_ctx *c) {
     }
     (void)hipFree(c->rope_tab);
     (void)hipFree(c->probe_counts);
-    for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_sd1, c->ev_ph0[0], c->ev_ph0[1], c->ev_ph1[0], c->ev_ph1[1]})
+    for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_ph0[0], c->ev_ph0[1], c->ev_ph1[0], c->ev_ph1[1]})
         if (e) (void)hipEventDestroy(e);
     for (auto &t : c->trace_pool) (void)hipEventDestroy(t.a), (void)hipEventDestroy(t.b);
     delete c;
@@ -740,8 +778,10 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         // test hook: the 256 x 256 GEMM tiles can be switched off to compare them bit for bit with the 128 x 128 ones
         const char *tiles = getenv("NEXUS_GEMM_TILES");
         c->allow_p256 = !(tiles && !strcmp(tiles, "128"));
+        if (const char *dbg = getenv("NEXUS_DEBUG_CHECKS")) c->debug_checks = atoi(dbg) != 0;
+        if (const char *ml = getenv("NEXUS_MAX_LAYOUTS")) c->max_layouts = std::max(1, std::min(64, atoi(ml)));
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
-        for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_sd1, &c->ev_ph0[0], &c->ev_ph0[1], &c->ev_ph1[0], &c->ev_ph1[1]})
+        for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_ph0[0], &c->ev_ph0[1], &c->ev_ph1[0], &c->ev_ph1[1]})
             if (hipEventCreateWithFlags(e, hipEventDisableSystemFence) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
         if (rc) break;
         if ((rc = alloc_phase_ws(c, NEXUS_PHASE_PREFILL, limits->max_prefill_tokens, limits->max_prefill_reqs))) break;
@@ -846,9 +886,8 @@ int nexus_kv_export(nexus_ctx *c, const nexus_kv_cache *kv, int layer, void *k_c
     return kv_convert(c, kv, layer, k_canon, v_canon, page_begin, page_count, false);
 }
 
-int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
-    if (!c) return fail(NEXUS_EINVAL, "null context");
-    DeviceGuard dg(c->device);
+// Finds the layout of a split, creating its stream pair if it does not exist yet (about 10 ms, once).
+static int get_layout(nexus_ctx *c, int prefill_cus, int decode_cus, Layout **out) {
     long key = 0;
     if (prefill_cus == NEXUS_CUS_ALL && decode_cus == NEXUS_CUS_ALL) {
         prefill_cus = decode_cus = 0;
@@ -861,16 +900,21 @@ int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
     }
     auto it = c->layouts.find(key);
     if (it == c->layouts.end()) {
-        // Every CU-masked stream owns a hardware queue: keep at most kMaxMaskedLayouts partitioned pairs alive and
-        // retire the least recently used one before creating another.
+        // Every CU-masked stream owns a hardware queue: keep at most max_layouts partitioned pairs alive and
+        // retire the least recently used one (never the current one) before creating another.
         int masked = 0;
         for (auto &kv : c->layouts) masked += kv.first != 0;
-        while (masked >= kMaxMaskedLayouts) {
+        while (masked >= c->max_layouts) {
             auto victim = c->layouts.end();
             for (auto jt = c->layouts.begin(); jt != c->layouts.end(); ++jt)
-                if (jt->first != 0 && (victim == c->layouts.end() || jt->second.last_use < victim->second.last_use)) victim = jt;
+                if (jt->first != 0 && (c->max_layouts == 1 || &jt->second != c->cur) &&
+                    (victim == c->layouts.end() || jt->second.last_use < victim->second.last_use))
+                    victim = jt;
+            if (victim == c->layouts.end()) break;
             HIP_TRY(hipStreamSynchronize(victim->second.sp));
             HIP_TRY(hipStreamSynchronize(victim->second.sd));
+            for (int ph = 0; ph < 2; ++ph)  // its work is complete; a new stream may reuse the handle value
+                if (c->done_stream[ph] == victim->second.sp || c->done_stream[ph] == victim->second.sd) c->done_stream[ph] = nullptr;
             if (c->cur == &victim->second) c->cur = &c->layouts[0];
             destroy_layout(victim->second);
             c->layouts.erase(victim);
@@ -881,7 +925,30 @@ int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
         it = c->layouts.emplace(key, L).first;
     }
     it->second.last_use = ++c->use_clock;
-    c->cur = &it->second;
+    *out = &it->second;
+    return NEXUS_OK;
+}
+
+int nexus_set_cu_split(nexus_ctx *c, int prefill_cus, int decode_cus) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    DeviceGuard dg(c->device);
+    Layout *L = nullptr;
+    NX_TRY(get_layout(c, prefill_cus, decode_cus, &L));
+    c->cur = L;  // work in flight on the previous layout keeps running there; later launches are ordered after it by events
+    return NEXUS_OK;
+}
+
+int nexus_prepare_cu_splits(nexus_ctx *c, int n, const int32_t *prefill_cus, const int32_t *decode_cus) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    if (n < 0 || (n > 0 && (!prefill_cus || !decode_cus))) return fail(NEXUS_EINVAL, "bad split list");
+    int distinct = 0;
+    for (int i = 0; i < n; ++i) distinct += !(prefill_cus[i] == NEXUS_CUS_ALL && decode_cus[i] == NEXUS_CUS_ALL);
+    if (distinct > c->max_layouts) return fail(NEXUS_ESHAPE, "%d partitioned layouts asked for, at most %d are kept alive", distinct, c->max_layouts);
+    DeviceGuard dg(c->device);
+    for (int i = 0; i < n; ++i) {
+        Layout *L = nullptr;
+        NX_TRY(get_layout(c, prefill_cus[i], decode_cus[i], &L));
+    }
     return NEXUS_OK;
 }
 
@@ -892,17 +959,34 @@ static PhaseRun make_run(nexus_ctx *c, int phase, const nexus_prefill_batch *pb,
     r.n_xcd = phase == NEXUS_PHASE_PREFILL ? c->cur->p_xcd : c->cur->d_xcd;
     r.cus = phase == NEXUS_PHASE_PREFILL ? c->cur->p_cus : c->cur->d_cus;
     if (r.cus <= 0) r.cus = c->n_cus;
+    r.ws = &c->ws[phase];
     r.T = phase == NEXUS_PHASE_PREFILL ? pb->n_tokens : db->n_reqs;
     return r;
 }
 
+// Orders stream s after the last launch that used `phase`'s workspace when that ran on another stream (another
+// layout, or the other stream of this one); on the same stream the stream's own order does it.
+static int order_after(nexus_ctx *c, hipStream_t s, int phase) {
+    if (c->ph_recorded[phase] && c->done_stream[phase] != s) HIP_TRY(hipStreamWaitEvent(s, c->ev_ph1[phase], 0));
+    return NEXUS_OK;
+}
+static int mark_done(nexus_ctx *c, hipStream_t s, int phase, bool timed) {
+    HIP_TRY(hipEventRecord(c->ev_ph1[phase], s));
+    c->ph_recorded[phase] = true, c->ph_timed[phase] = timed, c->done_stream[phase] = s;
+    return NEXUS_OK;
+}
+
 // A phase on its own: bracketed by events on the phase's stream so that the caller can poll for its completion
-// and read its duration while the other phase keeps running.
+// and read its duration while the other phase keeps running.  It follows the previous launch of the same phase
+// (and, for the fused step, which borrows the decode phase's attention workspace, of the decode phase too), never
+// the other phase: the two phase loops stay independent.
 static int run_single_phase(nexus_ctx *c, const PhaseRun &r, int lb, int le) {
+    NX_TRY(order_after(c, r.s, r.phase));
+    if (r.fused_decode) NX_TRY(order_after(c, r.s, NEXUS_PHASE_DECODE));
     HIP_TRY(hipEventRecord(c->ev_ph0[r.phase], r.s));
     NX_TRY(run_phase(r, lb, le));
-    HIP_TRY(hipEventRecord(c->ev_ph1[r.phase], r.s));
-    c->ph_recorded[r.phase] = true;
+    NX_TRY(mark_done(c, r.s, r.phase, true));
+    if (r.fused_decode) NX_TRY(mark_done(c, r.s, NEXUS_PHASE_DECODE, false));
     return NEXUS_OK;
 }
 
@@ -911,6 +995,7 @@ int nexus_prefill_chunk(nexus_ctx *c, int lb, int le, const nexus_prefill_batch 
     NX_TRY(check_kv(c, kv, le));
     NX_TRY(check_prefill(c, pb));
     DeviceGuard dg(c->device);
+    NX_TRY(debug_validate(c, pb, nullptr, kv));
     return run_single_phase(c, make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le);
 }
 
@@ -919,6 +1004,7 @@ int nexus_decode_step(nexus_ctx *c, int lb, int le, const nexus_decode_batch *db
     NX_TRY(check_kv(c, kv, le));
     NX_TRY(check_decode(c, db));
     DeviceGuard dg(c->device);
+    NX_TRY(debug_validate(c, nullptr, db, kv));
     return run_single_phase(c, make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le);
 }
 
@@ -933,6 +1019,7 @@ int nexus_fused_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *ba
         return fail(NEXUS_EINVAL, "max_decode_ctx %d outside (0, min(max_positions %d, max_total_len %d)]", max_decode_ctx, c->lim.max_positions, batch->max_total_len);
     if ((int64_t)batch->max_pages * kPage < max_decode_ctx) return fail(NEXUS_EINVAL, "page table rows (%d pages) cannot hold max_decode_ctx %d", batch->max_pages, max_decode_ctx);
     DeviceGuard dg(c->device);
+    NX_TRY(debug_validate(c, batch, nullptr, kv));
     PhaseRun r = make_run(c, NEXUS_PHASE_PREFILL, batch, nullptr, kv);
     r.fused_decode = n_decode_reqs, r.fused_max_ctx = max_decode_ctx;
     return run_single_phase(c, r, lb, le);
@@ -952,10 +1039,13 @@ int nexus_phase_query(nexus_ctx *c, int phase) {
 int nexus_phase_wait(nexus_ctx *c, int phase, float *elapsed_ms) {
     if (!c) return fail(NEXUS_EINVAL, "null context");
     if (phase != NEXUS_PHASE_PREFILL && phase != NEXUS_PHASE_DECODE) return fail(NEXUS_EINVAL, "unknown phase %d", phase);
-    if (!c->ph_recorded[phase]) return fail(NEXUS_ESTATE, "no single-phase call has been made for this phase");
+    if (!c->ph_recorded[phase]) return fail(NEXUS_ESTATE, "nothing has been launched for this phase");
     DeviceGuard dg(c->device);
     HIP_TRY(hipEventSynchronize(c->ev_ph1[phase]));
-    if (elapsed_ms) HIP_TRY(hipEventElapsedTime(elapsed_ms, c->ev_ph0[phase], c->ev_ph1[phase]));
+    if (elapsed_ms) {
+        if (c->ph_timed[phase]) HIP_TRY(hipEventElapsedTime(elapsed_ms, c->ev_ph0[phase], c->ev_ph1[phase]));
+        else *elapsed_ms = -1.f;  // the phase last ran inside a mixed or fused step, which brackets no phase of its own
+    }
     return NEXUS_OK;
 }
 
@@ -966,6 +1056,7 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
     NX_TRY(check_prefill(c, pb));
     NX_TRY(check_decode(c, db));
     DeviceGuard dg(c->device);
+    NX_TRY(debug_validate(c, pb, db, kv));
     Layout *L = c->cur;
     hipStream_t cs = (hipStream_t)caller_stream;
     const bool split = L->sd != L->sp;
@@ -974,12 +1065,15 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
         HIP_TRY(hipStreamWaitEvent(L->sp, c->ev_caller, 0));
         if (split) HIP_TRY(hipStreamWaitEvent(L->sd, c->ev_caller, 0));
     }
+    // Steps of one context never overlap: both phases of this step follow the previous launch of either phase,
+    // whatever layout that ran on (no-ops before the first step and for work on this very stream).  A request that
+    // finished prefilling in step n can therefore decode in step n + 1, and a change of layout between two steps
+    // needs no synchronisation.
+    NX_TRY(order_after(c, L->sp, NEXUS_PHASE_PREFILL));
+    NX_TRY(order_after(c, L->sp, NEXUS_PHASE_DECODE));
     if (split) {
-        // steps of one context never overlap: this step's prefill phase follows the previous step's decode phase
-        // (a no-op before the first step), and through the fork below so does its decode phase the previous
-        // prefill phase.  A request that finished prefilling in step n can therefore decode in step n + 1.
-        HIP_TRY(hipStreamWaitEvent(L->sp, c->ev_sd1, 0));
-        // fork: the decode stream starts when the prefill stream reaches this point
+        // fork: the decode stream starts when the prefill stream reaches this point, i.e. after everything the
+        // prefill stream has just been made to wait for
         HIP_TRY(hipEventRecord(c->ev_fork, L->sp));
         HIP_TRY(hipStreamWaitEvent(L->sd, c->ev_fork, 0));
     }
@@ -988,34 +1082,29 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
         if (split) HIP_TRY(hipEventRecord(c->ev_sd0, L->sd));
     }
     NX_TRY(run_phase(make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le));
-    if (timing) HIP_TRY(hipEventRecord(c->ev_sp1, L->sp));
+    NX_TRY(mark_done(c, L->sp, NEXUS_PHASE_PREFILL, false));
     NX_TRY(run_phase(make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le));
-    if (timing || split) HIP_TRY(hipEventRecord(c->ev_sd1, L->sd));
+    NX_TRY(mark_done(c, L->sd, NEXUS_PHASE_DECODE, false));
     if (cs) {
-        if (split) {
-            if (!timing) HIP_TRY(hipEventRecord(c->ev_sp1, L->sp));
-            HIP_TRY(hipStreamWaitEvent(cs, c->ev_sp1, 0));
-            HIP_TRY(hipStreamWaitEvent(cs, c->ev_sd1, 0));
-        } else {
-            HIP_TRY(hipEventRecord(c->ev_fork, L->sp));
-            HIP_TRY(hipStreamWaitEvent(cs, c->ev_fork, 0));
-        }
+        if (split) HIP_TRY(hipStreamWaitEvent(cs, c->ev_ph1[NEXUS_PHASE_PREFILL], 0));
+        HIP_TRY(hipStreamWaitEvent(cs, c->ev_ph1[NEXUS_PHASE_DECODE], 0));
     }
+    hipEvent_t ev_sp1 = c->ev_ph1[NEXUS_PHASE_PREFILL], ev_sd1 = c->ev_ph1[NEXUS_PHASE_DECODE];
     if (timing) {
         HIP_TRY(hipStreamSynchronize(L->sp));
         if (split) HIP_TRY(hipStreamSynchronize(L->sd));
         float tp = 0, td = 0;
-        HIP_TRY(hipEventElapsedTime(&tp, c->ev_sp0, c->ev_sp1));
+        HIP_TRY(hipEventElapsedTime(&tp, c->ev_sp0, ev_sp1));
         if (split) {
             float d0 = 0, pd = 0;
-            HIP_TRY(hipEventElapsedTime(&td, c->ev_sd0, c->ev_sd1));
-            HIP_TRY(hipEventElapsedTime(&pd, c->ev_sp0, c->ev_sd1));  // prefill start -> decode end
+            HIP_TRY(hipEventElapsedTime(&td, c->ev_sd0, ev_sd1));
+            HIP_TRY(hipEventElapsedTime(&pd, c->ev_sp0, ev_sd1));  // prefill start -> decode end
             HIP_TRY(hipEventElapsedTime(&d0, c->ev_sp0, c->ev_sd0));  // start skew (may be negative)
             const float start = std::min(0.f, d0);
             timing->t_prefill_ms = tp, timing->t_decode_ms = td;
             timing->t_step_ms = std::max(tp, pd) - start;
         } else {
-            HIP_TRY(hipEventElapsedTime(&td, c->ev_sp0, c->ev_sd1));  // decode waits for prefill: its latency includes it
+            HIP_TRY(hipEventElapsedTime(&td, c->ev_sp0, ev_sd1));  // decode waits for prefill: its latency includes it
             timing->t_prefill_ms = tp, timing->t_decode_ms = td, timing->t_step_ms = td;
         }
     }
@@ -1042,28 +1131,6 @@ static int time_phase(nexus_ctx *c, int phase, int lb, int le, const nexus_prefi
     }
     *out_ms = median(t);
     return NEXUS_OK;
-}
-
-// The selection rule; kept free of HIP so that the host tests can drive it with synthetic curves.
-int nexus_choose_split(int n, const float *t_p, const float *t_d, const float *t_step, float t_p_all, float t_d_all, int policy, float alpha,
-                       float beta) {
-    if (n <= 0 || !t_p || !t_d || !t_step) return fail(NEXUS_EINVAL, "bad curve arguments");
-    if (policy < 0 || policy > 2) return fail(NEXUS_EINVAL, "unknown policy %d", policy);
-    int best = -1;
-    if (policy == NEXUS_POLICY_MIN_STEP) {
-        for (int i = 0; i < n; ++i)
-            if (best < 0 || t_step[i] < t_step[best]) best = i;
-        return best;
-    }
-    const bool pp = policy == NEXUS_POLICY_PREFILL_PRIORITIZED;
-    const float *obj = pp ? t_p : t_d, *con = pp ? t_d : t_p;
-    const double bound = pp ? (double)beta * t_d_all : (double)alpha * t_p_all;
-    for (int i = 0; i < n; ++i)
-        if ((double)con[i] <= bound && (best < 0 || obj[i] < obj[best])) best = i;
-    if (best < 0)  // nothing meets the slack: take the candidate that violates it least
-        for (int i = 0; i < n; ++i)
-            if (best < 0 || con[i] < con[best]) best = i;
-    return best;
 }
 
 int nexus_profile_split(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
@@ -1163,91 +1230,6 @@ int nexus_debug_fetch(nexus_ctx *c, int phase, int which, int32_t n_tokens, void
         HIP_TRY(hipGetLastError());
     }
     HIP_TRY(hipStreamSynchronize(c->s_main));
-    return NEXUS_OK;
-}
-
-// ---------------------------------------------------------------------------------------------- partition controller
-static int check_cost_model(const nexus_cost_model *m) {
-    if (!m || (m->n_prefill_ops > 0 && !m->prefill_ops) || (m->n_decode_ops > 0 && !m->decode_ops)) return fail(NEXUS_EINVAL, "null cost model");
-    if (m->n_prefill_ops < 0 || m->n_decode_ops < 0) return fail(NEXUS_EINVAL, "negative operator count");
-    if (!(m->peak_flops > 0.0) || !(m->peak_bytes_per_s > 0.0)) return fail(NEXUS_EINVAL, "peak throughput and bandwidth must be positive");
-    for (int p = 0; p < 2; ++p) {
-        const nexus_cost_op *ops = p ? m->decode_ops : m->prefill_ops;
-        for (int i = 0; i < (p ? m->n_decode_ops : m->n_prefill_ops); ++i) {
-            if (!(ops[i].r_sat > 0.0) || ops[i].r_sat > 1.0) return fail(NEXUS_EINVAL, "operator %d: r_sat %g outside (0, 1]", i, ops[i].r_sat);
-            if (ops[i].flops < 0.0 || ops[i].bytes < 0.0) return fail(NEXUS_EINVAL, "operator %d: negative work", i);
-            if (ops[i].kind != NEXUS_OP_DENSE && ops[i].kind != NEXUS_OP_ATTENTION) return fail(NEXUS_EINVAL, "operator %d: bad kind", i);
-        }
-    }
-    return NEXUS_OK;
-}
-
-int nexus_cost_latency(const nexus_cost_model *model, int phase, int share, int total, double *seconds) {
-    NX_TRY(check_cost_model(model));
-    if (!seconds) return fail(NEXUS_EINVAL, "null output");
-    if (phase != NEXUS_PHASE_PREFILL && phase != NEXUS_PHASE_DECODE) return fail(NEXUS_EINVAL, "bad phase %d", phase);
-    if (total < 1 || share < 1 || share > total) return fail(NEXUS_EINVAL, "share %d of %d", share, total);
-    *seconds = CostModel(*model).phase_time(phase, share, total);
-    return NEXUS_OK;
-}
-
-int nexus_adjust_partition(const nexus_cost_model *model, int target_phase, int cur_prefill_share, int total, double alpha,
-                           double beta, int32_t *new_prefill_share, int32_t *evaluations) {
-    NX_TRY(check_cost_model(model));
-    if (!new_prefill_share) return fail(NEXUS_EINVAL, "null output");
-    if (target_phase != NEXUS_PHASE_PREFILL && target_phase != NEXUS_PHASE_DECODE) return fail(NEXUS_EINVAL, "bad phase %d", target_phase);
-    if (total < 2 || cur_prefill_share < 0 || cur_prefill_share > total) return fail(NEXUS_EINVAL, "prefill share %d of %d", cur_prefill_share, total);
-    if (!(alpha >= 1.0) || !(beta >= 1.0)) return fail(NEXUS_EINVAL, "slack factors must be >= 1");
-    int n = 0;
-    *new_prefill_share = CostModel(*model).adjust(target_phase, cur_prefill_share, total, alpha, beta, &n);
-    if (evaluations) *evaluations = n;
-    return NEXUS_OK;
-}
-
-int nexus_partition_controller(const nexus_cost_model *model, double kv_usage, double kv_switch, int cur_prefill_share,
-                               int total, double alpha, double beta, int delta, int32_t *new_prefill_share) {
-    if (delta < 0) return fail(NEXUS_EINVAL, "negative buffer zone");
-    int32_t proposed = 0;
-    const int target = kv_usage > kv_switch ? NEXUS_PHASE_DECODE : NEXUS_PHASE_PREFILL;
-    NX_TRY(nexus_adjust_partition(model, target, cur_prefill_share, total, alpha, beta, &proposed, nullptr));
-    *new_prefill_share = std::abs(proposed - cur_prefill_share) < delta ? cur_prefill_share : proposed;
-    return NEXUS_OK;
-}
-
-int nexus_cost_fit(int n, const double *shares, const double *seconds, double peak_flops, double *flops, double *r_sat, double *lambda) {
-    if (n < 1 || !shares || !seconds || !flops || !r_sat || !lambda) return fail(NEXUS_EINVAL, "bad argument");
-    if (!(peak_flops > 0.0)) return fail(NEXUS_EINVAL, "peak throughput must be positive");
-    for (int i = 0; i < n; ++i)
-        if (!(shares[i] > 0.0) || shares[i] > 1.0 || !(seconds[i] > 0.0)) return fail(NEXUS_EINVAL, "point %d: share %g, %g s", i, shares[i], seconds[i]);
-    fit_saturation_curve(n, shares, seconds, peak_flops, flops, r_sat, lambda);
-    return NEXUS_OK;
-}
-
-int nexus_cost_describe(const nexus_model_desc *d, int layers, double prefill_tokens, double prefill_pairs, double prefill_kv_tokens,
-                        double decode_reqs, double decode_kv_tokens, nexus_cost_op *prefill_ops, nexus_cost_op *decode_ops) {
-    if (!d || !prefill_ops || !decode_ops || layers < 1) return fail(NEXUS_EINVAL, "bad argument");
-    const double q_dim = (double)d->n_q_heads * d->head_dim, kv_dim = (double)d->n_kv_heads * d->head_dim;
-    const double out_rows[5] = {q_dim + 2 * kv_dim, 0, (double)d->hidden, 2.0 * d->ffn, (double)d->hidden};
-    const double in_cols[5] = {(double)d->hidden, 0, q_dim, (double)d->hidden, (double)d->ffn};
-    const double kv_token_bytes = 2.0 * kv_dim * 2.0;  // K and V, two bytes each
-    for (int i = 0; i < 5; ++i) {
-        nexus_cost_op p{}, q{};
-        p.r_sat = q.r_sat = 1.0;
-        if (i == 1) {
-            p.kind = q.kind = NEXUS_OP_ATTENTION;
-            p.flops = 4.0 * d->head_dim * d->n_q_heads * prefill_pairs;  // QK^T and PV, two flops per multiply-add
-            p.bytes = prefill_kv_tokens * kv_token_bytes;
-            q.flops = 4.0 * d->head_dim * d->n_q_heads * decode_kv_tokens;
-            q.bytes = decode_kv_tokens * kv_token_bytes;
-        } else {
-            const double weights = out_rows[i] * in_cols[i];
-            p.kind = q.kind = NEXUS_OP_DENSE;
-            p.flops = 2.0 * prefill_tokens * weights, p.bytes = 2.0 * weights;
-            q.flops = 2.0 * decode_reqs * weights, q.bytes = 2.0 * weights;
-        }
-        p.flops *= layers, p.bytes *= layers, q.flops *= layers, q.bytes *= layers;
-        prefill_ops[i] = p, decode_ops[i] = q;
-    }
     return NEXUS_OK;
 }
 

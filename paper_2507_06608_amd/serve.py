@@ -246,10 +246,15 @@ class DecoupledRunner(TraceRunner):
     def enable_controller(self, calibration, **params):
         """Repartition at run time: whenever a prefill batch is about to start next to a live decode pool, the
         library's controller is asked for the split (decode-prioritised above the KV-usage switch point,
-        prefill-prioritised below, changes smaller than delta steps suppressed) and the stream pair is re-created
-        if it answers with a new one.  The switch is synchronous: it waits for the decode step in flight."""
+        prefill-prioritised below, changes smaller than delta steps suppressed) and another stream pair is selected
+        if it answers with a new one.  The switch waits for nothing: the decode step in flight finishes on its old
+        share, the next one starts on the new pair (the library orders it after the old one)."""
         self.calibration = calibration
         self.ctrl.update(params)
+        # Sec. 5: every layout the controller can choose exists before serving starts
+        n_cus, total = self.ctx.cu_count, self.ctrl["total"]
+        step = n_cus // total
+        self.ctx.prepare_cu_splits([(step * k, n_cus - step * k) for k in range(1, total)])
 
     def _batch_shape(self, phase: int, it):
         if phase == nx.PHASE_PREFILL:
@@ -270,7 +275,7 @@ class DecoupledRunner(TraceRunner):
         new = model.partition_controller(kv_usage, c["kv_switch"], cur, c["total"], c["alpha"], c["beta"], c["delta"])
         if new != cur:
             t_l = time.perf_counter()
-            self.ctx.set_cu_split(step * new, n_cus - step * new)     # waits for what is in flight on the old pair
+            self.ctx.set_cu_split(step * new, n_cus - step * new)     # a pointer switch; nothing in flight is waited for
             self.switches.append((now, self.split[0], step * new, (time.perf_counter() - t_l) * 1e3))
             self.split = (step * new, n_cus - step * new)
 

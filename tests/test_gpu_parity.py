@@ -277,18 +277,19 @@ def test_argument_errors_launch_nothing(nx):
     ctx.close()
 
 
-def test_cfg2_full_size_sampled_outputs_in_bench_launch_configuration(nx, oracle):
-    """The benchmark workload at full size, run the way bench.py runs it (mixed step on a partitioned layout,
-    KV generated on the device).  The oracle evaluates a sample it can afford: the first 40 tokens of the chunk
-    (they attend to the whole 1536-token prefix) and 6 decode requests including the shortest and longest context.
-    Whole-output properties that hold at any size are checked on everything: finiteness, and bit-identity of the
-    concurrent step with the serialized one."""
-    _announce("cfg2 full size, sampled")
+def test_cfg2_full_size_every_output_in_bench_launch_configuration(nx, oracle):
+    """The 8B-shaped 512-over-1536 + 64-decode workload at full size, run the way bench.py runs it (mixed step on a
+    partitioned layout, KV generated on the device), with EVERY output compared with the oracle: all 512 chunk rows
+    (the last strips carry the longest causal span and the last key-range split of the attention), all 64 decode
+    requests, every appended K/V slot, every untouched slot bit for bit.  Plus bit-identity of the concurrent step
+    with the serialized one."""
+    _announce("cfg2 full size, every row")
     wl = synth.config(2, seed=0, kv_device="cuda:0")
     w = synth.make_weights(wl.shape, 0)
     ctx = nx.context_for(wl)
     ctx.load_layer(0, w)
     kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    before = ctx.kv_export(kv)
     pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
     ctx.set_cu_split(160, 96)
     ctx.mixed_step(pb, db, kv, stream=torch.cuda.Stream())
@@ -307,67 +308,93 @@ def test_cfg2_full_size_sampled_outputs_in_bench_launch_configuration(nx, oracle
     assert torch.equal(db.y.view(torch.int16), yd.view(torch.int16))
     for a, b in zip(ctx.kv_export(kv2), kv_after):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    del kv2
 
-    # sampled oracle comparison
-    d = wl.decode
-    order = np.argsort(d.ctx_len)
-    dec_sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 0, 17, 63})
-    n_pre = 40
-    sub = synth.subset_for_oracle(wl, [0], dec_sample)
-    sp = sub.prefill
-    sub.prefill = synth.PrefillBatch(sp.x[:n_pre], np.array([0, n_pre], np.int32), sp.prefix_len[:1], sp.page_table[:1])
-    ref = run_oracle(oracle, sub, w)
-    assert_close("cfg2 prefill rows 0..39", f32(yp[:n_pre]), ref["y_p"])
-    assert_close("cfg2 decode sample", f32(yd[dec_sample]), ref["y_d"])
-    # appended K/V of the sampled tokens: page ids of the sub-pool map back through notes["pages"]
-    pages = sub.notes["pages"]
-    ps = wl.shape.page_size
-    kg, vg = kv_after
-    for name, req_row, positions in (
-            [("prefill", sub.prefill.page_table[0], range(int(sp.prefix_len[0]), int(sp.prefix_len[0]) + n_pre))] +
-            [(f"decode {j}", sub.decode.page_table[i], [int(sub.decode.ctx_len[i])]) for i, j in enumerate(dec_sample)]):
-        for pos in positions:
-            sp_page = int(req_row[pos // ps])
-            full_page = pages[sp_page]
-            assert_close(f"K {name} pos {pos}", f32(kg[full_page, :, pos % ps]), ref["k_pool"][sp_page, :, pos % ps])
-            assert_close(f"V {name} pos {pos}", f32(vg[full_page, :, pos % ps]), ref["v_pool"][sp_page, :, pos % ps])
+    ref = run_oracle(oracle, wl, w)
+    assert_close("cfg2 prefill, all 512 rows", f32(yp), ref["y_p"])
+    assert_close("cfg2 prefill, last 32-row strip", f32(yp[-32:]), ref["y_p"][-32:])
+    assert_close("cfg2 decode, all 64 requests", f32(yd), ref["y_d"])
+    check_pools("cfg2", wl, kv_after, ref, expected_touched(wl), before)
     ctx.close()
 
 
-def _check_sampled(oracle, tag, wl, w, yp, yd, kv_after, n_pre=16):
-    """Oracle on the first n_pre rows of every chunk and on five decode requests (shortest, longest and median
-    context and two fixed ones) of a workload too large to evaluate whole, with the K/V those rows append."""
+def _strip_rows(cu, r, strip=32):
+    """Batch rows of request r in its first, a middle and its last 32-row strip (the last may be ragged)."""
+    a, b = int(cu[r]), int(cu[r + 1])
+    n = b - a
+    picks = set(range(a, min(a + strip, b)))
+    mid = a + (n // 2) // strip * strip
+    picks |= set(range(mid, min(mid + strip, b)))
+    picks |= set(range(a + (n - 1) // strip * strip, b))
+    return sorted(picks)
+
+
+def parity_stats(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    err, bound = np.abs(got - ref), 2e-2 + 2e-2 * np.abs(ref)
+    return float((err / bound).max()), float((err > bound).mean()), float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+
+
+def _check_sampled(oracle, tag, wl, w, yp, yd, kv_after, gate=True):
+    """Oracle on the first, a middle and the LAST 32-row strip of every chunk (the last strip has the longest causal
+    span, the ragged tail and the last key-range split) and on five decode requests (shortest, longest and median
+    context and two fixed ones) of a workload too large to evaluate whole; the K/V appended by EVERY chunk token and
+    by the sampled decode requests.  The oracle's row-subset entry appends all tokens' K/V and evaluates the listed
+    rows.  gate=False reports the elementwise figures without asserting them (relative L2 and K/V stay asserted).
+    Returns {name: (worst err/bound, fraction outside the bar, relative L2)}."""
+    from tests.parity_util import oracle_model, oracle_weights
     pb_host, d = wl.prefill, wl.decode
     order = np.argsort(d.ctx_len)
     dec_sample = sorted({int(order[0]), int(order[-1]), int(order[len(order) // 2]), 3, d.n_reqs - 2})
     sub = synth.subset_for_oracle(wl, list(range(pb_host.n_reqs)), dec_sample)
-    sp = sub.prefill
-    rows = np.concatenate([np.arange(int(sp.cu_chunk[r]), int(sp.cu_chunk[r]) + n_pre) for r in range(sp.n_reqs)])
-    sub.prefill = synth.PrefillBatch(sp.x[torch.as_tensor(rows)], np.arange(sp.n_reqs + 1, dtype=np.int32) * n_pre, sp.prefix_len, sp.page_table)
-    ref = run_oracle(oracle, sub, w)
-    full_rows = np.concatenate([np.arange(int(pb_host.cu_chunk[r]), int(pb_host.cu_chunk[r]) + n_pre) for r in range(pb_host.n_reqs)])
-    assert_close(f"{tag} prefill sampled rows", f32(yp[torch.as_tensor(full_rows, device=yp.device)]), ref["y_p"])
-    assert_close(f"{tag} decode sample", f32(yd[dec_sample]), ref["y_d"])
-    pages = sub.notes["pages"]
+    sp, sd = sub.prefill, sub.decode
+    rows = np.concatenate([_strip_rows(sp.cu_chunk, r) for r in range(sp.n_reqs)]).astype(np.int32)
+    m, ow = oracle_model(oracle, wl.shape), oracle_weights(w)
+    kp, vp = f32(sub.k_pool).copy(), f32(sub.v_pool).copy()
+    ref_p = oracle.layer_prefill_rows(m, ow, f32(sp.x), sp.cu_chunk, sp.prefix_len, sp.page_table, kp, vp, rows)
+    ref_d = oracle.layer_decode(m, ow, f32(sd.x), sd.ctx_len, sd.page_table, kp, vp)
+    got_p = f32(yp[torch.as_tensor(rows, device=yp.device, dtype=torch.long)])
+    got_d = f32(yd[dec_sample])
+    stats = {"prefill": parity_stats(got_p, ref_p), "decode": parity_stats(got_d, ref_d)}
+    if not gate:
+        # what the bf16 storage of the cache alone costs on these very rows (the exact layer with nothing changed but
+        # the rounding of the K/V it appends), and the path against THAT: its own arithmetic
+        kp2, vp2 = f32(sub.k_pool).copy(), f32(sub.v_pool).copy()
+        floor_p = oracle.layer_prefill_rows(m, ow, f32(sp.x), sp.cu_chunk, sp.prefix_len, sp.page_table, kp2, vp2, rows,
+                                            kv_store_bf16=True)
+        stats["prefill, bf16 cache storage alone"] = parity_stats(floor_p, ref_p)
+        stats["prefill, path against the layer with a bf16 cache"] = parity_stats(got_p, floor_p)
+        del kp2, vp2
+    if gate:
+        assert_close(f"{tag} prefill first/middle/last strips ({len(rows)} rows)", got_p, ref_p)
+        assert_close(f"{tag} decode sample", got_d, ref_d)
+    else:
+        for name, (wst, frac, rel) in stats.items():
+            print(f"[parity, reported] {tag} {name}: worst err/bound {wst:.2f}, {100 * frac:.2f} % outside the bar, rel L2 {rel:.2e}", flush=True)
+            assert rel <= 1e-2, f"{tag} {name}: relative L2 {rel:.3g}"
+    # appended K/V: every chunk token, and the new token of each sampled decode request
+    pages = np.asarray(sub.notes["pages"])
     ps = wl.shape.page_size
-    kg, vg = kv_after
-    checks = [(f"prefill {r}", sub.prefill.page_table[r], range(int(sp.prefix_len[r]), int(sp.prefix_len[r]) + n_pre))
-              for r in range(sp.n_reqs)]
-    checks += [(f"decode {j}", sub.decode.page_table[i], [int(sub.decode.ctx_len[i])]) for i, j in enumerate(dec_sample)]
-    for name, req_row, positions in checks:
-        for pos in positions:
-            sp_page = int(req_row[pos // ps])
-            full_page = pages[sp_page]
-            assert_close(f"{tag} K {name} pos {pos}", f32(kg[full_page, :, pos % ps]), ref["k_pool"][sp_page, :, pos % ps])
-            assert_close(f"{tag} V {name} pos {pos}", f32(vg[full_page, :, pos % ps]), ref["v_pool"][sp_page, :, pos % ps])
-
+    sp_pages, slots = [], []
+    for r in range(sp.n_reqs):
+        pos = np.arange(int(sp.prefix_len[r]), int(sp.prefix_len[r]) + int(sp.cu_chunk[r + 1] - sp.cu_chunk[r]))
+        sp_pages.append(sp.page_table[r, pos // ps]), slots.append(pos % ps)
+    for i in range(sd.n_reqs):
+        c = int(sd.ctx_len[i])
+        sp_pages.append(sd.page_table[i, c // ps:c // ps + 1]), slots.append(np.array([c % ps]))
+    sp_pages, slots = np.concatenate(sp_pages), np.concatenate(slots)
+    full = torch.as_tensor(pages[sp_pages], device=kv_after[0].device, dtype=torch.long)
+    sl = torch.as_tensor(slots, device=kv_after[0].device, dtype=torch.long)
+    assert_close(f"{tag} K appended ({len(slots)} tokens)", f32(kv_after[0][full, :, sl]), kp[sp_pages, :, slots])
+    assert_close(f"{tag} V appended ({len(slots)} tokens)", f32(kv_after[1][full, :, sl]), vp[sp_pages, :, slots])
+    return stats
 
 
 def test_cfg3_heavy_mix_full_size_sampled(nx, oracle, monkeypatch):
     """The heavy mix at full size (4 x 2048-token chunks over prefixes up to 6144, 256 decode requests with contexts
     up to 8192; one layer).  Long chunks take the 256 x 256 GEMM tiles and the decode batch of 256 takes the tiled
-    GEMM instead of the streaming one.  The oracle evaluates the first 16 rows of every chunk (rows 0, 2048, 4096,
-    6144 of the batch: four different token blocks, four prefix lengths) and five decode requests; every other
+    GEMM instead of the streaming one.  The oracle evaluates the first, a middle and the last 32-row strip of every
+    chunk (four prefix lengths) and five decode requests; every other
     output row is covered by a property that holds at any size: the step computed with 128 x 128 tiles only (same
     per-element summation order, different kernels) and the serialized step must both reproduce it bit for bit."""
     _announce("cfg3 full size, sampled")
@@ -404,14 +431,21 @@ def test_cfg3_heavy_mix_full_size_sampled(nx, oracle, monkeypatch):
     _check_sampled(oracle, "cfg3", wl, w, yp, yd, kv_after)
 
 
-@pytest.mark.parametrize("idx,layer,split", [(4, 47, (160, 96)), (5, 79, (192, 64))])
-def test_larger_model_shapes_full_size_sampled(nx, oracle, idx, layer, split):
+@pytest.mark.parametrize("idx,layer,split,std", [(4, 47, (160, 96), None), (5, 79, (192, 64), None), (5, 79, (192, 64), 0.02)],
+                         ids=["cfg4", "cfg5 fan-in weights", "cfg5 N(0, 0.02) weights"])
+def test_larger_model_shapes_full_size_sampled(nx, oracle, idx, layer, split, std):
     """One layer of the 14B-shaped (G = 5, hidden 5120) and the 70B-shaped (G = 8, hidden 8192, FFN 28672)
     configurations at full batch size, with the weights of a late layer of the stack: concurrent == serialized bit
-    for bit, and the oracle on sampled rows."""
-    _announce(f"cfg{idx} one layer at full size, sampled")
+    for bit, and the oracle on the first, a middle and the last strip of the chunk and on sampled decode requests.
+    The 70B shape runs under two weight recipes.  With the variance following the fan-in the whole bar is asserted.
+    With N(0, 0.02) at hidden 8192 the elementwise bar is out of reach of ANY path that keeps a bf16 KV cache
+    (tests/test_kv_storage_floor.py shows it on the CPU: the cache's rounding alone puts ~2 % of a layer's outputs
+    up to ~4x outside the bar); there the relative L2 bar, the appended K/V and finiteness are asserted, the
+    elementwise figures are printed, and the share of outputs outside the bar must stay at the level that floor
+    explains."""
+    _announce(f"cfg{idx} one layer at full size, sampled, weight std {std or 'default'}")
     wl = synth.config(idx, seed=0, kv_device="cuda:0")
-    w = synth.make_weights(wl.shape, 0, layer)
+    w = synth.make_weights(wl.shape, 0, layer, std=std)
 
     def run(split):
         ctx = nx.context_for(wl)
@@ -426,13 +460,22 @@ def test_larger_model_shapes_full_size_sampled(nx, oracle, idx, layer, split):
         return out
 
     yp, yd, kv_after = run(split)
+    assert torch.isfinite(yp.float()).all() and torch.isfinite(yd.float()).all()
     yp2, yd2, kv2 = run((nx.CUS_ALL, nx.CUS_ALL))
     assert torch.equal(yp2.view(torch.int16), yp.view(torch.int16))
     assert torch.equal(yd2.view(torch.int16), yd.view(torch.int16))
     for a, b in zip(kv2, kv_after):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
     del yp2, yd2, kv2
-    _check_sampled(oracle, f"cfg{idx}", wl, w, yp, yd, kv_after)
+    stats = _check_sampled(oracle, f"cfg{idx}", wl, w, yp, yd, kv_after, gate=std is None)
+    if std is not None:
+        # the share of outputs outside the bar stays at the level the cache's storage format alone produces on the
+        # same rows, and the path's own arithmetic adds less than that format does
+        floor, own = stats["prefill, bf16 cache storage alone"], stats["prefill, path against the layer with a bf16 cache"]
+        assert floor[0] > 1.0, "the storage format alone was expected to break the elementwise bar on this recipe"
+        assert stats["prefill"][1] < 2.0 * floor[1] + 0.01, stats
+        assert own[2] < floor[2] * 1.5, stats
+        assert stats["decode"][1] < 0.02, stats
 
 
 def test_cfg5_full_depth_80_layers_resident(nx):
@@ -475,7 +518,6 @@ def test_cfg5_full_depth_80_layers_resident(nx):
         ctx.sync()
         outs.append((pb.y.clone(), db.y.clone()))
         del kv
-        ctx._kv_keep = None
     assert torch.isfinite(outs[0][0].float()).all() and torch.isfinite(outs[0][1].float()).all()
     assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16))
     assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
@@ -508,7 +550,7 @@ def test_fused_single_batch_baseline_matches_the_two_phases(nx, oracle, idx):
         assert_close("fused: decode rows", f32(yd), ref["y_d"])
         check_pools("fused", wl, kv_after, ref, expected_touched(wl), before)
     else:
-        _check_sampled(oracle, "fused cfg2", wl, w, yp, yd, kv_after, n_pre=24)
+        _check_sampled(oracle, "fused cfg2", wl, w, yp, yd, kv_after)
     ctx.close()
 
 
@@ -546,7 +588,7 @@ def test_fused_step_with_both_attention_kernels(nx, oracle, idx):
         assert_close("fused step: decode rows", f32(yd), ref["y_d"])
         check_pools("fused step", wl, kv_after, ref, expected_touched(wl), before)
     else:
-        _check_sampled(oracle, "fused step cfg2", wl, w, yp, yd, kv_after, n_pre=24)
+        _check_sampled(oracle, "fused step cfg2", wl, w, yp, yd, kv_after)
     y2, kv2, _ = run((160, 96))
     assert torch.equal(y2.view(torch.int16), y.view(torch.int16))
     for a, b in zip(kv2, kv_after):

@@ -1,0 +1,180 @@
+"""The partition itself (Sec. 5 "SM Partitioning", Sec. 3.2: the split is spatial, not temporal): the two streams
+of a layout really run on disjoint compute units, every XCD serves both phases, and the two phases of a mixed step
+really overlap in time."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_06608_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nx():
+    from paper_2507_06608_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _cu_sets(ctx, nx, blocks=1 << 16):
+    """Hardware (XCD, shader engine, CU) ids on which probe workgroups of each phase's stream ran."""
+    out = []
+    for phase in (nx.PHASE_PREFILL, nx.PHASE_DECODE):
+        counts = ctx.cu_probe(phase, blocks)              # [xcd][se][cu]
+        assert counts.sum() == blocks
+        out.append({tuple(int(v) for v in idx) for idx in np.argwhere(counts > 0)})
+    return out
+
+
+@pytest.mark.parametrize("split", [(192, 64), (96, 160), (224, 32), (128, 64)], ids=lambda s: f"{s[0]}_{s[1]}")
+def test_phase_streams_run_on_disjoint_cu_sets_of_the_requested_sizes(nx, split):
+    print(f"[case] CU probe at split {split}", flush=True)
+    wl = synth.config(1)
+    ctx = nx.context_for(wl)
+    assert ctx.cu_count == 256
+    ctx.set_cu_split(*split)
+    pre, dec = _cu_sets(ctx, nx)
+    assert len(pre) == split[0], f"prefill stream ran on {len(pre)} CUs, asked for {split[0]}"
+    assert len(dec) == split[1], f"decode stream ran on {len(dec)} CUs, asked for {split[1]}"
+    assert not (pre & dec), f"{len(pre & dec)} CUs served both phases"
+    for name, cus, want in (("prefill", pre, split[0] // 8), ("decode", dec, split[1] // 8)):
+        per_xcd = [sum(1 for c in cus if c[0] == x) for x in range(8)]
+        assert per_xcd == [want] * 8, f"{name}: CUs per XCD {per_xcd}, expected {want} in each"
+    # and the unpartitioned layout reaches every CU of the chip from either phase
+    ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
+    both = _cu_sets(ctx, nx)
+    assert len(both[0]) == 256 and both[0] == both[1]
+    ctx.close()
+
+
+def test_the_two_phases_of_a_mixed_step_overlap_in_time(nx):
+    """Phases timed alone on their shares against the concurrent step on the same layout (medians of 5): a step that
+    ran the phases one after the other would take the sum."""
+    print("[case] overlap of the phases, 8B-shaped 512 over 1536 + 64 decodes", flush=True)
+    wl = synth.config(2, seed=0, kv_device="cuda:0")
+    ctx = nx.context_for(wl)
+    ctx.load_layer(0, synth.make_weights(wl.shape, 0))
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+    prof = ctx.profile_split(pb, db, kv, [160, 192], nx.POLICY_MIN_STEP, repeats=5)
+    for i, p_cus in enumerate(prof["cand_prefill_cus"]):
+        tp, td, ts = prof["t_prefill_ms"][i], prof["t_decode_ms"][i], prof["t_step_ms"][i]
+        print(f"[overlap] {p_cus}/{256 - p_cus}: prefill alone {tp:.3f} ms, decode alone {td:.3f} ms, together {ts:.3f} ms "
+              f"({ts / (tp + td):.2f} of the sum)", flush=True)
+        assert ts < 0.9 * (tp + td), (p_cus, tp, td, ts)
+        assert ts > 0.8 * max(tp, td)      # and nothing is lost: the step is at least as long as its longer phase
+    ctx.close()
+
+
+def test_layouts_are_created_once_and_switched_without_waiting(nx):
+    """Sec. 5 / Sec. 4.2: the layouts of every split in steps of 32 CUs are created ahead of use and stay alive;
+    selecting one afterwards is a host-side pointer switch (printed; asserted far below the ~10 ms a stream pair takes
+    to create) that neither waits for the step in flight nor changes a bit of any result."""
+    import time
+    print("[case] pre-created layouts, switching between steps without synchronising", flush=True)
+    wl = synth.config(2, seed=0, kv_device="cuda:0")
+    ctx = nx.context_for(wl)
+    ctx.load_layer(0, synth.make_weights(wl.shape, 0))
+    splits = [(32 * k, 256 - 32 * k) for k in range(1, 8)]
+    t0 = time.perf_counter()
+    ctx.prepare_cu_splits(splits)
+    print(f"[layouts] creating 7 stream pairs: {(time.perf_counter() - t0) * 1e3:.1f} ms", flush=True)
+    pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+
+    # reference: every step on its own, synchronised, on the unpartitioned layout
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
+    ctx.mixed_step(pb, db, kv)
+    ctx.sync()
+    ref = (pb.y.clone(), db.y.clone())
+    ref_kv = ctx.kv_export(kv)
+
+    # a chain of steps, each on another layout, with no synchronisation in between: every step rewrites the same
+    # outputs and cache slots from the same inputs, so any overlap of two steps on the shared workspace would show
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    pb.y.zero_(), db.y.zero_()
+    torch.cuda.synchronize()
+    order = [(192, 64), (64, 192), (nx.CUS_ALL, nx.CUS_ALL), (224, 32), (96, 160), (160, 96), (nx.CUS_ALL, nx.CUS_ALL), (128, 128), (32, 224)]
+    switch_us = []
+    for rep in range(3):
+        for sp in order:
+            t0 = time.perf_counter()
+            ctx.set_cu_split(*sp)
+            switch_us.append((time.perf_counter() - t0) * 1e6)
+            ctx.mixed_step(pb, db, kv)
+    ctx.sync()
+    assert torch.equal(pb.y.view(torch.int16), ref[0].view(torch.int16))
+    assert torch.equal(db.y.view(torch.int16), ref[1].view(torch.int16))
+    for a, b in zip(ctx.kv_export(kv), ref_kv):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    print(f"[layouts] nexus_set_cu_split with work in flight: median {np.median(switch_us):.1f} us, max {max(switch_us):.1f} us "
+          f"over {len(switch_us)} switches", flush=True)
+    assert np.median(switch_us) < 50.0 and max(switch_us) < 2000.0
+
+    # single-phase calls across a switch: the decode step launched on the new layout follows the one still running on
+    # the old layout's stream (same workspace), again without a sync
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    for sp in order[:5]:
+        ctx.set_cu_split(*sp)
+        ctx.decode_step(db, kv)
+        ctx.prefill_chunk(pb, kv)
+    ctx.sync()
+    assert torch.equal(pb.y.view(torch.int16), ref[0].view(torch.int16))
+    assert torch.equal(db.y.view(torch.int16), ref[1].view(torch.int16))
+    assert ctx.phase_done(nx.PHASE_PREFILL) and ctx.phase_done(nx.PHASE_DECODE)
+    ctx.close()
+
+
+def test_debug_mode_rejects_bad_device_side_indices_before_launching(nx):
+    print("[case] debug checks on device-side arrays", flush=True)
+    wl = synth.make_workload("dbg", synth.SHAPES["tiny"], 3, chunk_lens=[37, 50], prefix_lens=[0, 47], decode_ctx=[15, 16, 300], page_slack=2)
+    ctx = nx.context_for(wl)
+    ctx.load_layer(0, synth.make_weights(wl.shape, 3))
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+    ctx.set_debug_checks(True)
+    ctx.set_cu_split(128, 128)
+    ctx.mixed_step(pb, db, kv)                       # a valid step passes
+    ctx.sync()
+    good = (pb.y.clone(), db.y.clone(), ctx.kv_export(kv))
+    before = ctx.kv_export(kv)
+
+    # page id outside the pool in the decode table
+    saved = db.pt.clone()
+    db.pt[2, 5] = wl.n_pages + 3
+    torch.cuda.synchronize()
+    with pytest.raises(nx.NexusError, match="outside the pool"):
+        ctx.mixed_step(pb, db, kv)
+    with pytest.raises(nx.NexusError, match="outside the pool"):
+        ctx.decode_step(db, kv)
+    db.pt.copy_(saved)
+    # two requests appending into the same page
+    saved = pb.pt.clone()
+    pb.pt[1, 3] = db.pt[1, 1]
+    torch.cuda.synchronize()
+    with pytest.raises(nx.NexusError, match="written by"):
+        ctx.mixed_step(pb, db, kv)
+    pb.pt.copy_(saved)
+    # negative context length
+    saved = db.ctx.clone()
+    db.ctx[0] = -4
+    torch.cuda.synchronize()
+    with pytest.raises(nx.NexusError, match="negative ctx_len"):
+        ctx.decode_step(db, kv)
+    db.ctx.copy_(saved)
+    torch.cuda.synchronize()
+    ctx.sync()
+    # nothing was launched by the refused calls: the cache is as the valid step left it
+    for a, b in zip(ctx.kv_export(kv), before):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    # and the context still works, with the checks on and off
+    ctx.mixed_step(pb, db, kv)
+    ctx.sync()
+    assert torch.equal(pb.y.view(torch.int16), good[0].view(torch.int16)) and torch.equal(db.y.view(torch.int16), good[1].view(torch.int16))
+    ctx.set_debug_checks(False)
+    ctx.mixed_step(pb, db, kv)
+    ctx.sync()
+    assert torch.equal(db.y.view(torch.int16), good[1].view(torch.int16))
+    ctx.close()
