@@ -223,6 +223,23 @@ int nexus_decode_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexu
                       const nexus_kv_cache *kv);
 
 /*
+ * nexus_decode_step for callers that cannot allocate device memory or let a library do so: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results; the phase's workspace (activations, split-K partial sums, attention span partials) is laid out in a
+ * static device array of the library instead of the context's own buffers, so the call performs no hipMalloc /
+ * hipFree and calls no allocating routine; a small clear kernel (no memset node) zeroes what must start at zero.
+ * The array is 32 MiB per GPU, exists from library load to process exit and is shared by every context on that
+ * GPU: calls that overlap in time on one GPU race on it (calls of one context are ordered by the decode stream).
+ * A step whose workspace does not fit fails with NEXUS_ESHAPE before anything is launched: the need grows with
+ * n_reqs x (the split-K partial sums of the widest split projection + the attention partials of max_ctx / 256
+ * spans); a hidden-4096 GQA layer takes about 23 MB for 64 requests with contexts up to 4096 and does not fit
+ * 256 requests with contexts up to 8192.
+ * nexus_debug_fetch does not see this call's buffers.
+ */
+int nexus_decode_step_noalloc(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus_decode_batch *db,
+                              const nexus_kv_cache *kv);
+
+/*
  * The step of an engine WITHOUT phase separation (Sec. 2.4, the chunked-prefill engines the paper measures
  * against), for comparison: one batch in which the last n_decode_reqs requests are decode requests written as
  * one-token chunks (chunk length 1, prefix_len = context length, x = the new token's input).  Every projection and

@@ -36,7 +36,7 @@ EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "n
            "nexus_sched_create", "nexus_sched_destroy", "nexus_sched_submit", "nexus_sched_next", "nexus_sched_commit",
            "nexus_sched_request", "nexus_sched_summarize", "nexus_sched_samples", "nexus_sched_next_phase",
            "nexus_sched_commit_phase", "nexus_phase_query", "nexus_phase_wait", "nexus_fused_step",
-           "nexus_prepare_cu_splits", "nexus_set_debug_checks", "nexus_validate_batches")
+           "nexus_prepare_cu_splits", "nexus_set_debug_checks", "nexus_validate_batches", "nexus_decode_step_noalloc")
 
 
 class NexusError(RuntimeError):
@@ -280,6 +280,9 @@ class Nexus:
 
     def decode_step(self, db: DevDecode, kv: KVCache, layers=(0, 1)):
         _check(lib().nexus_decode_step(self._ctx, layers[0], layers[1], C.byref(db.c), C.byref(kv)))
+
+    def decode_step_noalloc(self, db: DevDecode, kv: KVCache, layers=(0, 1)):
+        _check(lib().nexus_decode_step_noalloc(self._ctx, layers[0], layers[1], C.byref(db.c), C.byref(kv)))
 
     def fused_step(self, batch: DevPrefill, n_decode_reqs: int, max_decode_ctx: int, kv: KVCache, layers=(0, 1)):
         """One batch, the last n_decode_reqs requests being decode requests written as one-token chunks."""

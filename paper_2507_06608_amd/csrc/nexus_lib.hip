@@ -34,6 +34,34 @@ using namespace nexus;
         if (s_ != NEXUS_OK) return s_; \
     } while (0)
 
+// ---------------------------------------------------------------------------------------------- static scratch
+// Workspace of nexus_decode_step_noalloc: device memory that exists from the moment the library is loaded, so the
+// call allocates nothing.  One copy per GPU, shared by every context on that GPU, held until the process ends.  In
+// host code the array's name is only a handle: its device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+// `device` must be current.
+static int scratch_address(int device, unsigned char **out) {
+    if (device < 0 || device >= kMaxDevices) return fail(NEXUS_EINVAL, "device %d outside [0, %d)", device, kMaxDevices);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(NEXUS_EHIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", device, hipGetErrorString(e));
+        g_scratch_ptr[device] = (unsigned char *)p;
+    }
+    *out = g_scratch_ptr[device];
+    return NEXUS_OK;
+}
+
+// Clears a byte range (a multiple of 16 bytes, 16-byte aligned) with a kernel: usable where a memset node is not.
+__global__ __launch_bounds__(256) void scratch_clear_kernel(uint4 *p, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) p[i] = uint4{0u, 0u, 0u, 0u};
+}
+
 // ---------------------------------------------------------------------------------------------- context
 struct LayerW {
     bf16_t *g1 = nullptr, *g2 = nullptr, *bqkv = nullptr;
@@ -102,6 +130,7 @@ struct nexus_ctx {
     std::vector<TraceRec> trace_pool;
     size_t trace_used = 0;
     int32_t *probe_counts = nullptr;
+    unsigned char *scratch_dev = nullptr;  // this GPU's copy of the static scratch array
 };
 
 struct DeviceGuard {
@@ -789,6 +818,7 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         const int half = m.head_dim / 2;
         if ((rc = dev_alloc(&c->rope_tab, (size_t)limits->max_positions * half, false))) break;
         if ((rc = dev_alloc(&c->probe_counts, 8 * 128, true))) break;
+        if ((rc = scratch_address(device, &c->scratch_dev))) break;
         const size_t n = (size_t)limits->max_positions * half;
         hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->s_main, c->rope_tab, limits->max_positions, half,
                            (double)m.rope_theta);
@@ -1006,6 +1036,75 @@ int nexus_decode_step(nexus_ctx *c, int lb, int le, const nexus_decode_batch *db
     DeviceGuard dg(c->device);
     NX_TRY(debug_validate(c, nullptr, db, kv));
     return run_single_phase(c, make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le);
+}
+
+// Lays the decode phase's workspace for T requests with contexts of at most max_ctx positions out over `base`
+// (256-byte aligned pieces).  Returns the bytes needed; *zero_bytes is the leading part that must be cleared before
+// use (tile-ordered operands whose padding the GEMMs read, and everything a previous call of another shape may have
+// left behind).  With base == nullptr it only measures.
+static size_t carve_decode_ws(const nexus_ctx *c, int T, int max_ctx, bool multi_layer, unsigned char *base, PhaseWs *w, size_t *zero_bytes) {
+    const nexus_model_desc &m = c->m;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        unsigned char *p = base ? base + off : nullptr;
+        off += (bytes + 255) & ~(size_t)255;
+        return p;
+    };
+    const int Tp = round_up(T, 32);
+    PhaseWs ws{};
+    ws.maxT = T;
+    ws.h = (f16_t *)take(p32_elems(Tp, m.hidden) * 2);
+    ws.attn = (f16_t *)take(p32_elems(Tp, c->q_dim) * 2);
+    ws.act = (f16_t *)take(p32_elems(Tp, m.ffn) * 2);
+    ws.qkv = (f16_t *)take((size_t)T * c->n_qkv * 2);
+    ws.q = (bf16_t *)take((size_t)T * c->q_dim * 2);
+    ws.x1 = (float *)take((size_t)T * m.hidden * 4);
+    if (multi_layer) {
+        ws.xbuf[0] = (bf16_t *)take((size_t)T * m.hidden * 2);
+        ws.xbuf[1] = (bf16_t *)take((size_t)T * m.hidden * 2);
+    }
+    *zero_bytes = off;
+    ws.max_spans = (max_ctx + kSpan - 1) / kSpan;
+    const size_t items = (size_t)T * m.n_q_heads * ws.max_spans;  // (request, kv head, span) x the G heads of the kv head
+    ws.part_o = (float *)take(items * m.head_dim * 2);  // half elements
+    ws.part_ml = (float *)take(items * 2 * 4);
+    size_t pe = 0;
+    const int shapes[4][2] = {{c->n_qkv, m.hidden}, {m.hidden, c->q_dim}, {2 * m.ffn, m.hidden}, {m.hidden, m.ffn}};
+    for (auto &sh : shapes) {
+        const GemmPlan p = plan_gemm(T, sh[0] / 32, p32_kp(sh[1]));
+        if (p.S > 1) pe = std::max(pe, (size_t)p.S * T * sh[0]);
+    }
+    ws.partial_elems = pe;
+    ws.partial = (float *)take(pe * 4);
+    if (w) *w = ws;
+    return off;
+}
+
+int nexus_decode_step_noalloc(nexus_ctx *c, int lb, int le, const nexus_decode_batch *db, const nexus_kv_cache *kv) {
+    NX_TRY(check_layers(c, lb, le));
+    NX_TRY(check_kv(c, kv, le));
+    NX_TRY(check_decode(c, db));
+    PhaseWs ws;
+    size_t zero_bytes = 0;
+    const size_t need = carve_decode_ws(c, db->n_reqs, db->max_ctx, le - lb > 1, nullptr, nullptr, &zero_bytes);
+    if (need > kScratchBytes)
+        return fail(NEXUS_ESHAPE, "a decode step of %d requests with contexts up to %d needs %zu bytes of workspace, the static scratch array holds %zu",
+                    db->n_reqs, db->max_ctx, need, kScratchBytes);
+    DeviceGuard dg(c->device);
+    NX_TRY(debug_validate(c, nullptr, db, kv));
+    unsigned char *base = nullptr;
+    NX_TRY(scratch_address(c->device, &base));
+    carve_decode_ws(c, db->n_reqs, db->max_ctx, le - lb > 1, base, &ws, &zero_bytes);
+    PhaseRun r = make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv);
+    r.ws = &ws;  // only read while the launches below are enqueued
+    NX_TRY(order_after(c, r.s, NEXUS_PHASE_DECODE));
+    HIP_TRY(hipEventRecord(c->ev_ph0[NEXUS_PHASE_DECODE], r.s));
+    const size_t n16 = zero_bytes / 16;  // every piece is a multiple of 256 bytes
+    hipLaunchKernelGGL(scratch_clear_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, r.s, (uint4 *)base, n16);
+    HIP_TRY(hipGetLastError());
+    NX_TRY(run_phase(r, lb, le));
+    NX_TRY(mark_done(c, r.s, NEXUS_PHASE_DECODE, true));
+    return NEXUS_OK;
 }
 
 int nexus_fused_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *batch, int32_t n_decode_reqs, int32_t max_decode_ctx,
