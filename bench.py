@@ -1,13 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the partitioned prefill/decode step on one MI355X.
 
-A "step" is one pass of the whole hot path over one batch: a chunked-prefill sub-batch and a decode sub-batch of
-one decoder layer, run concurrently on disjoint CU partitions (or back to back for the serialized baseline).
-Default workload: the Llama-3-8B-shaped layer with a 512-token chunk over a 1536-token prefix and 64 decode
-requests with contexts uniform in [512, 4096] (seeded, synthetic, resident in HBM before the timed region).
+A "step" is one pass of the whole hot path over one batch: a chunked-prefill sub-batch and a decode sub-batch through
+every layer of the stack, run concurrently on disjoint CU partitions (or back to back for the serialized baseline).
+
+Headline workload (the largest single-GPU configuration): the Llama-3-70B-shaped stack at full depth, 80 layers
+resident (~137 GB of packed weights drawn on the device + ~55 GB of KV), a 2048-token chunk over a 2048-token prefix
+next to 64 decode requests with contexts uniform in [1024, 4096]; seeded, synthetic, resident in HBM before the timed
+region.  The 8B-shaped single-layer configurations (512-token chunk + 64 decodes; 4 x 2048-token chunks + 256 decodes)
+ride along as `secondary` objects of the same JSON line.
 
 Prints ONE JSON line: mixed-step tokens/s at the chosen CU split, the sweep over splits with decode-step latency,
-the serialized baseline, the roofline of the dominant kernels and the CPU oracle timed on a bounded sample.
+the serialized baseline, the roofline of the dominant kernel and the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -21,16 +25,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_MFMA_TFLOPS = 2500.0   # MI355X dense fp16 / bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# what actually runs: storage and arithmetic types of the path
+DTYPE = "bf16 storage (x, y, KV cache, queries); fp16 GEMM operands; bf16 attention MFMA; fp32 accumulate"
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_work(wl):
-    """Flops / bytes the method itself must do per launch of each kernel family (one layer)."""
+def algorithmic_work(wl, layers):
+    """Flops / bytes the method itself must do per launch of each kernel family (one layer), and per step."""
     s = wl.shape
     p, d = wl.prefill, wl.decode
     T, B = p.n_tokens, d.n_reqs
@@ -43,7 +49,6 @@ def algorithmic_work(wl):
         "gemm_down": 2.0 * T * s.hidden * s.ffn,
         "attn_prefill": 4.0 * s.head_dim * s.n_q_heads * pairs,
     }
-    prefill_flops = sum(w.values())
     decode_kv_bytes = float(sum(int(c) + 1 for c in d.ctx_len)) * kv_tok_bytes
     weight_bytes = 2.0 * s.params_per_layer
     decode_bytes = {
@@ -54,32 +59,33 @@ def algorithmic_work(wl):
     # operand bytes of the prefill kernels (weights once + activations in + result out), for the traffic ratio only
     prefill_bytes = {
         "gemm_qkv": 2.0 * s.n_qkv * s.hidden + 2.0 * T * (s.hidden + s.n_qkv),
+        "gemm_o": 2.0 * s.hidden * s.q_dim + 2.0 * T * s.q_dim + 4.0 * T * s.hidden,
         "gemm_gate_up": 2.0 * 2 * s.ffn * s.hidden + 2.0 * T * (s.hidden + s.ffn),
+        "gemm_down": 2.0 * s.hidden * s.ffn + 2.0 * T * (s.ffn + s.hidden),
         "attn_prefill": float(sum(int(n) + int(pre) for n, pre in zip(p.chunk_len, p.prefix_len))) * kv_tok_bytes
                         + 2.0 * 2 * T * s.q_dim,
     }
-    return {"prefill_flops": w, "prefill_total_flops": prefill_flops, "decode_bytes": decode_bytes, "prefill_bytes": prefill_bytes,
-            "decode_total_bytes": decode_kv_bytes + weight_bytes, "weight_bytes": weight_bytes,
-            "tokens": T + B}
+    return {"prefill_flops": w, "prefill_layer_flops": sum(w.values()), "decode_bytes": decode_bytes, "prefill_bytes": prefill_bytes,
+            "decode_layer_bytes": decode_kv_bytes + weight_bytes, "tokens": T + B, "layers": layers}
 
 
-def cpu_baseline(wl, weights, n_prefill_tokens=512, n_decode=64, reps=2):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload (for the benchmark
-    configuration: its whole first chunk and up to 64 decode requests, `reps` passes, about 10 s of CPU work)."""
+def cpu_baseline(wl, weights, layers, n_prefill_tokens, n_decode, reps):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload: the first tokens of the
+    first chunk (they see the whole cached prefix) and the first decode requests, ONE layer; the rate is then divided
+    by the number of layers of the stack, which the oracle would run one after the other."""
     import numpy as np
 
     import oracle
     from paper_2507_06608_amd import synth
     p = wl.prefill
     sub = synth.subset_for_oracle(wl, [0], list(range(min(n_decode, wl.decode.n_reqs))))
-    # first n tokens of the chunk (they see the whole cached prefix); decode requests in batch order
     n = min(n_prefill_tokens, int(p.chunk_len[0]))
     sp = sub.prefill
     sp = synth.PrefillBatch(sp.x[:n], np.array([0, n], np.int32), sp.prefix_len[:1], sp.page_table[:1])
     m = oracle.Model(hidden=wl.shape.hidden, n_q_heads=wl.shape.n_q_heads, n_kv_heads=wl.shape.n_kv_heads,
                      head_dim=wl.shape.head_dim, ffn=wl.shape.ffn, page_size=wl.shape.page_size,
                      rms_eps=wl.shape.rms_eps, rope_theta=wl.shape.rope_theta)
-    ow = {k: v.float().numpy() for k, v in weights.items()}
+    ow = {k: v.float().cpu().numpy() for k, v in weights.items()}
     kp, vp = sub.k_pool.float().numpy().copy(), sub.v_pool.float().numpy().copy()
     oracle.lib()
     t0 = time.perf_counter()
@@ -88,50 +94,78 @@ def cpu_baseline(wl, weights, n_prefill_tokens=512, n_decode=64, reps=2):
         oracle.layer_decode(m, ow, sub.decode.x.float().numpy(), sub.decode.ctx_len, sub.decode.page_table, kp, vp)
     dt = time.perf_counter() - t0
     toks = reps * (n + sub.decode.n_reqs)
-    return {"value": toks / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+    return {"value": toks / dt / layers, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{n} of {p.n_tokens} prefill tokens (over the full {int(p.prefix_len[0])}-token prefix) + "
-                      f"{sub.decode.n_reqs} of {wl.decode.n_reqs} decode requests, one layer, {reps} passes, {dt:.1f} s"}
+                      f"{sub.decode.n_reqs} of {wl.decode.n_reqs} decode requests through ONE layer, {reps} pass(es), {dt:.1f} s of "
+                      f"CPU work; tokens/s of that layer divided by the {layers} layers of the stack"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2)
-    ap.add_argument("--split", default="auto", help="'auto' (profile and choose) or PREFILL_CUS/DECODE_CUS")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-sweep", action="store_true")
-    ap.add_argument("--no-trace", action="store_true", help="skip the trace-driven serving legs (48-layer 14B-shaped stack)")
-    ap.add_argument("--no-fused", action="store_true", help="skip the naive fused single-batch step (keeps a kernel trace to the two phases)")
-    ap.add_argument("--calib-copy", action="store_true",
-                    help="also run a plain 1 GiB device copy (known traffic) to calibrate rocprofv3 byte counters")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (the partitioned step is an intra-GPU method); --gpus must be 1")
+def device_layer_weights(shape, layer, std):
+    """One layer's bf16 weights drawn on the GPU (a host copy of the 70B-shaped stack's 137 GB is avoided)."""
+    import torch
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(1000 + layer)
 
+    def mat(r, c):
+        return (torch.randn((r, c), generator=g, device="cuda:0") * std).to(torch.bfloat16)
+
+    def gain():
+        return (1.0 + torch.randn(shape.hidden, generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
+    return {"attn_norm_g": gain(), "w_qkv": mat(shape.n_qkv, shape.hidden), "w_o": mat(shape.hidden, shape.q_dim),
+            "ffn_norm_g": gain(), "w_gate_up": mat(2 * shape.ffn, shape.hidden), "w_down": mat(shape.hidden, shape.ffn)}
+
+
+def load_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summaries (scaled by a copy of known
+    size; see the files): bench.py cannot run the profiler on itself, so it reports what those runs measured."""
+    traffic = {}
+    prof_dir = os.path.join(ROOT, "profiles")
+    if os.path.isdir(prof_dir):
+        for fn in sorted(os.listdir(prof_dir)):
+            if fn.startswith("hbm_traffic_"):
+                for line in open(os.path.join(prof_dir, fn)):
+                    f = line.split()
+                    if len(f) == 4 and f[0] == "traffic_bytes_per_launch" and f[1] == name:
+                        traffic[f[2]] = {"bytes_per_launch": float(f[3]), "source": "profiles/" + fn}
+    return traffic
+
+
+def measure(idx, layers, steps, warmup, args, headline):
+    """One configuration: serialized baseline, sweep of the split, timed steps at the chosen split, rooflines."""
     import numpy as np
     import torch
 
     from paper_2507_06608_amd import binding, synth
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     t0 = time.time()
-    wl = synth.config(args.config, seed=0, kv_device=dev)
-    weights = synth.make_weights(wl.shape, 0)
-    log(f"[bench] workload {wl.name}: inputs generated in {time.time() - t0:.1f} s")
-    ctx = binding.context_for(wl)
-    ctx.load_layer(0, weights)
-    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    wl = synth.config(idx, seed=0, kv_device=dev)
+    s = wl.shape
+    ctx = binding.context_for(wl, n_layers=layers)
+    if layers == 1:
+        first = synth.make_weights(s, 0)
+        ctx.load_layer(0, first)
+    else:
+        first = None
+        for l in range(layers):
+            w = device_layer_weights(s, l, synth.weight_std(s))
+            if l == 0:
+                first = {k: v.clone() for k, v in w.items()}
+            ctx.load_layer(l, w)
+            del w
+            if l % 20 == 19:
+                log(f"[bench] {wl.name}: {l + 1} of {layers} layers packed")
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool, layers=layers)
     pb, db = binding.DevPrefill(wl.prefill, ctx.device), binding.DevDecode(wl.decode, ctx.device)
-    work = algorithmic_work(wl)
+    work = algorithmic_work(wl, layers)
     n_cus = ctx.cu_count
+    L = (0, layers)
+    log(f"[bench] workload {wl.name} x {layers} layer(s): resident after {time.time() - t0:.1f} s")
     # No caller stream: the inputs are resident and complete before the loop starts, and the library itself orders
     # each step after both phases of the previous one, so steps do not overlap each other.
 
     def run_steps(n):
         for _ in range(n):
-            ctx.mixed_step(pb, db, kv)
+            ctx.mixed_step(pb, db, kv, layers=L)
 
     def timed(n):
         torch.cuda.synchronize()
@@ -140,180 +174,203 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / n * 1e3
 
+    # ---- serialized baseline (one unmasked stream, prefill then decode)
+    ctx.set_cu_split(binding.CUS_ALL, binding.CUS_ALL)
+    run_steps(warmup)
+    serial_ms = timed(max(3, steps // 4))
+    tm = [ctx.mixed_step(pb, db, kv, layers=L, timing=True) for _ in range(3)][-1]
+    serial = {"ms_per_step": serial_ms, "tokens_per_s": work["tokens"] / serial_ms * 1e3,
+              "t_prefill_ms": tm.t_prefill_ms, "decode_latency_ms": tm.t_decode_ms}
+    log(f"[bench] {wl.name} serialized: {serial}")
+
+    # ---- the engine without phase separation (the chunked-prefill engines the paper measures against): ONE batch,
+    # every projection once over all rows (weights read once), chunk rows through the chunked-prefill attention,
+    # decode rows through the decode attention; all CUs, one stream.  Single-layer configurations only: the fused
+    # batch needs a context (and a packed weight copy) of its own.
+    fused_res = None
+    if layers == 1 and not args.no_fused:
+        fused = synth.fused_single_batch(wl)
+        fctx = binding.Nexus(s, max_prefill_tokens=fused.n_tokens, max_prefill_reqs=fused.n_reqs,
+                             max_decode_reqs=wl.decode.n_reqs, max_positions=int((fused.prefix_len + fused.chunk_len).max()), n_layers=1)
+        fctx.load_layer(0, first)
+        fb = binding.DevPrefill(fused, fctx.device)
+        max_ctx = int(wl.decode.ctx_len.max()) + 1
+        for _ in range(warmup):
+            fctx.fused_step(fb, wl.decode.n_reqs, max_ctx, kv)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        n_f = max(3, steps // 4)
+        for _ in range(n_f):
+            fctx.fused_step(fb, wl.decode.n_reqs, max_ctx, kv)
+        torch.cuda.synchronize()
+        fused_ms = (time.perf_counter() - t) / n_f * 1e3
+        fused_res = {"ms_per_step": fused_ms, "tokens_per_s": work["tokens"] / fused_ms * 1e3, "decode_latency_ms": fused_ms}
+        log(f"[bench] {wl.name} fused single batch: {fused_res}")
+        fctx.close()
+        del fb, fctx
+
+    # ---- sweep of the CU split (steps of 32 CUs: shares in between leave a shader engine of every XCD a CU short and
+    # run at the speed of the next lower multiple of 32)
+    sweep, alone = [], {}
+    if args.split == "auto":
+        cands = [c for c in range(32, n_cus, 32)]
+        prof = ctx.profile_split(pb, db, kv, cands, binding.POLICY_MIN_STEP, repeats=5 if layers == 1 else 3, layers=L)
+        for i, c in enumerate(cands):
+            sweep.append({"prefill_cus": c, "decode_cus": n_cus - c, "t_prefill_alone_ms": prof["t_prefill_ms"][i],
+                          "t_decode_alone_ms": prof["t_decode_ms"][i], "t_step_ms": prof["t_step_ms"][i],
+                          "tokens_per_s": work["tokens"] / prof["t_step_ms"][i] * 1e3})
+        chosen = prof["chosen_prefill_cus"]
+        alone = {"t_prefill_all_cus_ms": prof["t_prefill_all_ms"], "t_decode_all_cus_ms": prof["t_decode_all_ms"]}
+        # the paper's two objectives on the same measured curves, for the record
+        for name, pol in (("prefill_prioritized", binding.POLICY_PREFILL_PRIORITIZED),
+                          ("decode_prioritized", binding.POLICY_DECODE_PRIORITIZED)):
+            i = binding.choose_split(prof["t_prefill_ms"], prof["t_decode_ms"], prof["t_step_ms"],
+                                     prof["t_prefill_all_ms"], prof["t_decode_all_ms"], pol, 1.3, 1.1)
+            alone[name + "_prefill_cus"] = cands[i]
+        log(f"[bench] {wl.name} sweep: {json.dumps(sweep)}")
+        log(f"[bench] {wl.name} alone on all CUs: {alone}; chosen prefill CUs (min step): {chosen}")
+    else:
+        a, b = (int(v) for v in args.split.split("/"))
+        if a + b > n_cus:
+            sys.exit(f"bench.py: split {a}/{b} exceeds the device's {n_cus} CUs")
+        chosen = a
+    d_cus = n_cus - chosen if args.split == "auto" else int(args.split.split("/")[1])
+    ctx.set_cu_split(chosen, d_cus)
+
+    # ---- kernel times at this split (short traced passes), to find the dominant kernel of the step
+    run_steps(max(1, warmup // 2))
+    kt = {}
+    traced = (("prefill", binding.PHASE_PREFILL, ("gemm_qkv", "attn_prefill", "gemm_o", "gemm_gate_up", "gemm_down")),
+              ("decode", binding.PHASE_DECODE, ("gemm_qkv", "attn_decode", "gemm_o", "gemm_gate_up", "gemm_down")))
+    n_tr = 3 if layers == 1 else 1
+    for pname, phase, names in traced:
+        for k in names:
+            ctx.trace_begin(phase, k)
+            run_steps(n_tr)
+            ms, n = ctx.trace_read()
+            kt[(pname, k)] = (ms, n / float(n_tr))
+    log(f"[bench] {wl.name} kernel times at {chosen}/{d_cus} (ms per launch, launches per step): " +
+        json.dumps({f"{a}.{b}": (round(v[0], 4), v[1]) for (a, b), v in kt.items()}))
+    dom = max(kt, key=lambda k: kt[k][0] * kt[k][1])     # most time per step
+
+    # ---- timed region: exactly `steps` steps, the dominant kernel bracketed by HIP events on its own stream
+    ctx.trace_begin(binding.PHASE_PREFILL if dom[0] == "prefill" else binding.PHASE_DECODE, dom[1])
+    ms_per_step = timed(steps)
+    dom_ms, dom_n = ctx.trace_read()
+    tms = [ctx.mixed_step(pb, db, kv, layers=L, timing=True) for _ in range(5 if layers == 1 else 3)]
+    dec_lat = float(np.median([t.t_decode_ms for t in tms]))
+    pre_lat = float(np.median([t.t_prefill_ms for t in tms]))
+
+    traffic = load_traffic(wl.name)
+
+    def roof(phase, k, ms):
+        if phase == "prefill":
+            fl = work["prefill_flops"][k]
+            ach = fl / (ms * 1e-3) / 1e12
+            r = {"kernel": f"{phase}.{k}", "bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS,
+                 "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_TFLOPS, "traffic": None, "ms_per_launch": ms,
+                 "flops_per_launch": fl, "cus": chosen, "frac_of_cu_share": ach / (PEAK_MFMA_TFLOPS * chosen / n_cus)}
+        else:
+            by = work["decode_bytes"][k]
+            ach = by / (ms * 1e-3) / 1e9
+            r = {"kernel": f"{phase}.{k}", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                 "frac": ach / PEAK_HBM_GBS, "traffic": None, "ms_per_launch": ms, "bytes_per_launch": by, "cus": d_cus}
+        t = traffic.get(f"{phase}.{k}")
+        if t:
+            r["traffic"] = t["bytes_per_launch"]
+            r["traffic_source"] = t["source"]
+            alg = work["decode_bytes"][k] if phase == "decode" else work["prefill_bytes"].get(k)
+            if alg:
+                r["traffic_over_operand_bytes"] = t["bytes_per_launch"] / alg
+        return r
+
+    roofline = roof(dom[0], dom[1], dom_ms)
+    roofline["launches_timed"] = dom_n
+    others = {f"{a}.{b}": roof(a, b, kt[(a, b)][0]) for (a, b) in (("prefill", "gemm_gate_up"), ("prefill", "attn_prefill"),
+                                                                   ("decode", "attn_decode"), ("decode", "gemm_gate_up")) if (a, b) != dom}
+    pf, dbytes = work["prefill_layer_flops"] * layers, work["decode_layer_bytes"] * layers
+    phase_roof = {
+        "prefill_phase_tflops": pf / (pre_lat * 1e-3) / 1e12,
+        "prefill_phase_frac_of_mfma_peak": pf / (pre_lat * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
+        "decode_phase_gbs": dbytes / (dec_lat * 1e-3) / 1e9,
+        "decode_phase_frac_of_hbm_peak": dbytes / (dec_lat * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
+    if alone:
+        phase_roof["prefill_alone_all_cus_frac_of_mfma_peak"] = pf / (alone["t_prefill_all_cus_ms"] * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS
+        phase_roof["decode_alone_all_cus_frac_of_hbm_peak"] = dbytes / (alone["t_decode_all_cus_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS
+    res = {
+        "value": work["tokens"] / ms_per_step * 1e3, "ms_per_step": ms_per_step, "steps": steps,
+        "config": {"workload": wl.name, "layers": layers, "prefill_tokens": wl.prefill.n_tokens,
+                   "decode_requests": wl.decode.n_reqs, "cu_split": f"{chosen}/{d_cus}",
+                   "split_policy": "min measured concurrent step time over the sweep of 32-CU steps" if args.split == "auto" else "given"},
+        "decode_step_latency_ms": dec_lat, "prefill_phase_latency_ms": pre_lat,
+        "serialized": serial, "speedup_vs_serialized": serial_ms / ms_per_step,
+        "fused_single_batch": fused_res, "speedup_vs_fused_single_batch": (fused_res["ms_per_step"] / ms_per_step) if fused_res else None,
+        "alone": alone, "sweep": sweep, "roofline": roofline, "roofline_other": others, "phase_roofline": phase_roof,
+    }
+    if headline and not args.no_cpu_baseline:
+        big = s.hidden >= 8192
+        res["cpu_baseline"] = cpu_baseline(wl, first, layers, 160 if big else 512, 32 if big else 64, 1 if big else 2)
+    ctx.close()
+    del ctx, kv, pb, db, wl
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps of the headline workload (default 20 at full depth, 200 for one layer)")
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=5, help="headline configuration (1..5)")
+    ap.add_argument("--layers", type=int, default=0, help="layers of the headline stack (0 = the configuration's own depth)")
+    ap.add_argument("--split", default="auto", help="'auto' (profile and choose) or PREFILL_CUS/DECODE_CUS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the 8B-shaped single-layer configurations")
+    ap.add_argument("--no-fused", action="store_true", help="skip the fused single-batch step of the single-layer configurations")
+    ap.add_argument("--trace", action="store_true", help="also run the trace-driven serving legs (48-layer 14B-shaped stack, about a minute)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) to calibrate rocprofv3 byte counters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the partitioned step is an intra-GPU method); --gpus must be 1")
+
+    import torch
+
+    from paper_2507_06608_amd import synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.config not in (1, 2, 3, 4, 5):
+        sys.exit("bench.py: --config must be 1..5")
+    depth = args.layers or {1: 1, 2: 1, 3: 1, 4: synth.SHAPES["qwen25_14b"].n_layers, 5: synth.SHAPES["llama3_70b"].n_layers}[args.config]
+    steps = args.steps if args.steps is not None else (20 if depth > 8 else 200)
+    warmup = args.warmup if args.warmup is not None else (3 if depth > 8 else 20)
+
     if args.calib_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- serialized baseline (one unmasked stream, prefill then decode)
-    ctx.set_cu_split(binding.CUS_ALL, binding.CUS_ALL)
-    run_steps(args.warmup)
-    serial_ms = timed(max(10, args.steps // 4))
-    tm = [ctx.mixed_step(pb, db, kv, timing=True) for _ in range(5)][-1]
-    serial = {"ms_per_step": serial_ms, "tokens_per_s": work["tokens"] / serial_ms * 1e3,
-              "t_prefill_ms": tm.t_prefill_ms, "decode_latency_ms": tm.t_decode_ms}
-    log(f"[bench] serialized: {serial}")
-
-    # ---- the engine without phase separation (the chunked-prefill engines the paper measures against): ONE batch,
-    # every projection once over all rows (weights read once), chunk rows through the chunked-prefill attention,
-    # decode rows through the decode attention; all CUs, one stream.  "naive" sends the decode rows through the
-    # chunked-prefill attention kernel as one-token chunks instead (31 of its 32 query rows idle).
-    fused_res = naive_res = None
-    if not args.no_fused:
-        fused = synth.fused_single_batch(wl)
-        fctx = binding.Nexus(wl.shape, max_prefill_tokens=fused.n_tokens, max_prefill_reqs=fused.n_reqs,
-                             max_decode_reqs=wl.decode.n_reqs, max_positions=int((fused.prefix_len + fused.chunk_len).max()), n_layers=1)
-        fctx.load_layer(0, weights)
-        fb = binding.DevPrefill(fused, fctx.device)
-        max_ctx = int(wl.decode.ctx_len.max()) + 1
-
-        def time_it(fn):
-            for _ in range(args.warmup):
-                fn()
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            n_f = max(10, args.steps // 4)
-            for _ in range(n_f):
-                fn()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t) / n_f * 1e3
-        fused_ms = time_it(lambda: fctx.fused_step(fb, wl.decode.n_reqs, max_ctx, kv))
-        naive_ms = time_it(lambda: fctx.prefill_chunk(fb, kv))
-        fused_res = {"ms_per_step": fused_ms, "tokens_per_s": work["tokens"] / fused_ms * 1e3, "decode_latency_ms": fused_ms}
-        naive_res = {"ms_per_step": naive_ms, "tokens_per_s": work["tokens"] / naive_ms * 1e3, "decode_latency_ms": naive_ms}
-        log(f"[bench] fused single batch: {fused_res}; naive: {naive_res}")
-        fctx.close()
-        del fb, fctx
-
-    # ---- sweep of the CU split
-    sweep = []
-    chosen = None
-    if args.split == "auto":
-        cands = [c for c in range(32, n_cus, 32)]
-        if not args.no_sweep:
-            prof = ctx.profile_split(pb, db, kv, cands, binding.POLICY_MIN_STEP, repeats=7)
-            for i, c in enumerate(cands):
-                sweep.append({"prefill_cus": c, "decode_cus": n_cus - c, "t_prefill_alone_ms": prof["t_prefill_ms"][i],
-                              "t_decode_alone_ms": prof["t_decode_ms"][i], "t_step_ms": prof["t_step_ms"][i],
-                              "tokens_per_s": work["tokens"] / prof["t_step_ms"][i] * 1e3})
-            # (steps of 32 CUs: shares in between leave a shader engine of every XCD a CU short and run at the speed
-            # of the next lower multiple of 32)
-            chosen = prof["chosen_prefill_cus"]
-            alone = {"t_prefill_all_cus_ms": prof["t_prefill_all_ms"], "t_decode_all_cus_ms": prof["t_decode_all_ms"]}
-            # the paper's two objectives on the same measured curves, for the record
-            for name, pol in (("prefill_prioritized", binding.POLICY_PREFILL_PRIORITIZED),
-                              ("decode_prioritized", binding.POLICY_DECODE_PRIORITIZED)):
-                i = binding.choose_split(prof["t_prefill_ms"], prof["t_decode_ms"], prof["t_step_ms"],
-                                         prof["t_prefill_all_ms"], prof["t_decode_all_ms"], pol, 1.3, 1.1)
-                alone[name + "_prefill_cus"] = cands[i]
-            log(f"[bench] sweep: {json.dumps(sweep)}")
-            log(f"[bench] alone on all CUs: {alone}; chosen prefill CUs (min step): {chosen}")
-        else:
-            chosen, alone = n_cus // 2, {}
-    else:
-        a, b = args.split.split("/")
-        chosen, alone = int(a), {}
-        assert int(a) + int(b) == n_cus or True
-    ctx.set_cu_split(chosen, n_cus - chosen)
-
-    # ---- find the dominant kernel of each phase at this split (short traced passes)
-    run_steps(args.warmup)
-    kt = {}
-    for phase, names in ((binding.PHASE_PREFILL, ("gemm_qkv", "attn_prefill", "gemm_o", "gemm_gate_up", "gemm_down",
-                                                   "rmsnorm", "rope_append", "splitk_reduce")),
-                         (binding.PHASE_DECODE, ("gemm_qkv", "attn_decode", "attn_merge", "gemm_o", "gemm_gate_up",
-                                                 "gemm_down", "rmsnorm", "rope_append", "splitk_reduce"))):
-        for k in names:
-            ctx.trace_begin(phase, k)
-            run_steps(5)
-            ms, n = ctx.trace_read()
-            kt[("prefill" if phase == 0 else "decode", k)] = (ms, n / 5.0)
-    log("[bench] kernel times at the chosen split (ms per launch, launches per step): " +
-        json.dumps({f"{a}.{b}": (round(v[0], 4), v[1]) for (a, b), v in kt.items()}))
-    dom = max((k for k in kt if k[1] in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down", "attn_prefill", "attn_decode")),
-              key=lambda k: kt[k][0])
-
-    # ---- timed region: exactly K steps, dominant kernel bracketed by HIP events on its own stream
-    ctx.trace_begin(binding.PHASE_PREFILL if dom[0] == "prefill" else binding.PHASE_DECODE, dom[1])
-    ms_per_step = timed(args.steps)
-    dom_ms, dom_n = ctx.trace_read()
-    tms = [ctx.mixed_step(pb, db, kv, timing=True) for _ in range(9)]
-    dec_lat = float(np.median([t.t_decode_ms for t in tms]))
-    pre_lat = float(np.median([t.t_prefill_ms for t in tms]))
-
-    # HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summaries (scaled by a copy of known
-    # size; see the files): bench.py cannot run the profiler on itself, so it reports what those runs measured.
-    traffic = {}
-    prof_dir = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles")
-    if os.path.isdir(prof_dir):
-        for fn in sorted(os.listdir(prof_dir)):
-            if fn.startswith("hbm_traffic_"):
-                for line in open(os.path.join(prof_dir, fn)):
-                    f = line.split()
-                    if len(f) == 4 and f[0] == "traffic_bytes_per_launch" and f[1] == wl.name:
-                        traffic[f[2]] = {"bytes_per_launch": float(f[3]), "source": "profiles/" + fn}
-
-    def roof(phase, k, ms):
-        r = roof_(phase, k, ms)
-        t = traffic.get(f"{phase}.{k}")
-        if t:
-            r["traffic"] = t["bytes_per_launch"]
-            r["traffic_source"] = t["source"]
-            r["traffic_over_algorithmic"] = t["bytes_per_launch"] / (work["decode_bytes"][k] if phase == "decode" else work["prefill_bytes"].get(k, float("nan")))
-        return r
-
-    def roof_(phase, k, ms):
-        if phase == "prefill":
-            fl = work["prefill_flops"][k]
-            ach = fl / (ms * 1e-3) / 1e12
-            return {"kernel": f"{phase}.{k}", "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "ms_per_launch": ms,
-                    "cus": chosen, "frac_of_cu_share": ach / (PEAK_BF16_TFLOPS * chosen / n_cus)}
-        by = work["decode_bytes"][k]
-        ach = by / (ms * 1e-3) / 1e9
-        # besides the published peak: what this many CUs can read at all (about 50 GB/s per CU on this chip, measured
-        # with a plain streaming kernel; the whole chip saturates near 5.7-6.0 TB/s for 4 KiB blocks)
-        share_ceiling = min(50.0 * (n_cus - chosen), 5850.0)
-        return {"kernel": f"{phase}.{k}", "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None, "ms_per_launch": ms, "cus": n_cus - chosen,
-                "measured_read_ceiling_of_these_cus": share_ceiling, "frac_of_that_ceiling": ach / share_ceiling}
-
-    roofline = roof(dom[0], dom[1], dom_ms)
-    # the other side of the target: best prefill GEMM against MFMA peak, decode attention against HBM peak
-    others = {}
-    for key in (("prefill", "gemm_gate_up"), ("decode", "attn_decode"), ("decode", "gemm_gate_up")):
-        if key != dom and key in kt:
-            others[f"{key[0]}.{key[1]}"] = roof(key[0], key[1], kt[key][0])
-    phase_roof = {
-        "prefill_phase_tflops": work["prefill_total_flops"] / (pre_lat * 1e-3) / 1e12,
-        "prefill_phase_frac_of_mfma_peak": work["prefill_total_flops"] / (pre_lat * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "decode_phase_gbs": work["decode_total_bytes"] / (dec_lat * 1e-3) / 1e9,
-        "decode_phase_frac_of_hbm_peak": work["decode_total_bytes"] / (dec_lat * 1e-3) / 1e9 / PEAK_HBM_GBS,
-    }
-
+    head = measure(args.config, depth, steps, warmup, args, headline=True)
     out = {
         "metric": "mixed-step tokens/s + decode-step latency vs CU split; MFMA %, HBM GB/s",
-        "value": work["tokens"] / ms_per_step * 1e3, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "layers": 1, "prefill_tokens": wl.prefill.n_tokens,
-                   "decode_requests": wl.decode.n_reqs, "cu_split": f"{chosen}/{n_cus - chosen}",
-                   "split_policy": "min measured concurrent step time over the sweep of 32-CU steps"},
-        "decode_step_latency_ms": dec_lat, "prefill_phase_latency_ms": pre_lat,
-        "serialized": serial, "speedup_vs_serialized": serial_ms / ms_per_step,
-        "fused_single_batch": fused_res, "speedup_vs_fused_single_batch": (fused_res["ms_per_step"] / ms_per_step) if fused_res else None,
-        "fused_single_batch_naive": naive_res,
-        "alone": alone, "sweep": sweep, "roofline": roofline, "roofline_other": others, "phase_roofline": phase_roof,
+        "value": head.pop("value"), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": DTYPE, "data": "synthetic",
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, weights)
-    ctx.close()
-    del ctx, kv, pb, db
-    if not args.no_trace:
-        torch.cuda.empty_cache()
+    head.pop("steps")
+    out.update(head)
+    if not args.no_secondary:
+        out["secondary"] = {}
+        for idx in (2, 3):
+            if idx == args.config and depth == 1:
+                continue
+            r = measure(idx, 1, 100 if idx == 2 else 30, 10 if idx == 2 else 5, args, headline=False)
+            r["tokens_per_s"] = r.pop("value")
+            out["secondary"][r["config"]["workload"]] = r
+    if args.trace:
         try:
             out["serving_trace"] = serving_trace(log)
         except Exception as e:  # the headline above does not depend on this leg
@@ -334,19 +391,9 @@ def serving_trace(log):
     rate, horizon = 12.0, 3.0
     trace = synth.poisson_trace(1, rate=rate, horizon_s=horizon, output_cap=384)
     arrivals = [a for a, _, _ in trace]
-    g = torch.Generator(device="cuda:0")
 
     def weights(l):
-        g.manual_seed(1000 + l)
-        std = synth.weight_std(shape)
-
-        def mat(r, c):
-            return (torch.randn((r, c), generator=g, device="cuda:0") * std).to(torch.bfloat16)
-
-        def gain():
-            return (1.0 + torch.randn(shape.hidden, generator=g, device="cuda:0") * 0.02).to(torch.bfloat16)
-        return {"attn_norm_g": gain(), "w_qkv": mat(shape.n_qkv, shape.hidden), "w_o": mat(shape.hidden, shape.q_dim),
-                "ffn_norm_g": gain(), "w_gate_up": mat(2 * shape.ffn, shape.hidden), "w_down": mat(shape.hidden, shape.ffn)}
+        return device_layer_weights(shape, l, synth.weight_std(shape))
 
     common = dict(policy=binding.PREFILL_SPF, token_budget=1024, max_decode_reqs=128, n_pages=12288, gamma=15.0,
                   max_prefill_reqs=8, seed=2)

@@ -63,7 +63,10 @@ typedef struct {
  * rounding (half holds every bf16 weight of magnitude >= 2^-14 exactly); accumulators, softmax and norm
  * statistics and the residual stream between attention and feed-forward are fp32 (where the keys of a request are
  * split over several workgroups, each part's output is normalised by its own softmax sum and held in half until the
- * parts are merged in fp32).  Activations feeding a GEMM must stay inside half's range (|v| < 65504).
+ * parts are merged in fp32).  RANGE: values fed to a GEMM as half operands must stay below 65504 in magnitude; a
+ * model with larger normalised activations, attention outputs or SwiGLU products (bf16 would hold them) overflows
+ * to infinity there and the layer output turns non-finite: a loud failure, never a finite wrong number.  The layer
+ * input / output and the residual stream are bf16 / fp32 and keep bf16's range.
  */
 
 /* Upper bounds that size the context's workspace; step calls beyond them fail with NEXUS_ESHAPE. */

@@ -21,6 +21,8 @@ using namespace nexus;
 
 extern "C" {
 
+const char *nexus_last_error(void) { return g_err; }
+
 // The selection rule; kept free of HIP so that the host tests can drive it with synthetic curves.
 int nexus_choose_split(int n, const float *t_p, const float *t_d, const float *t_step, float t_p_all, float t_d_all, int policy, float alpha,
                        float beta) {

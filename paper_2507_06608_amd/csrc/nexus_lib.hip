@@ -213,11 +213,11 @@ static GemmPlan plan_gemm(int T, int n_ftiles, int Kp) {
     return p;
 }
 
-template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI, bool ASM_READS = true>
+template <int FS, int TS, int WF, int WT, int BKT, int NST, int EPI, bool ASM_READS = true, int NWL = 0, bool BUF_LOADS = false>
 static hipError_t launch_gemm_t(const GemmArgs &a, dim3 grid, hipStream_t s) {
     constexpr int smem = NST * (FS + TS) * BKT * 1024;
     static bool attr_done = false;  // one context thread at a time (see header)
-    auto kern = gemm_dl_kernel<FS, TS, WF, WT, BKT, NST, EPI, ASM_READS>;
+    auto kern = gemm_dl_kernel<FS, TS, WF, WT, BKT, NST, EPI, ASM_READS, NWL, BUF_LOADS>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
@@ -247,7 +247,10 @@ template <int EPI>
 static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipStream_t s) {
     switch (variant) {
         case GV_P128: return launch_gemm_t<4, 4, 2, 2, 2, 4, EPI>(a, grid, s);
-        case GV_P256: return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI>(a, grid, s);
+        case GV_P256:  // buffer loads address an operand matrix with 32-bit offsets
+            if ((size_t)a.n_ftiles * a.Kp * 64 < ((size_t)1 << 32) && (size_t)a.n_ttiles * a.Kp * 64 < ((size_t)1 << 32))
+                return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI, true, 4, true>(a, grid, s);
+            return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI, true, 4, false>(a, grid, s);
         case GV_S64: return launch_gemm_stream_t<1, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S32: return launch_gemm_stream_t<1, 1, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S64W: return launch_gemm_stream_t<2, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
@@ -687,8 +690,6 @@ static void destroy_layout(Layout &L) {
 
 // ---------------------------------------------------------------------------------------------- C ABI
 extern "C" {
-
-const char *nexus_last_error(void) { return g_err; }
 
 int nexus_debug_token_order(int b, int n) {
     if (n <= 0 || b < 0 || b >= n) return fail(NEXUS_EINVAL, "token order: index %d outside [0, %d)", b, n);

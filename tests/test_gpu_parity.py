@@ -277,6 +277,37 @@ def test_argument_errors_launch_nothing(nx):
     ctx.close()
 
 
+def test_large_activations_inside_and_outside_the_range_of_half_operands(nx, oracle):
+    """The GEMM operands (normalised activations, attention output, SwiGLU activation) are IEEE half: up to 65504 they
+    carry three more mantissa bits than bf16, beyond it they overflow.  A layer whose feed-forward gain drives the
+    SwiGLU activation to ~2e4 must still match the oracle; one that drives it past 65504 must fail LOUDLY (non-finite
+    outputs), never with finite wrong numbers."""
+    _announce("large activations")
+    sh = synth.SHAPES["tiny"]
+    wl = synth.make_workload("big act", sh, 13, chunk_lens=[64], prefix_lens=[32], decode_ctx=[50, 20, 129])
+    for gain, in_range in ((80.0, True), (500.0, False)):
+        w = synth.make_weights(sh, 13)
+        w["ffn_norm_g"] = (w["ffn_norm_g"].float() * gain).to(torch.bfloat16)
+        ref = run_oracle(oracle, wl, w, debug=True)
+        g = _gpu_run(nx, wl, w, "mixed", split=(128, 128))
+        act = f32(g["ctx"].debug_fetch(nx.PHASE_PREFILL, nx.BUF_ACT, wl.prefill.n_tokens))
+        if in_range:
+            assert 5e3 < np.abs(act).max() < 65504.0, np.abs(act).max()
+            # the layer output has an rms of several hundred here, so the bar's absolute term (0.02) is meaningless:
+            # the comparison is relative to the output's own scale
+            for name, got, want in (("y_prefill", f32(g["y_p"]), ref["y_p"]), ("y_decode", f32(g["y_d"]), ref["y_d"])):
+                assert np.isfinite(got).all()
+                rel = np.linalg.norm(got - want) / np.linalg.norm(want)
+                worst = np.abs(got - want).max() / np.sqrt((want.astype(np.float64) ** 2).mean())
+                print(f"[parity] {name}, largest activation {np.abs(act).max():.0f}, output rms {np.sqrt((want ** 2).mean()):.0f}: "
+                      f"rel L2 {rel:.2e}, worst error {worst:.2e} of the output rms", flush=True)
+                assert rel <= 1e-2 and worst <= 2e-2
+        else:
+            assert not np.isfinite(act).all(), "activations past 65504 were expected to overflow the half operand"
+            assert not torch.isfinite(g["y_p"].float()).all(), "an overflowed operand must surface as non-finite output"
+        g["ctx"].close()
+
+
 def test_cfg2_full_size_every_output_in_bench_launch_configuration(nx, oracle):
     """The 8B-shaped 512-over-1536 + 64-decode workload at full size, run the way bench.py runs it (mixed step on a
     partitioned layout, KV generated on the device), with EVERY output compared with the oracle: all 512 chunk rows
