@@ -255,6 +255,19 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
                                              (__attribute__((address_space(3))) void *)(dst + i * (NWL * 1024)), 16, 0, 0);
     };
 
+    auto issue_unit = [&](int ks, int i) {  // unit i of this wavefront's share of step ks (i is a constant after unrolling)
+        char *dst = smem + (ks % NST) * STAGE + w * 1024 + i * (NWL * 1024);
+#if defined(__HIP_DEVICE_COMPILE__)
+        if constexpr (BUF_LOADS) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(uis_w[i] ? rsrc_w : rsrc_x, (__attribute__((address_space(3))) void *)dst, 16, (int)lane_off,
+                                                     (int)(uoff[i] + (unsigned)ks * (BKT * 1024)), 0, 0);
+            return;
+        }
+#endif
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ub[i] + (size_t)ks * (BKT * 1024) + lane_off),
+                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    };
+
     f32x16 acc[FW][TW];
 #pragma unroll
     for (int i = 0; i < FW; ++i)
@@ -340,6 +353,104 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[c][i], fb_[c][j], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);  // later waits and barriers stay behind these MFMAs
     };
+    // ---- interleaved pipeline (stages of two k-tiles, hand-issued LDS reads) ----------------------------------------
+    // Nothing is issued in bursts: inside the group of MFMAs of one k-tile, the LDS read of one operand fragment of the
+    // NEXT k-tile follows each of the first FW + TW MFMAs, and a loading wavefront also drops its global->LDS loads
+    // between the MFMAs, evenly spaced -- the first half of a step's loads in the group behind the barrier that frees
+    // their ring slot, the second half in the group after it.  Measured on MI355X against issuing the FW + TW reads
+    // ahead of the group and all loads right behind the barrier (256 x 256 tiles, K = 4096): 1.29 -> 1.41 PFLOP/s at
+    // 8192 tokens, 1.04 -> 1.23 at 512: with every wavefront of the workgroup released by the same barrier, bursts of
+    // LDS and vector-memory instructions queue up in front of the MFMAs of the wavefronts that issued them.
+    // The operands of a group are waited for with lgkmcnt(0) right behind the group that issued their reads; the last of
+    // them was issued two MFMAs (and the other wavefront's share of the SIMD) before.  The loop is cut into regions so
+    // that "this group carries loads" is a compile-time property and each region's body is straight-line code; a
+    // wavefront that loads nothing runs the same regions without loads.
+    if constexpr (BKT == 2 && ASM_READS && FW + TW <= FW * TW) {
+        auto group = [&](auto cur_tag, int ks_next, auto kt_tag, auto l0_tag, auto l1_tag, int ks_load) {
+            constexpr int CUR = decltype(cur_tag)::value, NXT = 1 - CUR, KT = decltype(kt_tag)::value, M = FW * TW, R = FW + TW;
+            constexpr int L0 = decltype(l0_tag)::value, NL = decltype(l1_tag)::value - L0;
+            const unsigned so = (ks_next % NST) * STAGE;
+            const unsigned bw = lds_w + so, bx = lds_x + so;
+            auto step = [&](auto self, auto m_tag) {
+                constexpr int MI = decltype(m_tag)::value;
+                acc[MI / TW][MI % TW] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[CUR][MI / TW], fb_[CUR][MI % TW], acc[MI / TW][MI % TW], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);  // the order written here is the order issued
+                if constexpr (KT >= 0 && MI < R) {
+                    if constexpr (MI < FW) lds_read_frag<(MI * BKT + (KT >= 0 ? KT : 0)) * 1024>(fa[NXT][MI], bw);
+                    else lds_read_frag<((MI - FW) * BKT + (KT >= 0 ? KT : 0)) * 1024>(fb_[NXT][MI - FW], bx);
+                }
+                if constexpr (NL > 0)
+                    if constexpr (((MI + 1) * NL) / M != (MI * NL) / M) issue_unit(ks_load, L0 + (MI * NL) / M);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (MI + 1 < M) self(self, std::integral_constant<int, MI + 1>{});
+            };
+            step(step, std::integral_constant<int, 0>{});
+        };
+        auto landed = [&](int buf) {  // every LDS read issued so far has returned; ties the registers to the wait
+            wait_lgkmcnt<0>();
+#pragma unroll
+            for (int i = 0; i < FW; ++i) asm volatile("" : "+v"(fa[buf][i]));
+#pragma unroll
+            for (int j = 0; j < TW; ++j) asm volatile("" : "+v"(fb_[buf][j]));
+        };
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using NoRead = std::integral_constant<int, -1>;
+        using LHalf = std::integral_constant<int, (LPW + 1) / 2>;
+        using LAll = std::integral_constant<int, LPW>;
+        const int n_load_steps = nsteps - (NST - 1);  // steps whose barrier also frees the slot of a step still to be loaded
+        // LA: the first group issues the second half of the loads that the previous stage's barrier released;
+        // LB: the group behind this stage's barrier issues the first half of the loads of step ks + NST - 1.
+        auto stage2 = [&](int ks, auto has_next, auto la_tag, auto lb_tag) {
+            constexpr bool LA = decltype(la_tag)::value, LB = decltype(lb_tag)::value;
+            if constexpr (LA) group(I0{}, ks, I1{}, LHalf{}, LAll{}, ks - 1 + NST - 1);
+            else group(I0{}, ks, I1{}, I0{}, I0{}, 0);
+            landed(1);
+            if constexpr (decltype(has_next)::value) {
+                // own loads of step ks + 1 landed: at most those of the NST - 3 newer steps stay in flight
+                if constexpr (LB) {
+                    wait_vmcnt<(NST >= 4 ? NST - 3 : 0) * LPW>();
+                } else {
+                    const int later = nsteps - 2 - ks;
+                    if (NST >= 4 && later >= NST - 3) wait_vmcnt<(NST >= 4 ? NST - 3 : 0) * LPW>();
+                    else wait_vmcnt<0>();
+                }
+                __builtin_amdgcn_s_barrier();  // step ks + 1 visible to all; every wavefront is done with step ks - 1
+                if constexpr (LB) group(I1{}, ks + 1, I0{}, I0{}, LHalf{}, ks + NST - 1);
+                else group(I1{}, ks + 1, I0{}, I0{}, I0{}, 0);
+                landed(0);  // see below: no hand-issued read is in flight when a stage ends
+            } else {
+                group(I1{}, 0, NoRead{}, I0{}, I0{}, 0);
+            }
+        };
+        auto run = [&](auto loader_tag) {
+            using T_ = std::true_type;
+            using F_ = std::false_type;
+            using L_ = std::integral_constant<bool, decltype(loader_tag)::value>;
+            int ks = 0;
+            if (n_load_steps >= 1) {
+                stage2(0, T_{}, F_{}, L_{});
+                for (ks = 1; ks < n_load_steps; ++ks) stage2(ks, T_{}, L_{}, L_{});
+                stage2(ks, T_{}, L_{}, F_{});  // NST >= 3: a next step exists
+                ++ks;
+            }
+            for (; ks + 1 < nsteps; ++ks) stage2(ks, T_{}, F_{}, F_{});
+            stage2(nsteps - 1, F_{}, F_{}, F_{});
+        };
+        // A hand-issued read is invisible to the compiler: until the wait, it takes the destination registers for
+        // valid and may copy them, which it does wherever two code regions disagree on the register assignment (the
+        // edges between the regions below, a loop's back edge).  So no such read is ever in flight across an edge:
+        // every stage, and the prologue's read of the first k-tile, ends with the wait for what it issued.  Inside a
+        // stage the code between a read and its wait is straight-line.
+        if (nsteps > 0) {
+            landed(0);
+            if (NWL == NW || w < NWL) run(std::true_type{});
+            else run(std::false_type{});
+        }
+        gemm_epilogue<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane);
+        return;
+    }
+    // ---- generic pipeline (four k-tiles per stage, or compiler-visible LDS reads) ----------------------------------------
     // One stage of MFMAs.  HAS_NEXT is a compile-time flag so that the steady-state loop body is straight-line code.
     auto stage = [&](int ks, auto has_next) {
         // k-tiles 0 .. BKT-2: prefetch the next k-tile of this stage, then multiply the current one

@@ -165,6 +165,8 @@ enum GemmVariant {
     GV_P128 = 0,  // gemm_dl_kernel, 128 x 128, 4 waves, 32-wide stages, 64 KiB ring: two workgroups per CU
     GV_P256,      // gemm_dl_kernel, 256 x 256, 8 waves, 128 KiB ring: half the LDS and L2 traffic per flop, for GEMMs
                   //   with several such tiles per CU of the share (same per-element summation order as GV_P128)
+    GV_P256x128,  // gemm_dl_kernel, 256 features x 128 tokens, 4 waves of 4 x 2 MFMA tiles, 96 KiB ring, one workgroup per
+                  //   CU: between the two in traffic per flop, for grids that the 256 x 256 tiles quantise badly
     GV_S64,       // gemm_stream_kernel, 128 features x 64 tokens, 4 waves: decode batches of 33..64
     GV_S32,       // gemm_stream_kernel, 128 features x 32 tokens, 4 waves: decode batches of at most 32
     GV_S64W,      // gemm_stream_kernel, 256 features x 64 tokens (two feature strips per wave): on a small CU share
@@ -251,6 +253,7 @@ static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipSt
             if ((size_t)a.n_ftiles * a.Kp * 64 < ((size_t)1 << 32) && (size_t)a.n_ttiles * a.Kp * 64 < ((size_t)1 << 32))
                 return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI, true, 4, true>(a, grid, s);
             return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI, true, 4, false>(a, grid, s);
+        case GV_P256x128: return launch_gemm_t<8, 4, 2, 2, 2, 4, EPI>(a, grid, s);
         case GV_S64: return launch_gemm_stream_t<1, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S32: return launch_gemm_stream_t<1, 1, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S64W: return launch_gemm_stream_t<2, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
@@ -323,17 +326,21 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
     a.out_p32 = out_p32, a.out_Kp = out_p32 ? p32_kp(out_K) : 0;
     a.partial = ws.partial;
     // Ring geometry and tile extent may follow the CU share (they do not change any element's summation order; the
-    // split factor S, which does, is problem-only).  256 x 256 tiles do about 15% more flops per CU-second than
-    // 128 x 128 (half the LDS and L2 traffic per flop) but quantise worse: one per CU against two.  Measured at
-    // K = 4096 on MI355X: a round of 256-tiles takes 132 us, a round of 128-tiles (two per CU) 75 us; the estimate
-    // below reproduced the measured times of all four projection GEMMs at 512 and 8192 tokens within 5%.
+    // split factor S, which does, is problem-only).  Larger tiles move fewer operand bytes through LDS per flop but
+    // quantise worse on a given number of CUs.  The choice minimises (rounds of the grid on this share) x (cost of one
+    // round), the costs being the measured time of one round at K = 4096 on MI355X in microseconds (they scale with
+    // K alike): 256 x 256 tiles, one per CU, 97 (1.41 PFLOP/s on the whole chip); 256 x 128 tiles, one per CU, 56
+    // (1.23); 128 x 128 tiles, two per CU, 60 (1.15).  Ties go to the larger tile.
     int variant = p.variant, FS = p.FS, TS = p.TS;
     if (variant == GV_P128 && p.S == 1 && c->allow_p256) {
         const long n128 = (long)((a.n_ttiles + 3) / 4) * ((n_ftiles + 3) / 4);
         const long n256 = (long)((a.n_ttiles + 7) / 8) * ((n_ftiles + 7) / 8);
-        const long est128 = (n128 + 2 * r.cus - 1) / (2 * r.cus) * 75;
-        const long est256 = (n256 + r.cus - 1) / r.cus * 132;
-        if (est256 < est128) variant = GV_P256, FS = 8, TS = 8;
+        const long n256x128 = (long)((a.n_ttiles + 3) / 4) * ((n_ftiles + 7) / 8);
+        const long est128 = (n128 + 2 * r.cus - 1) / (2 * r.cus) * 60;
+        const long est256 = (n256 + r.cus - 1) / r.cus * 97;
+        const long est256x128 = (n256x128 + r.cus - 1) / r.cus * 56;
+        if (est256 <= est128 && est256 <= est256x128) variant = GV_P256, FS = 8, TS = 8;
+        else if (est256x128 <= est128) variant = GV_P256x128, FS = 8, TS = 4;
     }
     // Measured on 64 of the 256 CUs (T = 64): gate/up 113 -> 98 us, down 55 -> 48, O 21.6 -> 18.9 with the wide
     // variant, QKV (too few workgroups left) 27 -> 30; on 96 CUs and more the narrow one wins or ties.
