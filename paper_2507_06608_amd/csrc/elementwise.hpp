@@ -9,14 +9,34 @@ namespace nexus {
 // Input row-major [T][d]: bf16 (the layer input), fp32 (the residual stream after attention), or -- fused with the
 // end of a split-K output projection -- the S fp32 partial slices of that GEMM plus the bf16 residual, in which
 // case the kernel also writes the residual stream x1 = residual + sum of slices (slices added in order, then the
-// residual, exactly as splitk_reduce_kernel does).  Output half, in P32 tile order (operand of the next GEMM).
-enum RmsIn { RMS_IN_BF16 = 0, RMS_IN_F32 = 1, RMS_IN_PARTIAL = 2 };
+// residual, exactly as splitk_reduce_kernel does).  A fourth input is the end of the previous layer's split-K down
+// projection: its S slices plus the fp32 residual x1; the kernel writes the layer output y = bf16(x1 + sum), which
+// is this layer's input, and normalises the rounded y -- the same values the reduce kernel followed by the bf16
+// norm would produce.  Output half, in P32 tile order (operand of the next GEMM).
+enum RmsIn { RMS_IN_BF16 = 0, RMS_IN_F32 = 1, RMS_IN_PARTIAL = 2, RMS_IN_PARTIAL_Y = 3 };
 struct RmsPartial {
     const float *partial;  // [S][T][d]
     int S, T;
-    const bf16_t *res;     // [T][d]
-    float *x1_out;         // [T][d]
+    const bf16_t *res;     // [T][d]   (RMS_IN_PARTIAL)
+    float *x1_out;         // [T][d]   (RMS_IN_PARTIAL)
+    const float *res_f32;  // [T][d]   (RMS_IN_PARTIAL_Y)
+    bf16_t *y_out;         // [T][d]   (RMS_IN_PARTIAL_Y)
 };
+// slices summed in order, then the fp32 residual, rounded to bf16 and stored; v receives the rounded values
+__device__ __forceinline__ void sum_partial_y8(const RmsPartial &pp, int t, int d, int ci, float (&v)[8]) {
+    sum_slices8(pp.partial + (size_t)t * d + 8 * ci, (size_t)pp.T * d, pp.S, v);
+    const float4 *rr = (const float4 *)(pp.res_f32 + (size_t)t * d) + 2 * ci;
+    const float4 r0 = rr[0], r1 = rr[1];
+    const uint4 y = make_uint4(pack2(v[0] + r0.x, v[1] + r0.y), pack2(v[2] + r0.z, v[3] + r0.w), pack2(v[4] + r1.x, v[5] + r1.y),
+                               pack2(v[6] + r1.z, v[7] + r1.w));
+    ((uint4 *)(pp.y_out + (size_t)t * d))[ci] = y;
+    const uint32_t wds[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[2 * e] = bf2f(wds[e] & 0xffff);
+        v[2 * e + 1] = bf2f(wds[e] >> 16);
+    }
+}
 template <int MAXC, int IN>  // 8-element chunks per thread, d <= MAXC * 256 * 8
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x, const bf16_t *__restrict__ g,
                                                       f16_t *__restrict__ out_p32, int d, int Kp, float eps, RmsPartial pp) {
@@ -34,6 +54,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x
                 float4 a0 = row[2 * ci], a1 = row[2 * ci + 1];
                 v[c][0] = a0.x, v[c][1] = a0.y, v[c][2] = a0.z, v[c][3] = a0.w;
                 v[c][4] = a1.x, v[c][5] = a1.y, v[c][6] = a1.z, v[c][7] = a1.w;
+            } else if (IN == RMS_IN_PARTIAL_Y) {
+                sum_partial_y8(pp, t, d, ci, v[c]);
             } else if (IN == RMS_IN_PARTIAL) {
                 sum_slices8(pp.partial + (size_t)t * d + 8 * ci, (size_t)pp.T * d, pp.S, v[c]);
                 uint4 u = ((const uint4 *)(pp.res + (size_t)t * d))[ci];
@@ -125,6 +147,14 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
             }
             v[c][0] = a0.x, v[c][1] = a0.y, v[c][2] = a0.z, v[c][3] = a0.w;
             v[c][4] = a1.x, v[c][5] = a1.y, v[c][6] = a1.z, v[c][7] = a1.w;
+        }
+    } else if (IN == RMS_IN_PARTIAL_Y) {
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int ci = lane + c * 64;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
+            if (ci < nchunk) sum_partial_y8(pp, t, d, ci, v[c]);
         }
     } else {
 #pragma unroll

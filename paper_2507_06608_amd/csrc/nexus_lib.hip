@@ -106,6 +106,7 @@ struct nexus_ctx {
     nexus_limits lim{};
     int device = 0, n_cus = 0, n_xcd = 8, cus_per_xcd = 32;
     bool allow_p256 = true;
+    int force_tile = 0;  // test hook: 256 = 256 x 256 tiles wherever the shape allows, 384 = 256 x 128
     int q_dim = 0, kv_dim = 0, n_qkv = 0;
     std::vector<LayerW> layers;
     PhaseWs ws[2];
@@ -327,20 +328,29 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
     a.partial = ws.partial;
     // Ring geometry and tile extent may follow the CU share (they do not change any element's summation order; the
     // split factor S, which does, is problem-only).  Larger tiles move fewer operand bytes through LDS per flop but
-    // quantise worse on a given number of CUs.  The choice minimises (rounds of the grid on this share) x (cost of one
-    // round), the costs being the measured time of one round at K = 4096 on MI355X in microseconds (they scale with
-    // K alike): 256 x 256 tiles, one per CU, 97 (1.41 PFLOP/s on the whole chip); 256 x 128 tiles, one per CU, 56
-    // (1.23); 128 x 128 tiles, two per CU, 60 (1.15).  Ties go to the larger tile.
+    // quantise worse on a given number of CUs.  The choice minimises the sum over the rounds of the grid of the time
+    // of one round, which depends on how many CUs the round keeps busy: the chip is power-limited under dense MFMA
+    // work and clocks higher when fewer CUs run it.  Fits to measurements on MI355X (the four projections of the 8B-
+    // and 70B-shaped layers on 128 ... 256 CUs), microseconds per 4096 elements of K, n = busy CUs: 256 x 256 tiles,
+    // one per CU, 72 + 0.14 max(0, n - 128) + 0.21 max(0, n - 192) plus 30 per launch for the fill and the drain of
+    // its last round; 256 x 128 tiles, one per CU, 55.5 + 0.06 max(0, n - 128); 128 x 128 tiles, two per CU,
+    // 60 + 0.0625 max(0, n - 128), 47 for a last round with at most one tile per CU.  Ties go to the larger tile.
     int variant = p.variant, FS = p.FS, TS = p.TS;
     if (variant == GV_P128 && p.S == 1 && c->allow_p256) {
         const long n128 = (long)((a.n_ttiles + 3) / 4) * ((n_ftiles + 3) / 4);
         const long n256 = (long)((a.n_ttiles + 7) / 8) * ((n_ftiles + 7) / 8);
         const long n256x128 = (long)((a.n_ttiles + 3) / 4) * ((n_ftiles + 7) / 8);
-        const long est128 = (n128 + 2 * r.cus - 1) / (2 * r.cus) * 60;
-        const long est256 = (n256 + r.cus - 1) / r.cus * 97;
-        const long est256x128 = (n256x128 + r.cus - 1) / r.cus * 56;
-        if (est256 <= est128 && est256 <= est256x128) variant = GV_P256, FS = 8, TS = 8;
-        else if (est256x128 <= est128) variant = GV_P256x128, FS = 8, TS = 4;
+        const double kscale = Kp / 4096.0;
+        auto total = [&](long tiles, int per_cu, auto round_us) {
+            const long slots = (long)per_cu * r.cus, rem = tiles % slots;
+            return kscale * ((double)(tiles / slots) * round_us(r.cus) + (rem ? round_us((int)((rem + per_cu - 1) / per_cu)) : 0.0));
+        };
+        const double est256 = 30.0 + total(n256, 1, [](int n) { return 72.0 + 0.14 * std::max(0, n - 128) + 0.21 * std::max(0, n - 192); });
+        const double est256x128 = total(n256x128, 1, [](int n) { return 55.5 + 0.06 * std::max(0, n - 128); });
+        double est128 = total(n128, 2, [](int n) { return 60.0 + 0.0625 * std::max(0, n - 128); });
+        if (n128 % (2L * r.cus) && n128 % (2L * r.cus) <= r.cus) est128 -= kscale * 13.0;  // last round: one tile per CU, 47
+        if (c->force_tile ? c->force_tile == 256 : (est256 <= est128 && est256 <= est256x128)) variant = GV_P256, FS = 8, TS = 8;
+        else if (c->force_tile ? c->force_tile == 384 : est256x128 <= est128) variant = GV_P256x128, FS = 8, TS = 4;
     }
     // Measured on 64 of the 256 CUs (T = 64): gate/up 113 -> 98 us, down 55 -> 48, O 21.6 -> 18.9 with the wide
     // variant, QKV (too few workgroups left) 27 -> 30; on 96 CUs and more the narrow one wins or ties.
@@ -491,7 +501,11 @@ static int launch_attn_decode(const PhaseRun &r, const AttnDecodeArgs &a) {
     return NEXUS_OK;
 }
 
-static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y_out) {
+// down_pending > 0: the previous layer's down projection left that many split-K slices in the workspace and its
+// residual in x1; x_in (that layer's output) is still unwritten and this layer's first norm produces it.
+// defer_down (may be null): when given and this layer's down projection is split along K, its slices are left for
+// the next layer in the same way and *defer_down receives their number, else 0.
+static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y_out, int down_pending, int *defer_down) {
     nexus_ctx *c = r.c;
     const nexus_model_desc &m = c->m;
     PhaseWs &ws = *r.ws;
@@ -500,7 +514,12 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
     bf16_t *k_pool = (bf16_t *)((char *)r.kv->k_pool + (size_t)layer * r.kv->layer_stride_bytes);
     bf16_t *v_pool = (bf16_t *)((char *)r.kv->v_pool + (size_t)layer * r.kv->layer_stride_bytes);
 
-    NX_TRY(run_rmsnorm<RMS_IN_BF16>(r, x_in, L.g1, ws.h));
+    if (down_pending) {
+        RmsPartial pp{ws.partial, down_pending, r.T, nullptr, nullptr, ws.x1, const_cast<bf16_t *>(x_in)};
+        NX_TRY(run_rmsnorm<RMS_IN_PARTIAL_Y>(r, nullptr, L.g1, ws.h, pp));
+    } else {
+        NX_TRY(run_rmsnorm<RMS_IN_BF16>(r, x_in, L.g1, ws.h));
+    }
     int qkv_slices = 0;  // a split-K QKV projection is summed by the rotary kernel
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_QKV, L.wqkv, c->n_qkv, ws.h, m.hidden, EPI_ROWMAJOR, ws.qkv, nullptr, L.bqkv, c->n_qkv,
                     nullptr, 0, &qkv_slices));
@@ -557,7 +576,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_O, L.wo, m.hidden, ws.attn, c->q_dim, EPI_RES_IN, ws.x1, x_in, nullptr, m.hidden,
                     nullptr, 0, &o_slices));
     if (o_slices) {
-        RmsPartial pp{ws.partial, o_slices, r.T, (const bf16_t *)x_in, ws.x1};
+        RmsPartial pp{ws.partial, o_slices, r.T, (const bf16_t *)x_in, ws.x1, nullptr, nullptr};
         NX_TRY(run_rmsnorm<RMS_IN_PARTIAL>(r, nullptr, L.g2, ws.h, pp));
     } else {
         NX_TRY(run_rmsnorm<RMS_IN_F32>(r, ws.x1, L.g2, ws.h));
@@ -565,7 +584,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_GATE_UP, L.wgu, 2 * m.ffn, ws.h, m.hidden, EPI_SWIGLU, nullptr, nullptr, nullptr, 0,
                     ws.act, m.ffn));
     NX_TRY(run_gemm(r, NEXUS_K_GEMM_DOWN, L.wdown, m.hidden, ws.act, m.ffn, EPI_RES_OUT, y_out, ws.x1, nullptr, m.hidden,
-                    nullptr, 0));
+                    nullptr, 0, defer_down));
     return NEXUS_OK;
 }
 
@@ -573,9 +592,13 @@ static int run_phase(const PhaseRun &r, int layer_begin, int layer_end) {
     PhaseWs &ws = *r.ws;
     const bf16_t *x = (const bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->x : r.db->x);
     bf16_t *y_final = (bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->y : r.db->y);
+    int pending = 0;  // split-K slices of the previous layer's down projection, summed by this layer's first norm
     for (int l = layer_begin; l < layer_end; ++l) {
-        bf16_t *y = (l + 1 == layer_end) ? y_final : ws.xbuf[(l - layer_begin) & 1];
-        NX_TRY(run_layer(r, l, x, y));
+        const bool last = l + 1 == layer_end;
+        bf16_t *y = last ? y_final : ws.xbuf[(l - layer_begin) & 1];
+        int next_pending = 0;
+        NX_TRY(run_layer(r, l, x, y, pending, last ? nullptr : &next_pending));
+        pending = next_pending;
         x = y;
     }
     return NEXUS_OK;
@@ -812,9 +835,11 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         c->cus_per_xcd = c->n_cus / c->n_xcd;
         const char *order = getenv("NEXUS_CU_BIT_ORDER");
         c->bits_xcd_major = order && !strcmp(order, "xcd_major");
-        // test hook: the 256 x 256 GEMM tiles can be switched off to compare them bit for bit with the 128 x 128 ones
+        // test hook: one GEMM tile shape for every prefill projection ("128", "256", "256x128"), to compare the shapes
+        // bit for bit and to time them against each other
         const char *tiles = getenv("NEXUS_GEMM_TILES");
         c->allow_p256 = !(tiles && !strcmp(tiles, "128"));
+        c->force_tile = tiles && !strcmp(tiles, "256") ? 256 : tiles && !strcmp(tiles, "256x128") ? 384 : tiles && !strcmp(tiles, "128") ? 128 : 0;
         if (const char *dbg = getenv("NEXUS_DEBUG_CHECKS")) c->debug_checks = atoi(dbg) != 0;
         if (const char *ml = getenv("NEXUS_MAX_LAYOUTS")) c->max_layouts = std::max(1, std::min(64, atoi(ml)));
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }

@@ -242,6 +242,43 @@ def test_two_layers_feed_forward(nx, oracle):
     ctx.close()
 
 
+def test_a_layer_range_equals_its_layers_run_one_call_each(nx):
+    """Inside a range of layers, a split-K down projection is summed by the next layer's first norm instead of a
+    reduce kernel (Sec. 2.3: the decode phase is bound by memory traffic and launches).  A layer run on its own never
+    takes that path, so three layers in one call must reproduce, bit for bit, three calls of one layer each that
+    hand y on as x -- on the 8B-shaped layer, whose decode down projection is split 8 ways and whose prefill one 2."""
+    _announce("layer range vs single layers, cfg2")
+    wl = synth.config(2, seed=3, kv_device="cuda:0")
+    L = 3
+    ws = [synth.make_weights(wl.shape, 3, layer=l) for l in range(L)]
+    ctx = nx.context_for(wl, n_layers=L)
+    for l in range(L):
+        ctx.load_layer(l, ws[l])
+    for split in ((nx.CUS_ALL, nx.CUS_ALL), (160, 96)):
+        ctx.set_cu_split(*split)
+        kv = ctx.make_kv(wl.k_pool, wl.v_pool, layers=L)
+        pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+        ctx.mixed_step(pb, db, kv, layers=(0, L))
+        ctx.sync()
+        yp, yd = pb.y.clone(), db.y.clone()
+        kv_range = [ctx.kv_export(kv, l) for l in range(L)]
+        kv1 = ctx.make_kv(wl.k_pool, wl.v_pool, layers=L)
+        pb1, db1 = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
+        for l in range(L):
+            ctx.mixed_step(pb1, db1, kv1, layers=(l, l + 1))
+            ctx.sync()
+            pb1.x.copy_(pb1.y)
+            db1.x.copy_(db1.y)
+            torch.cuda.synchronize()
+        assert torch.equal(yp.view(torch.int16), pb1.y.view(torch.int16)), f"prefill, split {split}"
+        assert torch.equal(yd.view(torch.int16), db1.y.view(torch.int16)), f"decode, split {split}"
+        for l in range(L):
+            k1, v1 = ctx.kv_export(kv1, l)
+            assert torch.equal(kv_range[l][0].view(torch.int16), k1.view(torch.int16)) and \
+                torch.equal(kv_range[l][1].view(torch.int16), v1.view(torch.int16)), f"KV of layer {l}, split {split}"
+    ctx.close()
+
+
 def test_argument_errors_launch_nothing(nx):
     _announce("argument errors")
     wl = synth.config(1)
