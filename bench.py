@@ -163,9 +163,16 @@ def measure(idx, layers, steps, warmup, args, headline):
     # No caller stream: the inputs are resident and complete before the loop starts, and the library itself orders
     # each step after both phases of the previous one, so steps do not overlap each other.
 
+    hand = [None]    # handover layer of the prefill phase inside the step (None: the split is held to the end of the step)
+
+    def one_step(timing=False):
+        if hand[0] is None:
+            return ctx.mixed_step(pb, db, kv, layers=L, timing=timing)
+        return ctx.mixed_step_handover(pb, db, kv, hand[0], layers=L, timing=timing)
+
     def run_steps(n):
         for _ in range(n):
-            ctx.mixed_step(pb, db, kv, layers=L)
+            one_step()
 
     def timed(n):
         torch.cuda.synchronize()
@@ -227,13 +234,34 @@ def measure(idx, layers, steps, warmup, args, headline):
             i = binding.choose_split(prof["t_prefill_ms"], prof["t_decode_ms"], prof["t_step_ms"],
                                      prof["t_prefill_all_ms"], prof["t_decode_all_ms"], pol, 1.3, 1.1)
             alone[name + "_prefill_cus"] = cands[i]
+        best_ms = min(e["t_step_ms"] for e in sweep)
+        if layers > 1 and not args.no_handover:
+            # Sec. 4.2 inside a step: at each split, hand the decode share back to the prefill phase at the first layer
+            # boundary after the decode step has ended (measured next to the prefill phase), and time that step too
+            for e in sweep:
+                ctx.set_cu_split(e["prefill_cus"], e["decode_cus"])
+                t = ctx.mixed_step(pb, db, kv, layers=L, timing=True)
+                h = min(layers, max(1, int(np.ceil(t.t_decode_ms / (t.t_prefill_ms / layers)))))
+                ts = [ctx.mixed_step_handover(pb, db, kv, h, layers=L, timing=True) for _ in range(3)]
+                e["handover_layer"] = h
+                e["t_step_handover_ms"] = float(np.median([x.t_step_ms for x in ts]))
+                e["decode_latency_handover_ms"] = float(np.median([x.t_decode_ms for x in ts]))
+            # the shortest step wins; among steps within 1 % of it, the one with the shortest decode step
+            t_min = min(best_ms, min(e["t_step_handover_ms"] for e in sweep))
+            near = [e for e in sweep if e["t_step_handover_ms"] <= 1.01 * t_min]
+            if near and t_min < best_ms:
+                e = min(near, key=lambda e: e["decode_latency_handover_ms"])
+                best_ms, chosen, hand[0] = e["t_step_handover_ms"], e["prefill_cus"], e["handover_layer"]
         log(f"[bench] {wl.name} sweep: {json.dumps(sweep)}")
-        log(f"[bench] {wl.name} alone on all CUs: {alone}; chosen prefill CUs (min step): {chosen}")
+        log(f"[bench] {wl.name} alone on all CUs: {alone}; chosen prefill CUs (min step): {chosen}" +
+            (f", decode share handed to prefill at layer {hand[0]}" if hand[0] is not None else ""))
     else:
         a, b = (int(v) for v in args.split.split("/"))
         if a + b > n_cus:
             sys.exit(f"bench.py: split {a}/{b} exceeds the device's {n_cus} CUs")
         chosen = a
+        if args.handover >= 0:
+            hand[0] = min(layers, args.handover)
     d_cus = n_cus - chosen if args.split == "auto" else int(args.split.split("/")[1])
     ctx.set_cu_split(chosen, d_cus)
 
@@ -257,11 +285,20 @@ def measure(idx, layers, steps, warmup, args, headline):
     ctx.trace_begin(binding.PHASE_PREFILL if dom[0] == "prefill" else binding.PHASE_DECODE, dom[1])
     ms_per_step = timed(steps)
     dom_ms, dom_n = ctx.trace_read()
-    tms = [ctx.mixed_step(pb, db, kv, layers=L, timing=True) for _ in range(5 if layers == 1 else 3)]
+    tms = [one_step(timing=True) for _ in range(5 if layers == 1 else 3)]
+    if layers > 1:
+        # the serialized baseline once more, after the timed region: clocks drift over a minute of sustained load
+        ctx.set_cu_split(binding.CUS_ALL, binding.CUS_ALL)
+        keep, hand[0] = hand[0], None
+        run_steps(1)
+        serial["ms_per_step_after_timed_region"] = timed(max(3, steps // 4))
+        hand[0] = keep
+        ctx.set_cu_split(chosen, d_cus)
     dec_lat = float(np.median([t.t_decode_ms for t in tms]))
     pre_lat = float(np.median([t.t_prefill_ms for t in tms]))
 
     traffic = load_traffic(wl.name)
+    eff_cus = chosen if hand[0] is None else (hand[0] * chosen + (layers - hand[0]) * n_cus) / layers
 
     def roof(phase, k, ms):
         if phase == "prefill":
@@ -269,7 +306,9 @@ def measure(idx, layers, steps, warmup, args, headline):
             ach = fl / (ms * 1e-3) / 1e12
             r = {"kernel": f"{phase}.{k}", "bound": "mfma", "achieved": ach, "peak": PEAK_MFMA_TFLOPS,
                  "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_TFLOPS, "traffic": None, "ms_per_launch": ms,
-                 "flops_per_launch": fl, "cus": chosen, "frac_of_cu_share": ach / (PEAK_MFMA_TFLOPS * chosen / n_cus)}
+                 "flops_per_launch": fl, "cus": chosen, "frac_of_cu_share": ach / (PEAK_MFMA_TFLOPS * eff_cus / n_cus)}
+            if hand[0] is not None:
+                r["cus"] = f"{chosen} for layers < {hand[0]}, {n_cus} from there on (launch-weighted mean {eff_cus:.0f})"
         else:
             by = work["decode_bytes"][k]
             ach = by / (ms * 1e-3) / 1e9
@@ -301,8 +340,11 @@ def measure(idx, layers, steps, warmup, args, headline):
     res = {
         "value": work["tokens"] / ms_per_step * 1e3, "ms_per_step": ms_per_step, "steps": steps,
         "config": {"workload": wl.name, "layers": layers, "prefill_tokens": wl.prefill.n_tokens,
-                   "decode_requests": wl.decode.n_reqs, "cu_split": f"{chosen}/{d_cus}",
-                   "split_policy": "min measured concurrent step time over the sweep of 32-CU steps" if args.split == "auto" else "given"},
+                   "decode_requests": wl.decode.n_reqs,
+                   "cu_split": f"{chosen}/{d_cus}" + (f", prefill on all {n_cus} CUs from layer {hand[0]}" if hand[0] is not None else ""),
+                   "split_policy": ("min measured step time over the sweep of 32-CU splits" +
+                                    (", each held to the end of the step or handed to the prefill phase when the decode step has ended" if layers > 1 and not args.no_handover else ""))
+                   if args.split == "auto" else "given"},
         "decode_step_latency_ms": dec_lat, "prefill_phase_latency_ms": pre_lat,
         "serialized": serial, "speedup_vs_serialized": serial_ms / ms_per_step,
         "fused_single_batch": fused_res, "speedup_vs_fused_single_batch": (fused_res["ms_per_step"] / ms_per_step) if fused_res else None,
@@ -329,6 +371,8 @@ def main():
     ap.add_argument("--no-secondary", action="store_true", help="skip the 8B-shaped single-layer configurations")
     ap.add_argument("--no-fused", action="store_true", help="skip the fused single-batch step of the single-layer configurations")
     ap.add_argument("--trace", action="store_true", help="also run the trace-driven serving legs (48-layer 14B-shaped stack, about a minute)")
+    ap.add_argument("--handover", type=int, default=-1, help="with --split: layer from which the prefill phase runs on all CUs")
+    ap.add_argument("--no-handover", action="store_true", help="keep every split to the end of the step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) to calibrate rocprofv3 byte counters")
     args = ap.parse_args()

@@ -283,6 +283,22 @@ int nexus_mixed_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus
                      const nexus_decode_batch *db, const nexus_kv_cache *kv, void *caller_stream,
                      nexus_step_timing *timing);
 /*
+ * nexus_mixed_step with the decode share handed back to the prefill phase inside the step (Sec. 4.2: the
+ * partition follows the load; Sec. 5: a change applies at a kernel boundary and blocks neither stream).  On a
+ * partitioned layout the decode step and the prefill layers [layer_begin, handover_layer) run side by side on
+ * their shares; the prefill layers [handover_layer, layer_end) are launched on the unmasked stream and so run on
+ * every CU, ordered after the layers before them by an event.  They do not wait for the decode step: when
+ * handover_layer is chosen so that the decode step has finished by then (from the phase times nexus_profile_split
+ * measures), the CUs it held are not idle for the rest of the step; when it has not, the two share CUs until it
+ * has.  Results are bit-identical to nexus_mixed_step for every handover_layer (no summation order depends on the
+ * CU share).  handover_layer = layer_end, or the unpartitioned layout, is nexus_mixed_step itself.  Everything else
+ * (ordering against other steps, caller_stream, timing) as there; t_prefill_ms spans both parts.
+ * NEXUS_EINVAL when handover_layer is outside [layer_begin, layer_end].
+ */
+int nexus_mixed_step_handover(nexus_ctx *ctx, int layer_begin, int layer_end, int handover_layer,
+                              const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
+                              void *caller_stream, nexus_step_timing *timing);
+/*
  * Latency-vs-CUs profiling (Sec. 3.2) and split choice (Sec. 4.1.2 on measured curves).  For each candidate i,
  * prefill gets cand_prefill_cus[i] CUs and decode the remaining ones; the phases are timed alone (median of
  * `repeats` runs after one warm-up) and together.  Host output arrays have n_cand entries; t_alone_all_ms[2]

@@ -29,7 +29,7 @@ BUF_NORM1, BUF_Q, BUF_ATTN, BUF_X1, BUF_ACT = range(5)
 
 EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "nexus_last_error", "nexus_cu_count",
            "nexus_kv_import", "nexus_kv_export", "nexus_set_cu_split",
-           "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_profile_split",
+           "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_mixed_step_handover", "nexus_profile_split",
            "nexus_choose_split", "nexus_trace_begin", "nexus_trace_read", "nexus_debug_fetch",
            "nexus_debug_cu_probe", "nexus_debug_token_order", "nexus_cost_latency", "nexus_adjust_partition", "nexus_partition_controller",
            "nexus_cost_fit", "nexus_cost_describe",
@@ -294,6 +294,14 @@ class Nexus:
         sp = C.c_void_p(stream.cuda_stream) if stream is not None else None
         _check(lib().nexus_mixed_step(self._ctx, layers[0], layers[1], C.byref(pb.c), C.byref(db.c), C.byref(kv), sp,
                                       C.byref(tm) if timing else None))
+        return tm
+
+    def mixed_step_handover(self, pb: DevPrefill, db: DevDecode, kv: KVCache, handover_layer: int, layers=(0, 1), stream=None,
+                            timing=False):
+        tm = StepTiming() if timing else None
+        sp = C.c_void_p(stream.cuda_stream) if stream is not None else None
+        _check(lib().nexus_mixed_step_handover(self._ctx, layers[0], layers[1], handover_layer, C.byref(pb.c), C.byref(db.c),
+                                               C.byref(kv), sp, C.byref(tm) if timing else None))
         return tm
 
     def phase_done(self, phase: int) -> bool:

@@ -116,7 +116,7 @@ struct nexus_ctx {
     Layout *cur = nullptr;
     long use_clock = 0;
     bool bits_xcd_major = false;  // CU-mask bit order (see make_mask)
-    hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr, ev_hand = nullptr;
     // ev_ph1[phase]: completion of the last launch that used the phase's workspace (single-phase call, mixed step or
     // fused step), recorded on whatever stream it ran on; every later launch on another stream waits for it, so steps
     // stay ordered across a change of layout.  ev_ph0[phase]: start of the last single-phase call.
@@ -588,19 +588,41 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
     return NEXUS_OK;
 }
 
-static int run_phase(const PhaseRun &r, int layer_begin, int layer_end) {
-    PhaseWs &ws = *r.ws;
-    const bf16_t *x = (const bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->x : r.db->x);
-    bf16_t *y_final = (bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->y : r.db->y);
+// A phase's pass over a layer range, enqueued one layer at a time so that the host can alternate between the two
+// phases of a step (neither stream then sits idle behind the other phase's launches).
+// tail (may be null): layers from tail_from on are launched with *tail -- the same phase, batch and workspace on
+// another stream and CU share -- ordered after the layers before them by an event.
+struct PhaseCursor {
+    PhaseRun r;
+    int layer_begin, layer_end, l;
+    const PhaseRun *tail = nullptr;
+    int tail_from = 0;
+    const bf16_t *x;
     int pending = 0;  // split-K slices of the previous layer's down projection, summed by this layer's first norm
-    for (int l = layer_begin; l < layer_end; ++l) {
+    PhaseCursor(const PhaseRun &run, int lb, int le, const PhaseRun *t = nullptr, int from = 0)
+        : r(run), layer_begin(lb), layer_end(le), l(lb), tail(t), tail_from(from),
+          x((const bf16_t *)(run.phase == NEXUS_PHASE_PREFILL ? run.pb->x : run.db->x)) {}
+    bool done() const { return l >= layer_end; }
+    hipStream_t last_stream() const { return tail && layer_end > tail_from ? tail->s : r.s; }
+    int step() {
+        PhaseWs &ws = *r.ws;
         const bool last = l + 1 == layer_end;
-        bf16_t *y = last ? y_final : ws.xbuf[(l - layer_begin) & 1];
+        bf16_t *y = last ? (bf16_t *)(r.phase == NEXUS_PHASE_PREFILL ? r.pb->y : r.db->y) : ws.xbuf[(l - layer_begin) & 1];
         int next_pending = 0;
-        NX_TRY(run_layer(r, l, x, y, pending, last ? nullptr : &next_pending));
+        if (tail && l == tail_from && tail->s != r.s) {
+            HIP_TRY(hipEventRecord(r.c->ev_hand, r.s));
+            HIP_TRY(hipStreamWaitEvent(tail->s, r.c->ev_hand, 0));
+        }
+        NX_TRY(run_layer(tail && l >= tail_from ? *tail : r, l, x, y, pending, last ? nullptr : &next_pending));
         pending = next_pending;
         x = y;
+        ++l;
+        return NEXUS_OK;
     }
+};
+static int run_phase(const PhaseRun &r, int layer_begin, int layer_end) {
+    PhaseCursor pc(r, layer_begin, layer_end);
+    while (!pc.done()) NX_TRY(pc.step());
     return NEXUS_OK;
 }
 
@@ -750,7 +772,7 @@ void nexus_destroy(nexus_ctx *c) {
     }
     (void)hipFree(c->rope_tab);
     (void)hipFree(c->probe_counts);
-    for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_ph0[0], c->ev_ph0[1], c->ev_ph1[0], c->ev_ph1[1]})
+    for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_hand, c->ev_ph0[0], c->ev_ph0[1], c->ev_ph1[0], c->ev_ph1[1]})
         if (e) (void)hipEventDestroy(e);
     for (auto &t : c->trace_pool) (void)hipEventDestroy(t.a), (void)hipEventDestroy(t.b);
     delete c;
@@ -843,7 +865,7 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         if (const char *dbg = getenv("NEXUS_DEBUG_CHECKS")) c->debug_checks = atoi(dbg) != 0;
         if (const char *ml = getenv("NEXUS_MAX_LAYOUTS")) c->max_layouts = std::max(1, std::min(64, atoi(ml)));
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
-        for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_ph0[0], &c->ev_ph0[1], &c->ev_ph1[0], &c->ev_ph1[1]})
+        for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_hand, &c->ev_ph0[0], &c->ev_ph0[1], &c->ev_ph1[0], &c->ev_ph1[1]})
             if (hipEventCreateWithFlags(e, hipEventDisableSystemFence) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
         if (rc) break;
         if ((rc = alloc_phase_ws(c, NEXUS_PHASE_PREFILL, limits->max_prefill_tokens, limits->max_prefill_reqs))) break;
@@ -1181,8 +1203,8 @@ int nexus_phase_wait(nexus_ctx *c, int phase, float *elapsed_ms) {
     return NEXUS_OK;
 }
 
-int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
-                     void *caller_stream, nexus_step_timing *timing) {
+static int mixed_step_impl(nexus_ctx *c, int lb, int le, int handover, const nexus_prefill_batch *pb, const nexus_decode_batch *db,
+                           const nexus_kv_cache *kv, void *caller_stream, nexus_step_timing *timing) {
     NX_TRY(check_layers(c, lb, le));
     NX_TRY(check_kv(c, kv, le));
     NX_TRY(check_prefill(c, pb));
@@ -1213,18 +1235,41 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
         HIP_TRY(hipEventRecord(c->ev_sp0, L->sp));
         if (split) HIP_TRY(hipEventRecord(c->ev_sd0, L->sd));
     }
-    NX_TRY(run_phase(make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), lb, le));
-    NX_TRY(mark_done(c, L->sp, NEXUS_PHASE_PREFILL, false));
-    NX_TRY(run_phase(make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv), lb, le));
-    NX_TRY(mark_done(c, L->sd, NEXUS_PHASE_DECODE, false));
+    const PhaseRun rp = make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), rd = make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv);
+    if (split) {
+        // the two phases are enqueued alternately, a layer of each at a time, the decode phase (whose kernels are the
+        // shorter ones) first: both streams have work from the start of the step
+        PhaseRun rt = rp;
+        if (handover < le) {
+            Layout *all = nullptr;
+            NX_TRY(get_layout(c, NEXUS_CUS_ALL, NEXUS_CUS_ALL, &all));
+            rt.s = all->sp, rt.n_xcd = all->p_xcd, rt.cus = c->n_cus;
+        }
+        PhaseCursor pc(rp, lb, le, handover < le ? &rt : nullptr, handover), dc(rd, lb, le);
+        while (!pc.done() || !dc.done()) {
+            if (!dc.done()) {
+                NX_TRY(dc.step());
+                if (dc.done()) NX_TRY(mark_done(c, L->sd, NEXUS_PHASE_DECODE, false));
+            }
+            if (!pc.done()) {
+                NX_TRY(pc.step());
+                if (pc.done()) NX_TRY(mark_done(c, pc.last_stream(), NEXUS_PHASE_PREFILL, false));
+            }
+        }
+    } else {
+        NX_TRY(run_phase(rp, lb, le));
+        NX_TRY(mark_done(c, L->sp, NEXUS_PHASE_PREFILL, false));
+        NX_TRY(run_phase(rd, lb, le));
+        NX_TRY(mark_done(c, L->sd, NEXUS_PHASE_DECODE, false));
+    }
     if (cs) {
         if (split) HIP_TRY(hipStreamWaitEvent(cs, c->ev_ph1[NEXUS_PHASE_PREFILL], 0));
         HIP_TRY(hipStreamWaitEvent(cs, c->ev_ph1[NEXUS_PHASE_DECODE], 0));
     }
     hipEvent_t ev_sp1 = c->ev_ph1[NEXUS_PHASE_PREFILL], ev_sd1 = c->ev_ph1[NEXUS_PHASE_DECODE];
     if (timing) {
-        HIP_TRY(hipStreamSynchronize(L->sp));
-        if (split) HIP_TRY(hipStreamSynchronize(L->sd));
+        HIP_TRY(hipEventSynchronize(ev_sp1));
+        HIP_TRY(hipEventSynchronize(ev_sd1));
         float tp = 0, td = 0;
         HIP_TRY(hipEventElapsedTime(&tp, c->ev_sp0, ev_sp1));
         if (split) {
@@ -1241,6 +1286,17 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
         }
     }
     return NEXUS_OK;
+}
+
+int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
+                     void *caller_stream, nexus_step_timing *timing) {
+    return mixed_step_impl(c, lb, le, le, pb, db, kv, caller_stream, timing);
+}
+
+int nexus_mixed_step_handover(nexus_ctx *c, int lb, int le, int handover_layer, const nexus_prefill_batch *pb, const nexus_decode_batch *db,
+                              const nexus_kv_cache *kv, void *caller_stream, nexus_step_timing *timing) {
+    if (handover_layer < lb || handover_layer > le) return fail(NEXUS_EINVAL, "handover layer %d outside [%d, %d]", handover_layer, lb, le);
+    return mixed_step_impl(c, lb, le, handover_layer, pb, db, kv, caller_stream, timing);
 }
 
 static float median(std::vector<float> v) {
