@@ -148,9 +148,10 @@ __device__ __forceinline__ void lds_read_frags(f16x8 (&dst)[N], unsigned base) {
 
 // NWL of the NW wavefronts issue the loads (0 = all of them).  With eight wavefronts (two per SIMD) and NWL = 4 four
 // of them issue the loads of all while the other four, which have none to issue, go straight to their MFMAs behind
-// the barrier (wavefronts w and w + 4 of a workgroup are placed on the same SIMD): a vector-memory instruction holds up the wavefront that issues it, and with all
-// wavefronts issuing at once the matrix unit idles meanwhile (measured on MI355X with 256 x 256 tiles: +2-3 % at 8192
-// tokens, +6 % at 512).
+// the barrier (assuming the usual placement of a workgroup's wavefronts round-robin over the four SIMDs, w and w + 4
+// share one; nothing depends on it but the size of the gain): a vector-memory instruction holds up the wavefront that
+// issues it, and with all wavefronts issuing at once the matrix unit idles meanwhile (measured on MI355X with
+// 256 x 256 tiles: +2-3 % at 8192 tokens, +6 % at 512).
 //
 // BUF_LOADS issues the loads as buffer loads (one resource descriptor per operand matrix, the unit's offset in a
 // scalar register, the lane's 16 bytes as the only vector operand) instead of global loads with a 64-bit address per
