@@ -264,6 +264,9 @@ def measure(idx, layers, steps, warmup, args, headline):
             hand[0] = min(layers, args.handover)
     d_cus = n_cus - chosen if args.split == "auto" else int(args.split.split("/")[1])
     ctx.set_cu_split(chosen, d_cus)
+    # the sweep left a stream pair per split alive; queues beyond the GPU's hardware queues are time-multiplexed, and
+    # with all of them alive back-to-back steps run 2-3 % slower: keep the chosen pair only
+    ctx.retire_cu_splits()
 
     # ---- kernel times at this split (short traced passes), to find the dominant kernel of the step
     run_steps(max(1, warmup // 2))

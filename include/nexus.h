@@ -215,6 +215,15 @@ int nexus_set_cu_split(nexus_ctx *ctx, int prefill_cus, int decode_cus);
  * when more partitioned layouts are asked for than are kept alive.
  */
 int nexus_prepare_cu_splits(nexus_ctx *ctx, int n, const int32_t *prefill_cus, const int32_t *decode_cus);
+/*
+ * Destroys every partitioned layout except the current one (waits for their work first); the unpartitioned layout
+ * stays.  Every CU-masked stream is a queue of its own, the GPU has fewer hardware queues than a full set of layouts
+ * has streams (4 per process by default), and queues beyond that number are time-multiplexed: measured on MI355X, a
+ * step whose successor is already enqueued runs 2-3.5 % slower with seven stream pairs alive than with one.  A caller
+ * that has settled on a split (after nexus_profile_split, say) gets that back with this call; a caller that keeps
+ * switching (Sec. 4.2) keeps the layouts and pays it.
+ */
+int nexus_retire_cu_splits(nexus_ctx *ctx);
 
 /* ---- the step (layers [layer_begin, layer_end); output of layer l feeds layer l + 1) ----------------------- */
 

@@ -36,7 +36,7 @@ EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "n
            "nexus_sched_create", "nexus_sched_destroy", "nexus_sched_submit", "nexus_sched_next", "nexus_sched_commit",
            "nexus_sched_request", "nexus_sched_summarize", "nexus_sched_samples", "nexus_sched_next_phase",
            "nexus_sched_commit_phase", "nexus_phase_query", "nexus_phase_wait", "nexus_fused_step",
-           "nexus_prepare_cu_splits", "nexus_set_debug_checks", "nexus_validate_batches", "nexus_decode_step_noalloc")
+           "nexus_prepare_cu_splits", "nexus_retire_cu_splits", "nexus_set_debug_checks", "nexus_validate_batches", "nexus_decode_step_noalloc")
 
 
 class NexusError(RuntimeError):
@@ -270,6 +270,9 @@ class Nexus:
         n = len(splits)
         p, d = (C.c_int32 * n)(*[s[0] for s in splits]), (C.c_int32 * n)(*[s[1] for s in splits])
         _check(lib().nexus_prepare_cu_splits(self._ctx, n, p, d))
+
+    def retire_cu_splits(self):
+        _check(lib().nexus_retire_cu_splits(self._ctx))
 
     def set_debug_checks(self, on: bool):
         _check(lib().nexus_set_debug_checks(self._ctx, int(on)))

@@ -178,6 +178,9 @@ enum GemmVariant {
     GV_S128W,     // gemm_stream_kernel, 256 features x 128 tokens, 8 waves sharing the activation tiles
     GV_R64,       // gemm_dl_kernel with the extent of GV_S64 / GV_S32: k ranges shorter than the streaming
     GV_R32,       //   kernel's pipeline (hidden sizes below 128)
+    GV_P320,      // gemm_dl_kernel, 320 features x 256 tokens, 8 waves of 5 x 2 MFMA tiles, 144 KiB ring: for a QKV
+                  //   projection whose width is a multiple of 320 (10240 of the 70B-shaped layer: 256 tiles for a
+                  //   2048-token chunk, one round of the whole chip where 256 x 256 tiles need a round and a quarter)
     GV_COUNT
 };
 struct GemmPlan {
@@ -255,6 +258,9 @@ static hipError_t launch_gemm_v(int variant, const GemmArgs &a, dim3 grid, hipSt
                 return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI, true, 4, true>(a, grid, s);
             return launch_gemm_t<8, 8, 4, 2, 2, 4, EPI, true, 4, false>(a, grid, s);
         case GV_P256x128: return launch_gemm_t<8, 4, 2, 2, 2, 4, EPI>(a, grid, s);
+        case GV_P320:  // planned for the row-major epilogue and operands below 4 GiB only
+            if constexpr (EPI == EPI_ROWMAJOR) return launch_gemm_t<10, 8, 2, 4, 2, 4, EPI, true, 4, true>(a, grid, s);
+            return hipErrorInvalidValue;
         case GV_S64: return launch_gemm_stream_t<1, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S32: return launch_gemm_stream_t<1, 1, 4, 4, kStreamDepth, EPI>(a, grid, s);
         case GV_S64W: return launch_gemm_stream_t<2, 2, 4, 4, kStreamDepth, EPI>(a, grid, s);
@@ -349,7 +355,15 @@ static int run_gemm(const PhaseRun &r, int kernel_id, const f16_t *W, int N_pack
         const double est256x128 = total(n256x128, 1, [](int n) { return 55.5 + 0.06 * std::max(0, n - 128); });
         double est128 = total(n128, 2, [](int n) { return 60.0 + 0.0625 * std::max(0, n - 128); });
         if (n128 % (2L * r.cus) && n128 % (2L * r.cus) <= r.cus) est128 -= kscale * 13.0;  // last round: one tile per CU, 47
-        if (c->force_tile ? c->force_tile == 256 : (est256 <= est128 && est256 <= est256x128)) variant = GV_P256, FS = 8, TS = 8;
+        // 320 x 256 tiles: the 256 x 256 kernel with five instead of four MFMA tiles per wavefront along the features
+        // (1.25x the time per round), where the width divides and the epilogue is the plain one
+        double est320 = 1e30;
+        if (epi == EPI_ROWMAJOR && n_ftiles % 10 == 0 && (size_t)n_ftiles * Kp * 64 < ((size_t)1 << 32) && (size_t)a.n_ttiles * Kp * 64 < ((size_t)1 << 32))
+            est320 = 30.0 + 1.25 * total((long)((a.n_ttiles + 7) / 8) * (n_ftiles / 10), 1,
+                                         [](int n) { return 72.0 + 0.14 * std::max(0, n - 128) + 0.21 * std::max(0, n - 192); });
+        const double best = std::min(std::min(est256, est256x128), std::min(est128, est320));
+        if (c->force_tile ? (c->force_tile == 320 && est320 < 1e30) : est320 == best && est320 < est256) variant = GV_P320, FS = 10, TS = 8;
+        else if (c->force_tile ? c->force_tile == 256 : (est256 <= est128 && est256 <= est256x128)) variant = GV_P256, FS = 8, TS = 8;
         else if (c->force_tile ? c->force_tile == 384 : est256x128 <= est128) variant = GV_P256x128, FS = 8, TS = 4;
     }
     // Measured on 64 of the 256 CUs (T = 64): gate/up 113 -> 98 us, down 55 -> 48, O 21.6 -> 18.9 with the wide
@@ -857,11 +871,12 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         c->cus_per_xcd = c->n_cus / c->n_xcd;
         const char *order = getenv("NEXUS_CU_BIT_ORDER");
         c->bits_xcd_major = order && !strcmp(order, "xcd_major");
-        // test hook: one GEMM tile shape for every prefill projection ("128", "256", "256x128"), to compare the shapes
+        // test hook: one GEMM tile shape for every prefill projection ("128", "256", "256x128"; "320" where it applies), to compare the shapes
         // bit for bit and to time them against each other
         const char *tiles = getenv("NEXUS_GEMM_TILES");
         c->allow_p256 = !(tiles && !strcmp(tiles, "128"));
-        c->force_tile = tiles && !strcmp(tiles, "256") ? 256 : tiles && !strcmp(tiles, "256x128") ? 384 : tiles && !strcmp(tiles, "128") ? 128 : 0;
+        c->force_tile = tiles && !strcmp(tiles, "256") ? 256 : tiles && !strcmp(tiles, "256x128") ? 384 : tiles && !strcmp(tiles, "128") ? 128
+                        : tiles && !strcmp(tiles, "320") ? 320 : 0;
         if (const char *dbg = getenv("NEXUS_DEBUG_CHECKS")) c->debug_checks = atoi(dbg) != 0;
         if (const char *ml = getenv("NEXUS_MAX_LAYOUTS")) c->max_layouts = std::max(1, std::min(64, atoi(ml)));
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
@@ -1033,6 +1048,24 @@ int nexus_prepare_cu_splits(nexus_ctx *c, int n, const int32_t *prefill_cus, con
     for (int i = 0; i < n; ++i) {
         Layout *L = nullptr;
         NX_TRY(get_layout(c, prefill_cus[i], decode_cus[i], &L));
+    }
+    return NEXUS_OK;
+}
+
+int nexus_retire_cu_splits(nexus_ctx *c) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    DeviceGuard dg(c->device);
+    for (auto it = c->layouts.begin(); it != c->layouts.end();) {
+        if (it->first == 0 || &it->second == c->cur) {
+            ++it;
+            continue;
+        }
+        HIP_TRY(hipStreamSynchronize(it->second.sp));
+        HIP_TRY(hipStreamSynchronize(it->second.sd));
+        for (int ph = 0; ph < 2; ++ph)  // its work is complete; a new stream may reuse the handle value
+            if (c->done_stream[ph] == it->second.sp || c->done_stream[ph] == it->second.sd) c->done_stream[ph] = nullptr;
+        destroy_layout(it->second);
+        it = c->layouts.erase(it);
     }
     return NEXUS_OK;
 }

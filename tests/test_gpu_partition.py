@@ -124,6 +124,24 @@ def test_layouts_are_created_once_and_switched_without_waiting(nx):
     assert torch.equal(pb.y.view(torch.int16), ref[0].view(torch.int16))
     assert torch.equal(db.y.view(torch.int16), ref[1].view(torch.int16))
     assert ctx.phase_done(nx.PHASE_PREFILL) and ctx.phase_done(nx.PHASE_DECODE)
+
+    # retiring the layouts not in use (with work in flight on them) and coming back to one of them later
+    kv = ctx.make_kv(wl.k_pool, wl.v_pool)
+    pb.y.zero_(), db.y.zero_()
+    torch.cuda.synchronize()
+    for sp in order[:4]:
+        ctx.set_cu_split(*sp)
+        ctx.mixed_step(pb, db, kv)
+    ctx.retire_cu_splits()                      # keeps 224/32 (current) and the unpartitioned layout
+    ctx.mixed_step(pb, db, kv)
+    t0 = time.perf_counter()
+    ctx.set_cu_split(64, 192)                   # retired above: created again
+    recreate_ms = (time.perf_counter() - t0) * 1e3
+    ctx.mixed_step(pb, db, kv)
+    ctx.sync()
+    print(f"[layouts] a retired split selected again: {recreate_ms:.1f} ms", flush=True)
+    assert torch.equal(pb.y.view(torch.int16), ref[0].view(torch.int16))
+    assert torch.equal(db.y.view(torch.int16), ref[1].view(torch.int16))
     ctx.close()
 
 
