@@ -261,6 +261,6 @@ def test_handover_inside_a_step_is_bit_identical_and_frees_the_decode_share(nx):
           f"{t_hand:.2f} ms (decode {hand.t_decode_ms:.2f}); serialized: {t_serial:.2f} ms (decode {serial.t_decode_ms:.2f})", flush=True)
     assert 1 <= h < L
     assert t_hand < 0.92 * t_plain          # measured 0.80
-    assert t_hand < 1.05 * t_serial         # measured 0.99: the serialized step's throughput ...
+    assert t_hand < 1.10 * t_serial         # measured 0.99-1.03: the serialized step's throughput ...
     assert hand.t_decode_ms < 0.5 * serial.t_decode_ms   # ... at a fraction of its decode latency (measured 0.2)
     ctx.close()
