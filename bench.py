@@ -188,6 +188,22 @@ def measure(idx, layers, steps, warmup, args, headline):
     tm = [ctx.mixed_step(pb, db, kv, layers=L, timing=True) for _ in range(3)][-1]
     serial = {"ms_per_step": serial_ms, "tokens_per_s": work["tokens"] / serial_ms * 1e3,
               "t_prefill_ms": tm.t_prefill_ms, "decode_latency_ms": tm.t_decode_ms}
+    # the same two phases in the other order (decode step first, then the chunk; all CUs, one stream): the purely
+    # temporal schedule with the short decode latency, for comparison with what the partition buys
+    def decode_first():
+        ctx.decode_step(db, kv, layers=L)
+        ctx.prefill_chunk(pb, kv, layers=L)
+    decode_first()
+    torch.cuda.synchronize()
+    n_df = max(3, steps // 4)
+    t = time.perf_counter()
+    for _ in range(n_df):
+        decode_first()
+    torch.cuda.synchronize()
+    df_ms = (time.perf_counter() - t) / n_df * 1e3
+    ctx.decode_step(db, kv, layers=L)
+    serial["decode_first"] = {"ms_per_step": df_ms, "tokens_per_s": work["tokens"] / df_ms * 1e3,
+                              "decode_latency_ms": ctx.phase_wait(binding.PHASE_DECODE)}
     log(f"[bench] {wl.name} serialized: {serial}")
 
     # ---- the engine without phase separation (the chunked-prefill engines the paper measures against): ONE batch,
