@@ -130,6 +130,65 @@ def load_traffic(name):
     return traffic
 
 
+def continuous_decode(ctx, binding, wl, pb, db, kv, layers, split, n_chunks=3):
+    """The two phases as independent loops (Sec. 5): prefill chunks back to back on the prefill share while decode steps
+    run back to back on the decode share; and, on all CUs, the temporal schedule that reaches the same time between
+    decode steps by slicing the chunk (a decode step, then k layers of the chunk, and so on).  Tokens per second of
+    each over the time the chunks take."""
+    import copy
+
+    import torch
+    L = (0, layers)
+    tokens_p, tokens_d = wl.prefill.n_tokens, wl.decode.n_reqs
+    ctx.set_cu_split(*split)
+    ctx.mixed_step(pb, db, kv, layers=L)
+    ctx.sync()
+    t0 = time.perf_counter()
+    for _ in range(n_chunks):
+        ctx.prefill_chunk(pb, kv, layers=L)
+    steps, t_steps = 0, []
+    while not ctx.phase_done(binding.PHASE_PREFILL):
+        ctx.decode_step(db, kv, layers=L)
+        t_steps.append(ctx.phase_wait(binding.PHASE_DECODE))
+        steps += 1
+    ctx.sync()
+    window = time.perf_counter() - t0
+    tbt = window / steps * 1e3
+    spatial = {"cu_split": f"{split[0]}/{split[1]}", "prefill_chunks": n_chunks, "decode_steps": steps, "window_ms": window * 1e3,
+               "time_between_decode_steps_ms": tbt, "decode_step_ms": float(sum(t_steps) / len(t_steps)),
+               "tokens_per_s": (n_chunks * tokens_p + steps * tokens_d) / window}
+    # temporal schedule on all CUs at (about) the same time between decode steps
+    ctx.set_cu_split(binding.CUS_ALL, binding.CUS_ALL)
+    ctx.decode_step(db, kv, layers=L)
+    t_dec = ctx.phase_wait(binding.PHASE_DECODE)
+    ctx.prefill_chunk(pb, kv, layers=L)
+    t_layer = ctx.phase_wait(binding.PHASE_PREFILL) / layers
+    k = max(1, min(layers, int(round((tbt - t_dec) / t_layer))))
+    bufs = [torch.empty_like(pb.y), torch.empty_like(pb.y)]
+    ctx.sync()
+    t0 = time.perf_counter()
+    steps_t = 0
+    for _ in range(n_chunks):
+        src = pb.x
+        for i, a in enumerate(range(0, layers, k)):
+            b = min(layers, a + k)
+            ctx.decode_step(db, kv, layers=L)
+            steps_t += 1
+            part = copy.copy(pb)
+            part.c = binding.PrefillBatchC.from_buffer_copy(pb.c)
+            dst = pb.y if b == layers else bufs[i & 1]
+            part.c.x, part.c.y = src.data_ptr(), dst.data_ptr()
+            ctx.prefill_chunk(part, kv, layers=(a, b))
+            src = dst
+    ctx.sync()
+    window_t = time.perf_counter() - t0
+    temporal = {"layers_per_slice": k, "prefill_chunks": n_chunks, "decode_steps": steps_t, "window_ms": window_t * 1e3,
+                "time_between_decode_steps_ms": window_t / steps_t * 1e3,
+                "tokens_per_s": (n_chunks * tokens_p + steps_t * tokens_d) / window_t}
+    return {"independent_loops": spatial, "temporal_slices_all_cus": temporal,
+            "tokens_per_s_ratio": spatial["tokens_per_s"] / temporal["tokens_per_s"]}
+
+
 def measure(idx, layers, steps, warmup, args, headline):
     """One configuration: serialized baseline, sweep of the split, timed steps at the chosen split, rooflines."""
     import numpy as np
@@ -369,6 +428,13 @@ def measure(idx, layers, steps, warmup, args, headline):
         "fused_single_batch": fused_res, "speedup_vs_fused_single_batch": (fused_res["ms_per_step"] / ms_per_step) if fused_res else None,
         "alone": alone, "sweep": sweep, "roofline": roofline, "roofline_other": others, "phase_roofline": phase_roof,
     }
+    if headline and layers > 1 and not args.no_continuous:
+        # steady state with decoding never paused (the serving case): the decode share that keeps a decode step within
+        # alpha = 1.3 of its best (the decode-prioritised choice of the sweep, Sec. 4.1.2), against temporal slicing
+        cd_splits = sorted({alone.get("decode_prioritized_prefill_cus", chosen) if alone else chosen, chosen, n_cus // 2}, reverse=True)
+        res["continuous_decode"] = [continuous_decode(ctx, binding, wl, pb, db, kv, layers, (c, n_cus - c)) for c in cd_splits]
+        ctx.set_cu_split(chosen, d_cus)
+        log(f"[bench] {wl.name} continuous decode: {json.dumps(res['continuous_decode'])}")
     if headline and not args.no_cpu_baseline:
         big = s.hidden >= 8192
         res["cpu_baseline"] = cpu_baseline(wl, first, layers, 160 if big else 512, 32 if big else 64, 1 if big else 2)
@@ -392,6 +458,7 @@ def main():
     ap.add_argument("--trace", action="store_true", help="also run the trace-driven serving legs (48-layer 14B-shaped stack, about a minute)")
     ap.add_argument("--handover", type=int, default=-1, help="with --split: layer from which the prefill phase runs on all CUs")
     ap.add_argument("--no-handover", action="store_true", help="keep every split to the end of the step")
+    ap.add_argument("--no-continuous", action="store_true", help="skip the continuous-decode leg of a multi-layer headline")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) to calibrate rocprofv3 byte counters")
     args = ap.parse_args()
