@@ -231,6 +231,14 @@ def test_handover_inside_a_step_is_bit_identical_and_frees_the_decode_share(nx):
             assert torch.equal(ka.view(torch.int16), kb.view(torch.int16)) and torch.equal(va.view(torch.int16), vb.view(torch.int16)), h
     with pytest.raises(nx.NexusError, match="handover"):
         ctx.mixed_step_handover(pb, db, ref[3], L + 1, layers=(0, L))
+    # on the unpartitioned layout there is nothing to hand over: the call is the plain serialized step
+    ctx.set_cu_split(nx.CUS_ALL, nx.CUS_ALL)
+    ctx.retire_cu_splits()                       # current layout unpartitioned: every stream pair goes
+    got = run(3)
+    assert torch.equal(ref[0].view(torch.int16), got[0].view(torch.int16)) and torch.equal(ref[1].view(torch.int16), got[1].view(torch.int16))
+    ctx.set_cu_split(128, 128)                   # created again
+    got = run(3)
+    assert torch.equal(ref[0].view(torch.int16), got[0].view(torch.int16)) and torch.equal(ref[1].view(torch.int16), got[1].view(torch.int16))
 
     ctx.close()
 
