@@ -91,11 +91,11 @@ struct Layout {
     int p_xcd = 8, d_xcd = 8;  // XCDs each stream is spread over (tile-order hint)
     long last_use = 0;
 };
-// Partitioned stream pairs kept alive.  Measured on MI355X (ROCm 7.2): with one pair alive every pair behaves;
-// with two or three, some pairs (reproducibly the third one created in a process, and with two alive every pair
-// after the second) run the decode queue's kernels 20-35 us late each once its attention kernel has run while the
-// prefill queue is active -- the concurrent step then loses 10-50%.  No synthetic probe reproduced it, so the
-// library never keeps more than one pair: changing the split re-creates the two streams (about 12 ms).
+// Partitioned stream pairs are kept alive once created (up to max_layouts of them, least recently used retired
+// beyond) and switched by pointer.  Every stream is a queue; a process has fewer hardware queues than a full set of
+// pairs has streams and the rest are time-multiplexed: measured on MI355X, back-to-back steps run 2-3.5 % slower
+// with seven pairs alive than with one (steps timed one at a time do not differ), which is what
+// nexus_retire_cu_splits is for.
 
 struct TraceRec {
     hipEvent_t a, b;
@@ -106,7 +106,7 @@ struct nexus_ctx {
     nexus_limits lim{};
     int device = 0, n_cus = 0, n_xcd = 8, cus_per_xcd = 32;
     bool allow_p256 = true;
-    int force_tile = 0;  // test hook: 256 = 256 x 256 tiles wherever the shape allows, 384 = 256 x 128
+    int force_tile = 0;  // test hook: 256 = 256 x 256 tiles wherever the shape allows, 384 = 256 x 128, 320 = 320 x 256, 128
     int q_dim = 0, kv_dim = 0, n_qkv = 0;
     std::vector<LayerW> layers;
     PhaseWs ws[2];
