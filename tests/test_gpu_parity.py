@@ -139,6 +139,31 @@ def test_ragged_and_gqa_shapes(nx, oracle, name, shape, chunks, prefixes, ctx):
     g["ctx"].close()
 
 
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_random_small_workloads(nx, oracle, seed):
+    """Seeded random batches on the small shapes: 1-4 prefill requests with chunks of 1-200 tokens over prefixes of
+    0-300, 0-9 decode requests with contexts of 0-600 (page boundaries fall where they fall), a random split, every
+    output and every cache slot against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    shape_name = ["tiny", "gqa4", "gqa8", "gqa5", "gqa2"][seed % 5]
+    sh = synth.SHAPES.get(shape_name) or EXTRA_SHAPES[shape_name]
+    n_p = int(rng.integers(1, 5))
+    chunks = [int(rng.integers(1, 201)) for _ in range(n_p)]
+    prefixes = [int(rng.integers(0, 301)) if rng.random() < 0.7 else 0 for _ in range(n_p)]
+    ctx = [int(rng.integers(0, 601)) for _ in range(int(rng.integers(0, 10)))] or [int(rng.integers(0, 601))]
+    split = [(64, 192), (128, 128), (192, 64), (32, 224), (224, 32)][int(rng.integers(0, 5))]
+    name = f"random {seed}: {shape_name}, chunks {chunks} over {prefixes}, decode contexts {ctx}, split {split}"
+    _announce(name)
+    wl = synth.make_workload(name, sh, 100 + seed, chunk_lens=chunks, prefix_lens=prefixes, decode_ctx=ctx, page_slack=3)
+    w = synth.make_weights(sh, 100 + seed)
+    ref = run_oracle(oracle, wl, w)
+    g = _gpu_run(nx, wl, w, "mixed", split=split)
+    assert_close("y_prefill", f32(g["y_p"]), ref["y_p"])
+    assert_close("y_decode", f32(g["y_d"]), ref["y_d"])
+    check_pools(name, wl, g["kv"], ref, expected_touched(wl), g["before"])
+    g["ctx"].close()
+
+
 def test_maximum_context_length(nx, oracle):
     """The longest context a prefill workgroup can address (2048 pages = 32768 positions): a 64-token chunk that
     ends exactly there, a decode request whose new token is the 32768th, and one position more is refused."""
