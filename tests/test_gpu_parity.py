@@ -164,6 +164,30 @@ def test_random_small_workloads(nx, oracle, seed):
     g["ctx"].close()
 
 
+def test_8b_shaped_ragged_batch_every_output(nx, oracle):
+    """The tiled GEMMs (128 x 128, 256 x 128 and 256 x 256 tiles, split-K) at full width with token counts that fill
+    none of their tiles evenly: two chunks of 300 and 477 tokens (777 rows: a last 32-row tile of 9, a last 128-token
+    block of 9) over prefixes of 100 and 2000, and 37 decode requests; every output and cache slot against the
+    oracle, on a split and serialized, bit-identical between the two."""
+    name = "8B-shaped ragged 777-token batch"
+    _announce(name)
+    sh = synth.SHAPES["llama3_8b"]
+    rng = np.random.default_rng(7)
+    ctx = [int(rng.integers(1, 3000)) for _ in range(37)]
+    wl = synth.make_workload(name, sh, 21, chunk_lens=[300, 477], prefix_lens=[100, 2000], decode_ctx=ctx, page_slack=3)
+    w = synth.make_weights(sh, 21)
+    ref = run_oracle(oracle, wl, w)
+    g = _gpu_run(nx, wl, w, "mixed", split=(192, 64))
+    assert_close("y_prefill", f32(g["y_p"]), ref["y_p"])
+    assert_close("y_decode", f32(g["y_d"]), ref["y_d"])
+    check_pools(name, wl, g["kv"], ref, expected_touched(wl), g["before"])
+    s_ = _gpu_run(nx, wl, w, "mixed", split=None)
+    for k in ("y_p", "y_d"):
+        assert torch.equal(g[k].view(torch.int16), s_[k].view(torch.int16)), k
+    g["ctx"].close()
+    s_["ctx"].close()
+
+
 def test_maximum_context_length(nx, oracle):
     """The longest context a prefill workgroup can address (2048 pages = 32768 positions): a 64-token chunk that
     ends exactly there, a decode request whose new token is the 32768th, and one position more is refused."""
