@@ -335,8 +335,16 @@ def measure(idx, layers, steps, warmup, args, headline):
         if a + b > n_cus:
             sys.exit(f"bench.py: split {a}/{b} exceeds the device's {n_cus} CUs")
         chosen = a
-        if args.handover >= 0:
-            hand[0] = min(layers, args.handover)
+        if args.handover == "auto":
+            # the library's own choice: its first step on a layout measures the two phases, the next ones use that
+            ctx.set_cu_split(a, b)
+            for _ in range(3):
+                ctx.mixed_step_handover(pb, db, kv, binding.HANDOVER_AUTO, layers=L)
+                ctx.sync()
+            hand[0] = ctx.last_handover_layer()
+            log(f"[bench] {wl.name} split {a}/{b}: the library hands the decode share over at layer {hand[0]}")
+        elif args.handover != "":
+            hand[0] = min(layers, max(0, int(args.handover)))
     d_cus = n_cus - chosen if args.split == "auto" else int(args.split.split("/")[1])
     ctx.set_cu_split(chosen, d_cus)
     # the sweep left a stream pair per split alive; queues beyond the GPU's hardware queues are time-multiplexed, and
@@ -456,7 +464,7 @@ def main():
     ap.add_argument("--no-secondary", action="store_true", help="skip the 8B-shaped single-layer configurations")
     ap.add_argument("--no-fused", action="store_true", help="skip the fused single-batch step of the single-layer configurations")
     ap.add_argument("--trace", action="store_true", help="also run the trace-driven serving legs (48-layer 14B-shaped stack, about a minute)")
-    ap.add_argument("--handover", type=int, default=-1, help="with --split: layer from which the prefill phase runs on all CUs")
+    ap.add_argument("--handover", default="", help="with --split: layer from which the prefill phase runs on all CUs, or 'auto' for the library's choice from its own phase timings")
     ap.add_argument("--no-handover", action="store_true", help="keep every split to the end of the step")
     ap.add_argument("--no-continuous", action="store_true", help="skip the continuous-decode leg of a multi-layer headline")
     ap.add_argument("--calib-copy", action="store_true",

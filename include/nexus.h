@@ -303,10 +303,21 @@ int nexus_mixed_step(nexus_ctx *ctx, int layer_begin, int layer_end, const nexus
  * CU share).  handover_layer = layer_end, or the unpartitioned layout, is nexus_mixed_step itself.  Everything else
  * (ordering against other steps, caller_stream, timing) as there; t_prefill_ms spans both parts.
  * NEXUS_EINVAL when handover_layer is outside [layer_begin, layer_end].
+ *
+ * handover_layer = NEXUS_HANDOVER_AUTO lets the library choose: every such step is bracketed by events, and once a
+ * step has completed its times are read back (without waiting: a step still running is skipped and read later) --
+ * how long the decode step took next to the prefill phase, and how long a prefill layer took on the share.  The next
+ * automatic step on the same layout hands over at the first layer boundary after the decode step's expected end (at
+ * least one layer runs on the share); the first automatic step on a layout has no measurement and holds the split to
+ * the end of the step, which yields one.  The choice follows the load from step to step (Sec. 4.2) at the price of
+ * four event records per step.  nexus_last_handover_layer returns the layer the most recent mixed step handed over
+ * at (layer_end when it did not; 0 before the first step).
  */
+#define NEXUS_HANDOVER_AUTO (-1)
 int nexus_mixed_step_handover(nexus_ctx *ctx, int layer_begin, int layer_end, int handover_layer,
                               const nexus_prefill_batch *pb, const nexus_decode_batch *db, const nexus_kv_cache *kv,
                               void *caller_stream, nexus_step_timing *timing);
+int nexus_last_handover_layer(nexus_ctx *ctx);
 /*
  * Latency-vs-CUs profiling (Sec. 3.2) and split choice (Sec. 4.1.2 on measured curves).  For each candidate i,
  * prefill gets cand_prefill_cus[i] CUs and decode the remaining ones; the phases are timed alone (median of

@@ -23,13 +23,14 @@ LIB_PATH = os.path.join(_HERE, "libnexus.so")
 CUS_ALL = -1
 PHASE_PREFILL, PHASE_DECODE = 0, 1
 POLICY_PREFILL_PRIORITIZED, POLICY_DECODE_PRIORITIZED, POLICY_MIN_STEP = 0, 1, 2
+HANDOVER_AUTO = -1
 KERNELS = ("rmsnorm", "gemm_qkv", "rope_append", "attn_prefill", "gemm_o", "gemm_gate_up", "gemm_down",
            "attn_decode", "attn_merge", "splitk_reduce")
 BUF_NORM1, BUF_Q, BUF_ATTN, BUF_X1, BUF_ACT = range(5)
 
 EXPORTS = ("nexus_create", "nexus_destroy", "nexus_load_layer", "nexus_sync", "nexus_last_error", "nexus_cu_count",
            "nexus_kv_import", "nexus_kv_export", "nexus_set_cu_split",
-           "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_mixed_step_handover", "nexus_profile_split",
+           "nexus_prefill_chunk", "nexus_decode_step", "nexus_mixed_step", "nexus_mixed_step_handover", "nexus_last_handover_layer", "nexus_profile_split",
            "nexus_choose_split", "nexus_trace_begin", "nexus_trace_read", "nexus_debug_fetch",
            "nexus_debug_cu_probe", "nexus_debug_token_order", "nexus_cost_latency", "nexus_adjust_partition", "nexus_partition_controller",
            "nexus_cost_fit", "nexus_cost_describe",
@@ -306,6 +307,9 @@ class Nexus:
         _check(lib().nexus_mixed_step_handover(self._ctx, layers[0], layers[1], handover_layer, C.byref(pb.c), C.byref(db.c),
                                                C.byref(kv), sp, C.byref(tm) if timing else None))
         return tm
+
+    def last_handover_layer(self) -> int:
+        return _check(lib().nexus_last_handover_layer(self._ctx))
 
     def phase_done(self, phase: int) -> bool:
         return bool(_check(lib().nexus_phase_query(self._ctx, phase)))

@@ -117,6 +117,18 @@ struct nexus_ctx {
     long use_clock = 0;
     bool bits_xcd_major = false;  // CU-mask bit order (see make_mask)
     hipEvent_t ev_fork = nullptr, ev_caller = nullptr, ev_sp0 = nullptr, ev_sp1 = nullptr, ev_sd0 = nullptr, ev_hand = nullptr;
+    // automatic handover: phase times of recent steps, read back once those steps have completed (two sets of events,
+    // so that a step can be enqueued while the one before it still runs)
+    struct HandoverSample {
+        hipEvent_t p0 = nullptr, d0 = nullptr, ph = nullptr, d1 = nullptr;  // prefill start, decode start, end of the prefill head, decode end
+        Layout *layout = nullptr;
+        int head_layers = 0;
+        bool pending = false;
+    } ho_sample[2];
+    int ho_next = 0;
+    Layout *ho_layout = nullptr;              // layout the estimates below were measured on
+    float ho_decode_ms = 0.f, ho_head_layer_ms = 0.f;
+    int last_handover_layer = 0;
     // ev_ph1[phase]: completion of the last launch that used the phase's workspace (single-phase call, mixed step or
     // fused step), recorded on whatever stream it ran on; every later launch on another stream waits for it, so steps
     // stay ordered across a change of layout.  ev_ph0[phase]: start of the last single-phase call.
@@ -786,6 +798,9 @@ void nexus_destroy(nexus_ctx *c) {
     }
     (void)hipFree(c->rope_tab);
     (void)hipFree(c->probe_counts);
+    for (auto &hs : c->ho_sample)
+        for (hipEvent_t e : {hs.p0, hs.d0, hs.ph, hs.d1})
+            if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : {c->ev_fork, c->ev_caller, c->ev_sp0, c->ev_sp1, c->ev_sd0, c->ev_hand, c->ev_ph0[0], c->ev_ph0[1], c->ev_ph1[0], c->ev_ph1[1]})
         if (e) (void)hipEventDestroy(e);
     for (auto &t : c->trace_pool) (void)hipEventDestroy(t.a), (void)hipEventDestroy(t.b);
@@ -882,6 +897,9 @@ int nexus_create(const nexus_model_desc *desc, const nexus_limits *limits, int d
         if (hipStreamCreateWithFlags(&c->s_main, hipStreamNonBlocking) != hipSuccess) { rc = fail(NEXUS_EHIP, "stream creation failed"); break; }
         for (hipEvent_t *e : {&c->ev_fork, &c->ev_caller, &c->ev_sp0, &c->ev_sp1, &c->ev_sd0, &c->ev_hand, &c->ev_ph0[0], &c->ev_ph0[1], &c->ev_ph1[0], &c->ev_ph1[1]})
             if (hipEventCreateWithFlags(e, hipEventDisableSystemFence) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
+        for (auto &hs : c->ho_sample)
+            for (hipEvent_t *e : {&hs.p0, &hs.d0, &hs.ph, &hs.d1})
+                if (hipEventCreate(e) != hipSuccess) { rc = fail(NEXUS_EHIP, "event creation failed"); break; }
         if (rc) break;
         if ((rc = alloc_phase_ws(c, NEXUS_PHASE_PREFILL, limits->max_prefill_tokens, limits->max_prefill_reqs))) break;
         if ((rc = alloc_phase_ws(c, NEXUS_PHASE_DECODE, limits->max_decode_reqs, limits->max_decode_reqs))) break;
@@ -1247,6 +1265,29 @@ static int mixed_step_impl(nexus_ctx *c, int lb, int le, int handover, const nex
     Layout *L = c->cur;
     hipStream_t cs = (hipStream_t)caller_stream;
     const bool split = L->sd != L->sp;
+    const bool auto_handover = handover == NEXUS_HANDOVER_AUTO;
+    nexus_ctx::HandoverSample *sample = nullptr;
+    if (auto_handover) {
+        handover = le;
+        if (split) {
+            // phase times of earlier steps that have completed by now
+            for (auto &hs : c->ho_sample) {
+                if (!hs.pending || hipEventQuery(hs.d1) != hipSuccess || hipEventQuery(hs.ph) != hipSuccess) continue;
+                float t_dec = 0.f, t_head = 0.f;
+                hs.pending = false;
+                if (hipEventElapsedTime(&t_dec, hs.d0, hs.d1) != hipSuccess || hipEventElapsedTime(&t_head, hs.p0, hs.ph) != hipSuccess) continue;
+                if (hs.head_layers > 0 && t_head > 0.f && t_dec > 0.f)
+                    c->ho_layout = hs.layout, c->ho_decode_ms = t_dec, c->ho_head_layer_ms = t_head / hs.head_layers;
+            }
+            // the first layer boundary after the decode step's end; without a measurement on this layout the split is
+            // held to the end of the step, which produces one
+            if (c->ho_layout == L && c->ho_head_layer_ms > 0.f)
+                handover = std::max(lb + 1, std::min(le, lb + (int)std::ceil(c->ho_decode_ms / c->ho_head_layer_ms)));
+            sample = &c->ho_sample[c->ho_next];
+            c->ho_next ^= 1;
+        }
+    }
+    c->last_handover_layer = split ? handover : le;
     if (cs) {
         HIP_TRY(hipEventRecord(c->ev_caller, cs));
         HIP_TRY(hipStreamWaitEvent(L->sp, c->ev_caller, 0));
@@ -1268,6 +1309,11 @@ static int mixed_step_impl(nexus_ctx *c, int lb, int le, int handover, const nex
         HIP_TRY(hipEventRecord(c->ev_sp0, L->sp));
         if (split) HIP_TRY(hipEventRecord(c->ev_sd0, L->sd));
     }
+    if (sample) {
+        HIP_TRY(hipEventRecord(sample->p0, L->sp));
+        HIP_TRY(hipEventRecord(sample->d0, L->sd));
+        sample->layout = L, sample->head_layers = handover - lb, sample->pending = true;
+    }
     const PhaseRun rp = make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), rd = make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv);
     if (split) {
         // the two phases are enqueued alternately, a layer of each at a time, the decode phase (whose kernels are the
@@ -1282,10 +1328,14 @@ static int mixed_step_impl(nexus_ctx *c, int lb, int le, int handover, const nex
         while (!pc.done() || !dc.done()) {
             if (!dc.done()) {
                 NX_TRY(dc.step());
-                if (dc.done()) NX_TRY(mark_done(c, L->sd, NEXUS_PHASE_DECODE, false));
+                if (dc.done()) {
+                    if (sample) HIP_TRY(hipEventRecord(sample->d1, L->sd));
+                    NX_TRY(mark_done(c, L->sd, NEXUS_PHASE_DECODE, false));
+                }
             }
             if (!pc.done()) {
                 NX_TRY(pc.step());
+                if (sample && pc.l == handover) HIP_TRY(hipEventRecord(sample->ph, L->sp));  // end of the layers run on the share
                 if (pc.done()) NX_TRY(mark_done(c, pc.last_stream(), NEXUS_PHASE_PREFILL, false));
             }
         }
@@ -1328,8 +1378,14 @@ int nexus_mixed_step(nexus_ctx *c, int lb, int le, const nexus_prefill_batch *pb
 
 int nexus_mixed_step_handover(nexus_ctx *c, int lb, int le, int handover_layer, const nexus_prefill_batch *pb, const nexus_decode_batch *db,
                               const nexus_kv_cache *kv, void *caller_stream, nexus_step_timing *timing) {
-    if (handover_layer < lb || handover_layer > le) return fail(NEXUS_EINVAL, "handover layer %d outside [%d, %d]", handover_layer, lb, le);
+    if (handover_layer != NEXUS_HANDOVER_AUTO && (handover_layer < lb || handover_layer > le))
+        return fail(NEXUS_EINVAL, "handover layer %d outside [%d, %d]", handover_layer, lb, le);
     return mixed_step_impl(c, lb, le, handover_layer, pb, db, kv, caller_stream, timing);
+}
+
+int nexus_last_handover_layer(nexus_ctx *c) {
+    if (!c) return fail(NEXUS_EINVAL, "null context");
+    return c->last_handover_layer;
 }
 
 static float median(std::vector<float> v) {

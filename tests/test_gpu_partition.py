@@ -269,6 +269,38 @@ def test_handover_inside_a_step_is_bit_identical_and_frees_the_decode_share(nx):
           f"{t_hand:.2f} ms (decode {hand.t_decode_ms:.2f}); serialized: {t_serial:.2f} ms (decode {serial.t_decode_ms:.2f})", flush=True)
     assert 1 <= h < L
     assert t_hand < 0.92 * t_plain          # measured 0.80
+    # the library choosing the layer itself: the first automatic step on a layout has no measurement and holds the
+    # split (which yields one), the following ones hand over where the decode step ended; also with steps enqueued
+    # back to back (a step's times are read only once it has completed)
+    ctx.set_cu_split(128, 128)
+    ctx.retire_cu_splits()
+    ctx.set_cu_split(96, 160)                # a layout with no history
+    ref_y = None
+    used = []
+    for i in range(4):
+        ctx.mixed_step_handover(pb, db, kv, nx.HANDOVER_AUTO, layers=(0, L))
+        used.append(ctx.last_handover_layer())
+        ctx.sync()
+        if ref_y is None:
+            ref_y = (pb.y.clone(), db.y.clone())
+        assert torch.equal(pb.y.view(torch.int16), ref_y[0].view(torch.int16)) and torch.equal(db.y.view(torch.int16), ref_y[1].view(torch.int16))
+    print(f"[handover] automatic, one step at a time, split 96/160: handover layers {used}", flush=True)
+    assert used[0] == L and all(1 <= u < L for u in used[1:])
+    used = []
+    for i in range(6):
+        ctx.mixed_step_handover(pb, db, kv, nx.HANDOVER_AUTO, layers=(0, L))
+        used.append(ctx.last_handover_layer())
+    ctx.sync()
+    print(f"[handover] automatic, six steps enqueued back to back: handover layers {used}", flush=True)
+    assert all(1 <= u <= L for u in used) and used[-1] < L
+    assert torch.equal(pb.y.view(torch.int16), ref_y[0].view(torch.int16)) and torch.equal(db.y.view(torch.int16), ref_y[1].view(torch.int16))
+    auto_ms = med(lambda: ctx.mixed_step_handover(pb, db, kv, nx.HANDOVER_AUTO, layers=(0, L), timing=True))
+    auto_h = ctx.last_handover_layer()
+    held_ms = med(lambda: ctx.mixed_step(pb, db, kv, layers=(0, L), timing=True))
+    assert ctx.last_handover_layer() == L    # a held step reports no handover
+    print(f"[handover] split 96/160: automatic {auto_ms:.2f} ms (handover at {auto_h}), held {held_ms:.2f} ms", flush=True)
+    assert auto_ms < 0.92 * held_ms
+    ctx.set_cu_split(128, 128)
     assert t_hand < 1.10 * t_serial         # measured 0.99-1.03: the serialized step's throughput ...
     assert hand.t_decode_ms < 0.5 * serial.t_decode_ms   # ... at a fraction of its decode latency (measured 0.2)
     ctx.close()
