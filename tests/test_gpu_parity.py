@@ -624,20 +624,31 @@ def test_cfg5_full_depth_80_layers_resident(nx):
             print(f"[cfg5] {l + 1} layers loaded", flush=True)
     pb, db = nx.DevPrefill(wl.prefill, ctx.device), nx.DevDecode(wl.decode, ctx.device)
     outs = []
-    for split in ((224, 32), (nx.CUS_ALL, nx.CUS_ALL)):
+    # the benchmark's launch configuration (160/96, decode share handed to the prefill phase at layer 16), the same
+    # split with the layer chosen by the library, a split held to the end of the step, and the serialized order
+    for split, hand in (((160, 96), 16), ((160, 96), nx.HANDOVER_AUTO), ((224, 32), None), ((nx.CUS_ALL, nx.CUS_ALL), None)):
         kv = ctx.make_kv(wl.k_pool, wl.v_pool, layers=s.n_layers)
         ctx.set_cu_split(*split)
-        ctx.mixed_step(pb, db, kv, layers=(0, s.n_layers))
+
+        def step(timing=False):
+            if hand is None:
+                return ctx.mixed_step(pb, db, kv, layers=(0, s.n_layers), timing=timing)
+            return ctx.mixed_step_handover(pb, db, kv, hand, layers=(0, s.n_layers), timing=timing)
+        step()
         ctx.sync()
-        t = ctx.mixed_step(pb, db, kv, layers=(0, s.n_layers), timing=True)
-        print(f"[cfg5] split {split}: step {t.t_step_ms:.1f} ms over {s.n_layers} layers, decode {t.t_decode_ms:.1f} ms", flush=True)
-        ctx.mixed_step(pb, db, kv, layers=(0, s.n_layers))
+        t = step(timing=True)
+        at = "" if hand is None else f", handover at layer {ctx.last_handover_layer()}"
+        print(f"[cfg5] split {split}{at}: step {t.t_step_ms:.1f} ms over {s.n_layers} layers, decode {t.t_decode_ms:.1f} ms", flush=True)
+        if hand == nx.HANDOVER_AUTO:
+            assert 1 <= ctx.last_handover_layer() < s.n_layers
+        step()
         ctx.sync()
         outs.append((pb.y.clone(), db.y.clone()))
         del kv
     assert torch.isfinite(outs[0][0].float()).all() and torch.isfinite(outs[0][1].float()).all()
-    assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16))
-    assert torch.equal(outs[0][1].view(torch.int16), outs[1][1].view(torch.int16))
+    for o in outs[1:]:
+        assert torch.equal(outs[0][0].view(torch.int16), o[0].view(torch.int16))
+        assert torch.equal(outs[0][1].view(torch.int16), o[1].view(torch.int16))
     ctx.close()
 
 
