@@ -760,6 +760,13 @@ static int make_layout(nexus_ctx *c, int p_cus, int d_cus, Layout *out) {
     return NEXUS_OK;
 }
 
+// A layout about to be destroyed takes its phase-time measurements with it (a later layout may get its address).
+static void forget_handover_history(nexus_ctx *c, const Layout *L) {
+    if (c->ho_layout == L) c->ho_layout = nullptr;
+    for (auto &hs : c->ho_sample)
+        if (hs.layout == L) hs.pending = false, hs.layout = nullptr;
+}
+
 static void destroy_layout(Layout &L) {
     if (L.sd && L.sd != L.sp) (void)hipStreamDestroy(L.sd);
     if (L.sp) (void)hipStreamDestroy(L.sp);
@@ -1034,6 +1041,7 @@ static int get_layout(nexus_ctx *c, int prefill_cus, int decode_cus, Layout **ou
             for (int ph = 0; ph < 2; ++ph)  // its work is complete; a new stream may reuse the handle value
                 if (c->done_stream[ph] == victim->second.sp || c->done_stream[ph] == victim->second.sd) c->done_stream[ph] = nullptr;
             if (c->cur == &victim->second) c->cur = &c->layouts[0];
+            forget_handover_history(c, &victim->second);
             destroy_layout(victim->second);
             c->layouts.erase(victim);
             --masked;
@@ -1082,6 +1090,7 @@ int nexus_retire_cu_splits(nexus_ctx *c) {
         HIP_TRY(hipStreamSynchronize(it->second.sd));
         for (int ph = 0; ph < 2; ++ph)  // its work is complete; a new stream may reuse the handle value
             if (c->done_stream[ph] == it->second.sp || c->done_stream[ph] == it->second.sd) c->done_stream[ph] = nullptr;
+        forget_handover_history(c, &it->second);
         destroy_layout(it->second);
         it = c->layouts.erase(it);
     }
@@ -1271,7 +1280,8 @@ static int mixed_step_impl(nexus_ctx *c, int lb, int le, int handover, const nex
         handover = le;
         if (split) {
             // phase times of earlier steps that have completed by now
-            for (auto &hs : c->ho_sample) {
+            for (int i = 0; i < 2; ++i) {  // the older set first: the newest completed step has the last word
+                auto &hs = c->ho_sample[c->ho_next ^ i];
                 if (!hs.pending || hipEventQuery(hs.d1) != hipSuccess || hipEventQuery(hs.ph) != hipSuccess) continue;
                 float t_dec = 0.f, t_head = 0.f;
                 hs.pending = false;
@@ -1312,7 +1322,7 @@ static int mixed_step_impl(nexus_ctx *c, int lb, int le, int handover, const nex
     if (sample) {
         HIP_TRY(hipEventRecord(sample->p0, L->sp));
         HIP_TRY(hipEventRecord(sample->d0, L->sd));
-        sample->layout = L, sample->head_layers = handover - lb, sample->pending = true;
+        sample->layout = L, sample->head_layers = handover - lb, sample->pending = false;
     }
     const PhaseRun rp = make_run(c, NEXUS_PHASE_PREFILL, pb, nullptr, kv), rd = make_run(c, NEXUS_PHASE_DECODE, nullptr, db, kv);
     if (split) {
@@ -1339,6 +1349,7 @@ static int mixed_step_impl(nexus_ctx *c, int lb, int le, int handover, const nex
                 if (pc.done()) NX_TRY(mark_done(c, pc.last_stream(), NEXUS_PHASE_PREFILL, false));
             }
         }
+        if (sample) sample->pending = true;  // all four events of the sample are recorded
     } else {
         NX_TRY(run_phase(rp, lb, le));
         NX_TRY(mark_done(c, L->sp, NEXUS_PHASE_PREFILL, false));
