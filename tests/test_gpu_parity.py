@@ -595,6 +595,50 @@ def test_larger_model_shapes_full_size_sampled(nx, oracle, idx, layer, split, st
         assert stats["decode"][1] < 0.02, stats
 
 
+@pytest.mark.parametrize("shape_name,chunk,seed", [("llama3_8b", 436, 312), ("qwen25_14b", 116, 301)], ids=["8B-shaped", "14B-shaped"])
+def test_first_chunk_of_a_prompt_at_the_wide_shapes(nx, oracle, shape_name, chunk, seed):
+    """The first chunk of a prompt (no prefix) on the 8B- and 14B-shaped layers, every output row.  Rows with few
+    keys are the hard ones for a bf16 cache: their attention output averages over few values, so it is large (rms
+    0.3-0.7 against 0.07 behind a 1500-token prefix) and the 2^-9 roundings of K and V reach the layer's output
+    unaveraged, amplified by the N(0, 0.02) feed-forward block (output rms ~3).  The exact layer with nothing changed
+    but the rounding of the K/V it appends already leaves the elementwise bar on such rows (the floor, computed
+    here on the CPU); the path adds the bf16 rounding of the rotated queries and ends ~1.4x above the floor in
+    relative L2.  Asserted: relative L2 of every stage and of the output, the appended K/V and the queries to the
+    whole bar, finiteness, the path's own arithmetic (against the layer with a bf16 cache) within 2x of the floor's
+    relative L2, at most 1 % of the outputs outside the elementwise bar, and none of it on the decode side (whose
+    contexts are long).  The elementwise figures of the prefill output are printed, together with the floor's."""
+    from tests.parity_util import oracle_model, oracle_weights
+    _announce(f"first chunk of {chunk} tokens, {shape_name}")
+    sh = synth.SHAPES[shape_name]
+    wl = synth.make_workload("first chunk", sh, seed, chunk_lens=[chunk], prefix_lens=[0], decode_ctx=[100, 200, 1000], page_slack=3)
+    w = synth.make_weights(sh, seed)
+    ref = run_oracle(oracle, wl, w, debug=True)
+    g = _gpu_run(nx, wl, w, "mixed", split=(128, 128))
+    T = wl.prefill.n_tokens
+    assert torch.isfinite(g["y_p"].float()).all()
+    assert_close("q", f32(g["ctx"].debug_fetch(nx.PHASE_PREFILL, nx.BUF_Q, T)), ref["dbg_p"]["q"])
+    assert_close("y_decode", f32(g["y_d"]), ref["y_d"])
+    check_pools("first chunk", wl, g["kv"], ref, expected_touched(wl), g["before"])
+    p = wl.prefill
+    kp, vp = f32(wl.k_pool).copy(), f32(wl.v_pool).copy()
+    floor = oracle.layer_prefill_rows(oracle_model(oracle, sh), oracle_weights(w), f32(p.x), p.cu_chunk, p.prefix_len, p.page_table,
+                                      kp, vp, np.arange(T, dtype=np.int32), kv_store_bf16=True)
+    got = f32(g["y_p"])
+    stats = {"attention output": parity_stats(f32(g["ctx"].debug_fetch(nx.PHASE_PREFILL, nx.BUF_ATTN, T)), ref["dbg_p"]["attn"]),
+             "x1": parity_stats(f32(g["ctx"].debug_fetch(nx.PHASE_PREFILL, nx.BUF_X1, T)), ref["dbg_p"]["x1"]),
+             "output": parity_stats(got, ref["y_p"]),
+             "bf16 cache storage alone": parity_stats(floor, ref["y_p"]),
+             "path against the layer with a bf16 cache": parity_stats(got, floor)}
+    bad_rows = np.nonzero((np.abs(got - ref["y_p"]) > 2e-2 + 2e-2 * np.abs(ref["y_p"])).any(axis=1))[0]
+    for name, (wst, frac, rel) in stats.items():
+        print(f"[parity, reported] {shape_name} first chunk, {name}: worst err/bound {wst:.2f}, {100 * frac:.3f} % outside the bar, rel L2 {rel:.2e}", flush=True)
+        assert rel <= 1e-2, f"{name}: relative L2 {rel:.3g}"
+    print(f"[parity, reported] rows with an output outside the bar: {len(bad_rows)} of {T}, the last one row {bad_rows.max() if len(bad_rows) else -1}", flush=True)
+    assert stats["output"][1] < 0.01, stats
+    assert stats["path against the layer with a bf16 cache"][2] < 2.0 * stats["bf16 cache storage alone"][2], stats
+    g["ctx"].close()
+
+
 def test_cfg5_full_depth_80_layers_resident(nx):
     """The 70B-shaped stack at full depth on the one GPU: 80 layers of packed weights (~137 GB) and 80 layers of
     KV (~55 GB) resident, one mixed step through all of them.  Layer weights are drawn on the device (a host copy
