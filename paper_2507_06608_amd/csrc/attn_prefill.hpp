@@ -50,7 +50,12 @@ __device__ __forceinline__ void attn_split_range(int n_tiles, int n_splits, int 
 }
 
 constexpr int kAttnTile = 32;   // keys per LDS stage (2 pages of K and of V)
-constexpr int kAttnStages = 4;  // ring depth: three tiles in flight while one is consumed
+constexpr float kAttnLazyLog2 = 8.f;  // rise of a row's running maximum (log2 units) that moves the exponents' reference
+// Tiles issued ahead of the one whose K operands are read.  The ring holds those, that one, and the one before it
+// (whose V operands are read an iteration later).  A workgroup of up to four wavefronts shares its CU with a second
+// one, and two rings of five 16 KiB stages would not fit the CU's LDS next to the staged page ids: it looks two ahead.
+constexpr int attn_ahead(int n_waves) { return n_waves > 4 ? 3 : 2; }
+constexpr int attn_stages(int n_waves) { return attn_ahead(n_waves) + 2; }
 
 template <int HD, int G, int SPB>
 __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefillArgs a) {  // two wavefronts per SIMD
@@ -62,7 +67,7 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     constexpr int LW = NW >= 8 ? 8 : NW >= 4 ? 4 : NW;  // wavefronts that issue loads: UNITS / LW each
     static_assert(UNITS % LW == 0, "uniform load count per loading wavefront (the vmcnt waits rely on it)");
     constexpr int LPW = UNITS / LW;
-    constexpr int NST = kAttnStages;
+    constexpr int NST = attn_stages(NW), AHEAD = attn_ahead(NW);
     constexpr int KK = HD / 16;              // k-steps of the QK^T product
     constexpr int RT = HD / 32;              // 32-row tiles of O^T
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -164,21 +169,36 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
         }
     };
 
-    // The loop is software-pipelined over the key tiles.  Iteration t: (barrier: tile t has landed) -> issue the K
-    // operand reads of tile t -> softmax and PV of tile t - 1 (scores and V operands are in registers since the
-    // previous iteration) -> issue the V operand reads of tile t -> QK^T of tile t.  The LDS latency of the K reads
-    // passes under the softmax, that of the V reads under the QK^T chain, and a wavefront alternates between one
-    // block of 2 KK matrix instructions and one block of vector instructions, which the other wavefront of its
-    // SIMD (see the priority above) fills with the opposite block.
-    f32x16 s;
-    bf16x8 kf[KK];
-    u32x4 vf[2][RT];
-    // softmax of the scores in s (tile `tile`) and O^T += V^T P^T with the V operands in vf
-    auto softmax_pv = [&](int tile) {
+    // The loop is software-pipelined over the key tiles.  Iteration t (after the barrier: tile t has landed, and
+    // everyone is done with tile t - 2, whose stage is refilled): the scores of tile t - 1 are pending in registers;
+    // the QK^T chain of tile t and the softmax of tile t - 1 are independent and are issued INTERLEAVED, one matrix
+    // instruction per dozen vector instructions, with the K operand reads of tile t and the V operand reads of tile
+    // t - 1 spread between them, so that a single wavefront keeps the matrix unit and the vector unit busy at the
+    // same time (the eight wavefronts of a workgroup run in step from barrier to barrier: with a vector block
+    // followed by a matrix block in each of them, the two wavefronts of a SIMD would want the same unit at the same
+    // time); the PV product of tile t - 1 follows.  Tiles that need the causal mask or reach past the block's last
+    // key, the first and the last iteration take the plain order (softmax, PV, then QK^T).
+    f32x16 s;  // scores of the pending tile
+    auto read_k = [&](const char *sK, bf16x8 (&kf)[KK]) __attribute__((always_inline)) {
+        // operand A row (lane % 32): page row / 16, slot row % 16 (slots are rows as they stand); k-slot group g
+        const char *kp = sK + (col >> 4) * BLK + (col & 15) * 16 + g * 256;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) kf[kk] = *(const bf16x8 *)(kp + kk * 512);
+    };
+    auto read_v = [&](const char *sK, u32x4 (&vf)[2][RT]) __attribute__((always_inline)) {
+        // V block [2 token groups][hd][8]: lane (col, g) reads hd row 32 i + col of token group g
+        const char *sV = sK + 2 * BLK;
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int i = 0; i < RT; ++i) vf[pg][i] = *(const u32x4 *)(sV + pg * BLK + (g * HD + col) * 16 + i * 512);
+    };
+    // Softmax of the scores in s (tile `tile`) in two parts.  First the running maximum: returns the factor alpha the
+    // output accumulators must be rescaled by before this tile's PV product, and the reference mref of the exponents.
+    auto softmax_max = [&](int tile, const bool need_mask, float &mref) __attribute__((always_inline)) -> float {
         const int key0 = tile * kAttnTile;
         // Register 4b + j of s is row 8b + 4g + j: page b / 2, slot 8(b%2) + 4g + j, which holds token
         // 8g + 4(b%2) + j.  So registers 8p .. 8p+7 are tokens 8g .. 8g+7 of page p, in order.
-        const bool need_mask = key0 + kAttnTile - 1 > wave_min_pos;
         // The running maximum is kept in scaled units (score * log2(e) / sqrt(hd)); the scale is positive, so
         // the maximum is taken over the raw scores and scaled once, and the scaling of every score is folded
         // into the exponent's fused multiply-add.
@@ -194,10 +214,21 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
         for (int e = 0; e < 16; ++e) mraw = fmaxf(mraw, s[e]);
         float mx = fmaxf(m_run, mraw * a.scale_log2e);
         mx = xor32_max(mx);
+        // The reference of the exponents follows the running maximum lazily: it moves only when the maximum has
+        // risen by more than kAttnLazyLog2 since it was last set.  Any reference gives the same softmax as long as
+        // sum and accumulators refer to the same one; a stale one lets the probabilities reach 2^kAttnLazyLog2
+        // instead of 1 (no matter to fp32 sums or bf16 operands) and spares the rescale of the 16 RT accumulator
+        // registers on almost every tile (with 32 rows a wavefront, some row sets a new maximum in most tiles of
+        // the first few thousand keys).
+        const float m_new = mx > m_run + kAttnLazyLog2 ? mx : m_run;
         // a row may see no key at all in this split's range yet: keep the arithmetic finite
-        const float mref = mx == -INFINITY ? 0.f : mx;
+        mref = m_new == -INFINITY ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run - mref);
-        m_run = mx;
+        m_run = m_new;
+        return alpha;
+    };
+    // Then the exponentials: s holds the probabilities afterwards, and the running sum moves on.
+    auto softmax_exp = [&](float mref, float alpha) __attribute__((always_inline)) {
         float rs = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -206,14 +237,38 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
             rs += p;
         }
         l_run = l_run * alpha + rs;
-        // After the first few tiles the maximum rarely moves and alpha is exactly 1 in every lane: the 16 RT
-        // multiplications of the rescale are then skipped (multiplying by 1.0 changes no bit).
+    };
+    // O^T *= alpha.  After the first few tiles the maximum rarely moves and alpha is exactly 1 in every lane: the 16 RT
+    // multiplications are then skipped (multiplying by 1.0 changes no bit).
+    auto rescale = [&](float alpha) __attribute__((always_inline)) {
         if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
             for (int i = 0; i < RT; ++i)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
         }
+    };
+    // O^T += V^T P^T with the probabilities in s and the V operands in vf
+    auto pv = [&](u32x4 (&vf)[2][RT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+            bf16x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[8 * pg + e];
+#pragma unroll
+            for (int i = 0; i < RT; ++i)
+                o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf[pg][i], pf, o_acc[i], 0, 0, 0);
+        }
+    };
+    // the plain order for the pending tile: V operands, softmax, PV
+    auto softmax_pv = [&](int tile) __attribute__((always_inline)) {
+        const int key0 = tile * kAttnTile;
+        u32x4 vf[2][RT];
+        read_v(smem + (tile % NST) * STAGE, vf);
+        float mref;
+        const float alpha = softmax_max(tile, key0 + kAttnTile - 1 > wave_min_pos, mref);
+        softmax_exp(mref, alpha);
+        rescale(alpha);
         // V slots at or past kmax may hold anything (even NaN): their probability is exactly 0, but 0 * NaN is
         // not, so the last tile zeroes them.
         if (key0 + kAttnTile > kmax) {  // uniform: the last tile of the block only
@@ -227,64 +282,77 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
                         if (e >= left) vf[pg][i][e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
             }
         }
-#pragma unroll
-        for (int pg = 0; pg < 2; ++pg) {
-            bf16x8 pf;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[8 * pg + e];
-#pragma unroll
-            for (int i = 0; i < RT; ++i)
-                o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf[pg][i], pf, o_acc[i], 0, 0, 0);
-        }
+        pv(vf);
     };
 
 #pragma unroll
-    for (int i = 0; i < NST - 1; ++i)
+    for (int i = 0; i < AHEAD; ++i)
         if (t_begin + i < t_end) issue(t_begin + i);
-    bool pending = false;  // s and vf hold a tile whose softmax and PV are still to come
-    for (int tile = t_begin; tile < t_end; ++tile) {
-        // loads issued after those of this tile and allowed to stay in flight: min(NST - 2, tiles left after it)
+    // what every wavefront does at the top of an iteration, whatever it computes there
+    auto tile_landed = [&](int tile) __attribute__((always_inline)) {
+        // loads issued after those of this tile and allowed to stay in flight: min(AHEAD - 1, tiles left after it)
         const int later = t_end - 1 - tile;
-        if (later >= NST - 2) wait_vmcnt_attn<(NST - 2) * LPW>();
+        if (later >= AHEAD - 1) wait_vmcnt_attn<(AHEAD - 1) * LPW>();
         else if (later == 1) wait_vmcnt_attn<LPW>();
         else wait_vmcnt_attn<0>();
-        // Everyone's part of this tile has landed, and everyone has the operands of tile - 1 in registers (its K
-        // went through QK^T, the reads of its V were waited for below): the stage of tile - 1 may be refilled.
+        // Everyone's part of this tile has landed, and everyone has issued the matrix instructions that consume the
+        // operands of tile - 2 (hence has them in registers): the stage of tile - 2 may be refilled.
         __builtin_amdgcn_s_barrier();
-        if (tile + NST - 1 < t_end) issue(tile + NST - 1);
+        if (tile + AHEAD < t_end) issue(tile + AHEAD);
+    };
+    // the plain iteration: softmax and PV of the pending tile, then the scores of this one
+    bool pending = false;  // s holds the scores of tile - 1, whose softmax and PV are still to come
+    auto plain_iteration = [&](int tile) __attribute__((always_inline)) {
+        tile_landed(tile);
         // rows of this wave see keys up to prefix + st*32 + 31; tiles entirely past that contribute nothing
         const bool act = wave_active && tile * kAttnTile <= wave_min_pos + 31;
-        const char *sK = smem + (tile % NST) * STAGE;
-        if (act) {
-            // operand A row (lane % 32): page row / 16, slot row % 16 (slots are rows as they stand); k-slot group g
-            const char *kp = sK + (col >> 4) * BLK + (col & 15) * 16 + g * 256;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) kf[kk] = *(const bf16x8 *)(kp + kk * 512);
-        }
         if (pending) softmax_pv(tile - 1);
         pending = act;
         if (act) {
-            // V block [2 token groups][hd][8]: lane (col, g) reads hd row 32 i + col of token group g
-            const char *sV = sK + 2 * BLK;
-#pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-                for (int i = 0; i < RT; ++i) vf[pg][i] = *(const u32x4 *)(sV + pg * BLK + (g * HD + col) * 16 + i * 512);
+            bf16x8 kf[KK];
+            read_k(smem + (tile % NST) * STAGE, kf);
 #pragma unroll
             for (int e = 0; e < 16; ++e) s[e] = 0.f;
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
-            // The V reads go out right behind the first instruction of the chain: the wait the compiler puts in
-            // front of the chain (for the K operands, long landed) then does not cover them, and the rest of the
-            // chain covers their latency.
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * RT, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, KK - 1, 0);
-            // the V operands must be in registers before the next barrier lets their stage be refilled
-            __builtin_amdgcn_sched_barrier(0);   // (after the chain, where the wait costs nothing)
-            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0) alone
         }
+    };
+    // Interleaved iterations run for the tiles t with a tile pending, every key of the pending tile visible to every
+    // row of this wavefront (no mask) and inside the block's key range: t_begin < t <= t_il, a range that depends on
+    // the wavefront's strip.  Every wavefront passes one barrier per tile in either kind of iteration.
+    int t_il = (wave_min_pos + 1) / kAttnTile;
+    if (kmax / kAttnTile < t_il) t_il = kmax / kAttnTile;
+    if (t_end - 1 < t_il) t_il = t_end - 1;
+    if (!wave_active) t_il = t_begin;
+    int tile = t_begin;
+    plain_iteration(tile++);
+    for (; tile <= t_il; ++tile) {
+        tile_landed(tile);
+        bf16x8 kf[KK];
+        u32x4 vf[2][RT];
+        read_k(smem + (tile % NST) * STAGE, kf);
+        read_v(smem + ((tile - 1) % NST) * STAGE, vf);
+        float mref;
+        const float alpha = softmax_max(tile - 1, false, mref);  // vector work under the latency of the reads
+        rescale(alpha);
+        // one scheduling region from here to the end of the iteration: 2 KK matrix instructions, the exponentials,
+        // the conversion of the probabilities
+        f32x16 sn;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sn[e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sn, 0, 0, 0);
+        softmax_exp(mref, alpha);
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        pv(vf);
+        s = sn;
     }
+    for (; tile < t_end; ++tile) plain_iteration(tile);
     if (pending) softmax_pv(t_end - 1);
 
     if (!tok_ok) return;

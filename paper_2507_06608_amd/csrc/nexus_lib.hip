@@ -460,10 +460,10 @@ static int launch_attn_prefill(const PhaseRun &r, const AttnPrefillArgs &base) {
     nexus_ctx *c = r.c;
     const int G = c->m.n_q_heads / c->m.n_kv_heads;
     AttnPrefillArgs a = base;
-    constexpr int smem = kAttnStages * 4 * kPage * HD * 2 + kAttnMaxPages * 4;
 #define NX_ATTN_CASE(GG, SPB)                                                                                        \
     case GG: {                                                                                                       \
         auto kern = attn_prefill_kernel<HD, GG, SPB>;                                                                \
+        constexpr int smem = attn_stages(GG * SPB) * 4 * kPage * HD * 2 + kAttnMaxPages * 4;                         \
         static bool done = false;                                                                                    \
         if (!done) {                                                                                                 \
             HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));      \
