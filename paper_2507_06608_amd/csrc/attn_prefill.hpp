@@ -12,10 +12,11 @@
 // probabilities never leave registers.  The private page layouts make both LDS reads conflict-free 16-byte reads.
 //
 // K/V tiles of 32 keys (2 pages of K, 2 of V) move global->LDS asynchronously (global_load_lds_dwordx4, 1 KiB per
-// wavefront instruction, page blocks copied verbatim) into a four-stage ring, three tiles in flight while one is
-// consumed; the request's page ids are staged in LDS once so that no load waits on a page-table read.  A short chunk has too few (strip, head) pairs to fill the
-// chip, so the key range can be split over gridDim.z workgroups whose partial (max, sum, O) results are merged by
-// attn_prefill_merge_kernel; the split count depends on the problem only.
+// wavefront instruction, page blocks copied verbatim) into a ring of stages: the tiles in flight, the tile whose K
+// operands are read, and the two before it, whose V operands are read two iterations later.  The request's page ids
+// are staged in LDS once so that no load waits on a page-table read.  A short chunk has too few (strip, head) pairs
+// to fill the chip, so the key range can be split over gridDim.z workgroups whose partial (max, sum, O) results are
+// merged by attn_prefill_merge_kernel; the split count depends on the problem only.
 #pragma once
 #include "common.hpp"
 
@@ -51,11 +52,12 @@ __device__ __forceinline__ void attn_split_range(int n_tiles, int n_splits, int 
 
 constexpr int kAttnTile = 32;   // keys per LDS stage (2 pages of K and of V)
 constexpr float kAttnLazyLog2 = 8.f;  // rise of a row's running maximum (log2 units) that moves the exponents' reference
-// Tiles issued ahead of the one whose K operands are read.  The ring holds those, that one, and the one before it
-// (whose V operands are read an iteration later).  A workgroup of up to four wavefronts shares its CU with a second
-// one, and two rings of five 16 KiB stages would not fit the CU's LDS next to the staged page ids: it looks two ahead.
-constexpr int attn_ahead(int n_waves) { return n_waves > 4 ? 3 : 2; }
-constexpr int attn_stages(int n_waves) { return attn_ahead(n_waves) + 2; }
+// Tiles issued ahead of the one whose K operands are read.  The ring holds those, that one, and the two before it
+// (V operands are read two iterations after the K operands).  A workgroup of up to four wavefronts shares its CU
+// with a second one, and two rings of more than four 16 KiB stages would not fit the CU's LDS next to the staged
+// page ids: it looks one tile ahead.
+constexpr int attn_ahead(int n_waves) { return n_waves > 4 ? 3 : 1; }
+constexpr int attn_stages(int n_waves) { return attn_ahead(n_waves) + 3; }
 
 template <int HD, int G, int SPB>
 __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefillArgs a) {  // two wavefronts per SIMD
@@ -101,10 +103,8 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     attn_split_range(n_kv_tiles, a.n_splits, z, t_begin, t_end);
     if (t_begin >= t_end) return;  // the merge kernel applies the same rule and never reads this split
 
-    // A SIMD holds two of these wavefronts (one of each resident workgroup), and each alternates between a matrix
-    // phase (QK^T, PV) and a vector phase (softmax) of about the same length.  At equal priority the two fall into
-    // step -- both in the same phase, one unit idle -- and stay there; with the wavefront in the odd hardware slot
-    // always served first, the other one fills the unit it leaves free and the phases interleave.
+    // A SIMD holds two of these wavefronts.  The one in the odd hardware slot is always served first: with equal
+    // priorities the two, which pass the same barriers, want the same unit at the same time more often.
     {
         unsigned hw_id;
         asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
@@ -169,15 +169,10 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
         }
     };
 
-    // The loop is software-pipelined over the key tiles.  Iteration t (after the barrier: tile t has landed, and
-    // everyone is done with tile t - 2, whose stage is refilled): the scores of tile t - 1 are pending in registers;
-    // the QK^T chain of tile t and the softmax of tile t - 1 are independent and are issued INTERLEAVED, one matrix
-    // instruction per dozen vector instructions, with the K operand reads of tile t and the V operand reads of tile
-    // t - 1 spread between them, so that a single wavefront keeps the matrix unit and the vector unit busy at the
-    // same time (the eight wavefronts of a workgroup run in step from barrier to barrier: with a vector block
-    // followed by a matrix block in each of them, the two wavefronts of a SIMD would want the same unit at the same
-    // time); the PV product of tile t - 1 follows.  Tiles that need the causal mask or reach past the block's last
-    // key, the first and the last iteration take the plain order (softmax, PV, then QK^T).
+    // The loop is software-pipelined over the key tiles, three tiles deep in its steady state (see below): the
+    // scores of tile t, the softmax of tile t - 1 and the PV product of tile t - 2 share an iteration.  Tiles that
+    // need the causal mask or reach past the block's last key, and the first iteration, take the plain order
+    // (softmax and PV of the pending tile, then the scores of the new one).
     f32x16 s;  // scores of the pending tile
     auto read_k = [&](const char *sK, bf16x8 (&kf)[KK]) __attribute__((always_inline)) {
         // operand A row (lane % 32): page row / 16, slot row % 16 (slots are rows as they stand); k-slot group g
@@ -248,17 +243,20 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
                 for (int e = 0; e < 16; ++e) o_acc[i][e] *= alpha;
         }
     };
-    // O^T += V^T P^T with the probabilities in s and the V operands in vf
-    auto pv = [&](u32x4 (&vf)[2][RT]) __attribute__((always_inline)) {
+    // the probabilities in s as the two bf16 operands of the PV product (token groups 0 and 1 of the tile)
+    auto pack_p = [&](bf16x8 (&pf)[2]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int pg = 0; pg < 2; ++pg) {
-            bf16x8 pf;
+        for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s[8 * pg + e];
+            for (int e = 0; e < 8; ++e) pf[pg][e] = (__bf16)s[8 * pg + e];
+    };
+    // O^T += V^T P^T
+    auto pv = [&](const bf16x8 (&pf)[2], u32x4 (&vf)[2][RT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
             for (int i = 0; i < RT; ++i)
-                o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf[pg][i], pf, o_acc[i], 0, 0, 0);
-        }
+                o_acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(bf16x8 *)&vf[pg][i], pf[pg], o_acc[i], 0, 0, 0);
     };
     // the plain order for the pending tile: V operands, softmax, PV
     auto softmax_pv = [&](int tile) __attribute__((always_inline)) {
@@ -282,23 +280,31 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
                         if (e >= left) vf[pg][i][e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
             }
         }
-        pv(vf);
+        bf16x8 pf[2];
+        pack_p(pf);
+        pv(pf, vf);
     };
 
 #pragma unroll
     for (int i = 0; i < AHEAD; ++i)
         if (t_begin + i < t_end) issue(t_begin + i);
-    // what every wavefront does at the top of an iteration, whatever it computes there
-    auto tile_landed = [&](int tile) __attribute__((always_inline)) {
+    // what every wavefront does at the top of an iteration, whatever it computes there, in two steps
+    auto tile_barrier = [&](int tile) __attribute__((always_inline)) {
         // loads issued after those of this tile and allowed to stay in flight: min(AHEAD - 1, tiles left after it)
         const int later = t_end - 1 - tile;
         if (later >= AHEAD - 1) wait_vmcnt_attn<(AHEAD - 1) * LPW>();
         else if (later == 1) wait_vmcnt_attn<LPW>();
         else wait_vmcnt_attn<0>();
         // Everyone's part of this tile has landed, and everyone has issued the matrix instructions that consume the
-        // operands of tile - 2 (hence has them in registers): the stage of tile - 2 may be refilled.
+        // operands of tile - 3 (hence has them in registers): the stage of tile - 3 may be refilled.
         __builtin_amdgcn_s_barrier();
+    };
+    auto tile_refill = [&](int tile) __attribute__((always_inline)) {
         if (tile + AHEAD < t_end) issue(tile + AHEAD);
+    };
+    auto tile_landed = [&](int tile) __attribute__((always_inline)) {
+        tile_barrier(tile);
+        tile_refill(tile);
     };
     // the plain iteration: softmax and PV of the pending tile, then the scores of this one
     bool pending = false;  // s holds the scores of tile - 1, whose softmax and PV are still to come
@@ -317,40 +323,76 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
             for (int kk = 0; kk < KK; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
         }
     };
-    // Interleaved iterations run for the tiles t with a tile pending, every key of the pending tile visible to every
-    // row of this wavefront (no mask) and inside the block's key range: t_begin < t <= t_il, a range that depends on
-    // the wavefront's strip.  Every wavefront passes one barrier per tile in either kind of iteration.
+    // Interleaved iterations run for the tiles t whose predecessors need no mask (every key visible to every row of
+    // this wavefront) and lie inside the block's key range: t_begin < t <= t_il, a range that depends on the
+    // wavefront's strip.  Every wavefront passes one barrier per tile in either kind of iteration.
     int t_il = (wave_min_pos + 1) / kAttnTile;
     if (kmax / kAttnTile < t_il) t_il = kmax / kAttnTile;
     if (t_end - 1 < t_il) t_il = t_end - 1;
     if (!wave_active) t_il = t_begin;
     int tile = t_begin;
     plain_iteration(tile++);
-    for (; tile <= t_il; ++tile) {
-        tile_landed(tile);
-        bf16x8 kf[KK];
-        u32x4 vf[2][RT];
-        read_k(smem + (tile % NST) * STAGE, kf);
-        read_v(smem + ((tile - 1) % NST) * STAGE, vf);
-        float mref;
-        const float alpha = softmax_max(tile - 1, false, mref);  // vector work under the latency of the reads
-        rescale(alpha);
-        // one scheduling region from here to the end of the iteration: 2 KK matrix instructions, the exponentials,
-        // the conversion of the probabilities
-        f32x16 sn;
+    if (tile <= t_il) {
+        // Three tiles in flight per wavefront: iteration t issues the QK^T chain of tile t and the PV product of tile
+        // t - 2 (probabilities packed an iteration ago) as ONE run of 2 KK matrix instructions, and spreads the whole
+        // softmax of tile t - 1 between them; nothing in the run depends on anything else in it.
+        bf16x8 pf[2];        // probabilities of tile - 2 (after the filling iteration: of tile - 1)
+        float alpha_pend;    // factor the accumulators take before that tile's PV product
+        {   // filling iteration: scores of this tile, softmax of the pending one, no PV yet
+            tile_landed(tile);
+            bf16x8 kf[KK];
+            read_k(smem + (tile % NST) * STAGE, kf);
+            float mref;
+            alpha_pend = softmax_max(tile - 1, false, mref);
+            f32x16 sn;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sn[e] = 0.f;
+            for (int e = 0; e < 16; ++e) sn[e] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sn, 0, 0, 0);
-        softmax_exp(mref, alpha);
+            for (int kk = 0; kk < KK; ++kk) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sn, 0, 0, 0);
+            softmax_exp(mref, alpha_pend);
+            pack_p(pf);
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+            for (int kk = 0; kk < KK; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+            }
+            s = sn;
+            ++tile;
         }
-        __builtin_amdgcn_sched_barrier(0);
-        pv(vf);
-        s = sn;
+        for (; tile <= t_il; ++tile) {
+            tile_barrier(tile);
+            bf16x8 kf[KK];
+            u32x4 vf[2][RT];
+            read_v(smem + ((tile - 2) % NST) * STAGE, vf);
+            read_k(smem + (tile % NST) * STAGE, kf);
+            // the refill (page ids out of LDS, addresses, loads) comes behind the operand reads: it works tiles ahead
+            // and is in no hurry, the matrix unit waits for the operands
+            tile_refill(tile);
+            rescale(alpha_pend);
+            // one scheduling region from here to the end of the iteration
+            float mref;
+            alpha_pend = softmax_max(tile - 1, false, mref);
+            f32x16 sn;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sn[e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], sn, 0, 0, 0);
+            pv(pf, vf);
+            softmax_exp(mref, alpha_pend);
+            pack_p(pf);
+#pragma unroll
+            for (int i = 0; i < KK + 2 * RT; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+            }
+            s = sn;
+        }
+        {   // draining: the PV product of tile - 2; its stage is still in the ring
+            u32x4 vf[2][RT];
+            read_v(smem + ((tile - 2) % NST) * STAGE, vf);
+            rescale(alpha_pend);
+            pv(pf, vf);
+        }
     }
     for (; tile < t_end; ++tile) plain_iteration(tile);
     if (pending) softmax_pv(t_end - 1);
