@@ -103,14 +103,6 @@ __global__ __launch_bounds__(64 * G * SPB, 2) void attn_prefill_kernel(AttnPrefi
     attn_split_range(n_kv_tiles, a.n_splits, z, t_begin, t_end);
     if (t_begin >= t_end) return;  // the merge kernel applies the same rule and never reads this split
 
-    // A SIMD holds two of these wavefronts.  The one in the odd hardware slot is always served first: with equal
-    // priorities the two, which pass the same barriers, want the same unit at the same time more often.
-    {
-        unsigned hw_id;
-        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hw_id));
-        if (hw_id & 1) __builtin_amdgcn_s_setprio(2);
-    }
-
     const int st = lt * SPB + strip;               // this wave's 32-token strip inside the request
     const bool wave_active = st * 32 < n_r;
     const int local = st * 32 + col;
