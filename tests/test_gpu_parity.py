@@ -548,7 +548,7 @@ def test_cfg3_heavy_mix_full_size_sampled(nx, oracle, monkeypatch):
     _check_sampled(oracle, "cfg3", wl, w, yp, yd, kv_after)
 
 
-@pytest.mark.parametrize("idx,layer,split,std", [(4, 47, (160, 96), None), (5, 79, (192, 64), None), (5, 79, (192, 64), 0.02)],
+@pytest.mark.parametrize("idx,layer,split,std", [(4, 47, (160, 96), None), (5, 79, (160, 96), None), (5, 79, (128, 128), 0.02)],
                          ids=["cfg4", "cfg5 fan-in weights", "cfg5 N(0, 0.02) weights"])
 def test_larger_model_shapes_full_size_sampled(nx, oracle, idx, layer, split, std):
     """One layer of the 14B-shaped (G = 5, hidden 5120) and the 70B-shaped (G = 8, hidden 8192, FFN 28672)
