@@ -104,20 +104,25 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x
 }
 
 // The same norm with one wavefront per token, for long batches: the wavefront keeps its whole row in registers
-// (MAXC 16-byte chunks per lane, all loaded before the first is used), the only reduction is a wavefront shuffle
-// and no barrier or LDS is involved; kRmsWaves rows share a workgroup.  With thousands of rows this moves 1.4x the
-// bytes per second of the workgroup-per-token kernel above (8192 rows of 4096: 72 -> 53 us); with a few hundred
-// rows the latter has four times the wavefronts to hide its latencies with and wins, above all where the slices of
-// a split-K GEMM are summed in passing (512 rows: 10 us against 22).
-constexpr int kRmsWaves = 4;
+// (MAXC 16-byte chunks per lane, all loaded before the first is used) and the only reduction is a wavefront
+// shuffle.  With thousands of rows this moves 1.4x the bytes per second of the workgroup-per-token kernel above
+// (8192 rows of 4096: 72 -> 53 us); with a few hundred rows the latter has four times the wavefronts to hide its
+// latencies with and wins, above all where the slices of a split-K GEMM are summed in passing (512 rows: 10 us
+// against 22).  A workgroup is kRmsWaves = 8 consecutive rows, because 8 rows of the tile-ordered output are one
+// 128-byte line (16 bytes of each): the wavefronts pass their normalised chunks through LDS, 64 chunks of every row
+// at a time, and write whole lines instead of 16-byte pieces of 64 different lines each.
+constexpr int kRmsWaves = 8;
 template <int MAXC, int IN>  // 8-element chunks per lane, d <= MAXC * 64 * 8
 __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void *__restrict__ x, const bf16_t *__restrict__ g,
                                                                  f16_t *__restrict__ out_p32, int n_tokens, int d, int Kp, float eps,
                                                                  RmsPartial pp) {
-    const int lane = threadIdx.x & 63;
-    const int t = xcd_run_index(blockIdx.x, gridDim.x) * kRmsWaves + (threadIdx.x >> 6);  // 8 output rows share a cache line
-    if (t >= n_tokens) return;
+    __shared__ uint4 stage[2][kRmsWaves][65];  // two buffers of [row][chunk]; 65: the transposed reads spread over the banks
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int t0 = xcd_run_index(blockIdx.x, gridDim.x) * kRmsWaves;
+    const int t = t0 + w < n_tokens ? t0 + w : n_tokens - 1;  // (a wavefront past the last row touches no row: see nload)
+    const bool row_ok = t0 + w < n_tokens;
     const int nchunk = d >> 3;
+    const int nload = row_ok ? nchunk : 0;  // a wavefront without a row loads and stores nothing and carries zeros
     float v[MAXC][8];
     if (IN == RMS_IN_BF16) {
         uint4 u[MAXC];
@@ -125,7 +130,7 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
         for (int c = 0; c < MAXC; ++c) {
             const int ci = lane + c * 64;
             u[c] = make_uint4(0, 0, 0, 0);
-            if (ci < nchunk) u[c] = ((const uint4 *)((const bf16_t *)x + (size_t)t * d))[ci];
+            if (ci < nload) u[c] = ((const uint4 *)((const bf16_t *)x + (size_t)t * d))[ci];
         }
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
         for (int c = 0; c < MAXC; ++c) {
             const int ci = lane + c * 64;
             float4 a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
-            if (ci < nchunk) {
+            if (ci < nload) {
                 const float4 *row = (const float4 *)((const float *)x + (size_t)t * d);
                 a0 = row[2 * ci], a1 = row[2 * ci + 1];
             }
@@ -154,7 +159,7 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
             const int ci = lane + c * 64;
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
-            if (ci < nchunk) sum_partial_y8(pp, t, d, ci, v[c]);
+            if (ci < nload) sum_partial_y8(pp, t, d, ci, v[c]);
         }
     } else {
 #pragma unroll
@@ -162,12 +167,12 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
             const int ci = lane + c * 64;
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[c][e] = 0.f;
-            if (ci < nchunk) sum_slices8(pp.partial + (size_t)t * d + 8 * ci, (size_t)pp.T * d, pp.S, v[c]);
+            if (ci < nload) sum_slices8(pp.partial + (size_t)t * d + 8 * ci, (size_t)pp.T * d, pp.S, v[c]);
         }
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
             const int ci = lane + c * 64;
-            if (ci < nchunk) {
+            if (ci < nload) {
                 const uint4 u = ((const uint4 *)(pp.res + (size_t)t * d))[ci];
                 const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
@@ -189,9 +194,12 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
     const float inv = rsqrtf(ss / (float)d + eps);
+    // lane (row r = lane % 8, line lane / 8 of this wavefront's eight) of the write-out: 8 lanes cover one 128-byte line
+    const int r_out = lane & 7, li = w * 8 + (lane >> 3);
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
         const int ci = lane + c * 64;
+        uint4 o4 = make_uint4(0, 0, 0, 0);
         if (ci < nchunk) {
             const uint4 gu = ((const uint4 *)g)[ci];
             const uint32_t gw[4] = {gu.x, gu.y, gu.z, gu.w};
@@ -199,8 +207,13 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 o[e] = packh2(v[c][2 * e] * inv * bf2f(gw[e] & 0xffff), v[c][2 * e + 1] * inv * bf2f(gw[e] >> 16));
-            *(uint4 *)(out_p32 + p32_offset(t, ci * 8, Kp)) = make_uint4(o[0], o[1], o[2], o[3]);
+            o4 = make_uint4(o[0], o[1], o[2], o[3]);
         }
+        stage[c & 1][w][lane] = o4;
+        // one barrier per round: the buffer written in round c + 1 was last read in round c - 1, before this barrier
+        __syncthreads();
+        const int co = li + c * 64;
+        if (co < nchunk && t0 + r_out < n_tokens) *(uint4 *)(out_p32 + p32_offset(t0 + r_out, co * 8, Kp)) = stage[c & 1][r_out][li];
     }
 }
 
@@ -238,29 +251,12 @@ struct RopeArgs {
     const bf16_t *bias;
 };
 
-template <bool PREFILL>
-__global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
-    // Neighbouring tokens of a chunk share cache lines in everything this kernel writes (8 rows of a query tile are
-    // one 128-byte line, 8 tokens one 16-byte V operand, 16 slots a 256-byte run of a K block), so each XCD takes
-    // runs of consecutive tokens (8192 tokens: 140 -> 95 us).  Decode tokens belong to different requests and pages.
-    const int t = PREFILL ? xcd_run_index(blockIdx.x, a.T) : blockIdx.x;
+// The decode side: one workgroup per request's new token (the tokens of a decode batch belong to different requests
+// and pages, there is nothing to share between neighbours).
+__global__ __launch_bounds__(256) void rope_append_decode_kernel(RopeArgs a) {
+    const int t = blockIdx.x;
     const int hd = a.hd, half = hd >> 1, cph = half >> 3;  // chunks of 8 rotary pairs per head
-    int r, pos, qrow;
-    if (PREFILL) {
-        r = 0;
-        int tile_base = 0;
-        while (r + 1 < a.n_reqs && a.cu_chunk[r + 1] <= t) {
-            tile_base += (a.cu_chunk[r + 1] - a.cu_chunk[r] + 31) >> 5;
-            ++r;
-        }
-        const int local = t - a.cu_chunk[r];
-        pos = a.pos_base[r] + local;
-        qrow = tile_base * 32 + local;
-    } else {
-        r = t;
-        pos = a.pos_base[t];
-        qrow = t;
-    }
+    const int r = t, pos = a.pos_base[t], qrow = t;
     const int qd = a.Hq * hd, kvd = a.Hkv * hd;
     const f16_t *row = a.qkv + (size_t)t * (qd + 2 * kvd);
     int page = -1;
@@ -307,13 +303,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
             uint4 plo = make_uint4(pack2(ol[0], ol[1]), pack2(ol[2], ol[3]), pack2(ol[4], ol[5]), pack2(ol[6], ol[7]));
             uint4 phi = make_uint4(pack2(oh[0], oh[1]), pack2(oh[2], oh[3]), pack2(oh[4], oh[5]), pack2(oh[6], oh[7]));
             if (h < a.Hq) {
-                if (PREFILL) {
-                    *(uint4 *)(a.q_out + p32_offset(qrow, h * hd + c * 8, qd)) = plo;
-                    *(uint4 *)(a.q_out + p32_offset(qrow, h * hd + half + c * 8, qd)) = phi;
-                } else {
-                    *(uint4 *)(a.q_out + (size_t)qrow * qd + h * hd + c * 8) = plo;
-                    *(uint4 *)(a.q_out + (size_t)qrow * qd + h * hd + half + c * 8) = phi;
-                }
+                *(uint4 *)(a.q_out + (size_t)qrow * qd + h * hd + c * 8) = plo;
+                *(uint4 *)(a.q_out + (size_t)qrow * qd + h * hd + half + c * 8) = phi;
             } else if (page_ok) {
                 const int kvh = h - a.Hq;
                 bf16_t *blk = a.k_pool + ((size_t)page * a.Hkv + kvh) * (kPage * hd);
@@ -329,6 +320,126 @@ __global__ __launch_bounds__(256) void rope_append_kernel(RopeArgs a) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) blk[vblk_offset(slot, c * 8 + e, hd)] = f2bf(vv[e]);
         }
+    }
+}
+
+// The prefill side of the same operation with a workgroup per 8 consecutive chunk tokens of a request (a quarter of
+// a 32-row query tile), because 8 is the unit everything it writes comes in: 8 rows of a query tile are one 128-byte
+// line (16 bytes of each), 8 tokens one 16-byte V operand, 8 consecutive positions two 64-byte runs of a K block.
+// With a workgroup per token every store instruction put 16-byte (V: 2-byte) pieces into 64 different lines; here
+// the 8 lanes that share a line are neighbours.  Thread (j = tid % 8, tid / 8): token j of the group, one of 32
+// units in flight; a unit is a chunk of 8 rotary pairs of a head (q heads first, then k heads) or 8 value elements.
+// The values of a unit pass through LDS to change hands: lane j then holds element j of the unit for the 8 tokens.
+// Grid: x = 4 groups per 32-row tile of the request-aligned query rows (at least the batch's tile count), y = the
+// workgroups that share a group's units (short batches have too few groups to fill the chip).
+__global__ __launch_bounds__(256) void rope_append_prefill_kernel(RopeArgs a) {
+    __shared__ uint4 vst[32][9];  // [unit in flight][token] (+ 1: the transposed reads spread over the banks)
+    const int b = xcd_run_index(blockIdx.x, gridDim.x);
+    const int ti = b >> 2, sub = b & 3;
+    int r = 0, tile_base = 0;
+    for (;; ++r) {
+        if (r >= a.n_reqs) return;
+        const int nt = (a.cu_chunk[r + 1] - a.cu_chunk[r] + 31) >> 5;
+        if (ti < tile_base + nt) break;
+        tile_base += nt;
+    }
+    const int c0 = a.cu_chunk[r], n_r = a.cu_chunk[r + 1] - c0;
+    const int local0 = (ti - tile_base) * 32 + sub * 8;
+    if (local0 >= n_r) return;  // the whole workgroup
+    const int j = threadIdx.x & 7, ul = threadIdx.x >> 3;
+    const bool tok_ok = local0 + j < n_r;
+    const int t = c0 + (tok_ok ? local0 + j : n_r - 1);  // (a lane without a token reads the last one's row and stores nothing)
+    const int pos0 = a.pos_base[r] + local0, pos = pos0 + j;
+    const int qrow = ti * 32 + sub * 8 + j;
+    const int hd = a.hd, half = hd >> 1, cph = half >> 3;
+    const int qd = a.Hq * hd, kvd = a.Hkv * hd, width = qd + 2 * kvd;
+    const f16_t *row = a.qkv + (size_t)t * width;
+    auto page_of = [&](int p) {
+        const int lp = p >> 4;
+        const int page = lp < a.max_pages ? a.page_table[(size_t)r * a.max_pages + lp] : -1;
+        return (unsigned)page < (unsigned)a.n_pages ? page : -1;
+    };
+    const int page = tok_ok ? page_of(pos) : -1;
+    const int slot = pos & 15;
+    const float2 *tab = a.rope_tab + (size_t)(pos < a.n_pos ? pos : a.n_pos - 1) * half;
+    auto load8 = [&](int col, float (&o)[8]) {
+        if (a.partial) {
+            sum_slices8(a.partial + (size_t)t * width + col, (size_t)a.T * width, a.S, o);
+            if (a.bias) {
+                const uint4 bb = *(const uint4 *)(a.bias + col);
+                const uint32_t bw[4] = {bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] += bf2f((bw[e >> 1] >> ((e & 1) * 16)) & 0xffff);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = h2f(f2h(o[e]));
+        } else {
+            const uint4 u = *(const uint4 *)(row + col);
+            const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = h2f((f16_t)((w[e >> 1] >> ((e & 1) * 16)) & 0xffff));
+        }
+    };
+    const int rope_units = (a.Hq + a.Hkv) * cph;
+    const int uy = 32 * blockIdx.y, ustep = 32 * gridDim.y;  // the units are dealt to gridDim.y workgroups, 32 at a time
+    for (int u = uy + ul; u < rope_units; u += ustep) {
+        if (!tok_ok) continue;
+        const int h = u / cph, c = u % cph;
+        float xl[8], xh[8], ol[8], oh[8];
+        load8(h * hd + c * 8, xl);
+        load8(h * hd + half + c * 8, xh);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x0 = xl[e], x1 = xh[e];
+            const float2 cs = tab[c * 8 + e];
+            ol[e] = x0 * cs.x - x1 * cs.y;
+            oh[e] = x1 * cs.x + x0 * cs.y;
+        }
+        const uint4 plo = make_uint4(pack2(ol[0], ol[1]), pack2(ol[2], ol[3]), pack2(ol[4], ol[5]), pack2(ol[6], ol[7]));
+        const uint4 phi = make_uint4(pack2(oh[0], oh[1]), pack2(oh[2], oh[3]), pack2(oh[4], oh[5]), pack2(oh[6], oh[7]));
+        if (h < a.Hq) {
+            *(uint4 *)(a.q_out + p32_offset(qrow, h * hd + c * 8, qd)) = plo;
+            *(uint4 *)(a.q_out + p32_offset(qrow, h * hd + half + c * 8, qd)) = phi;
+        } else if (page >= 0) {
+            bf16_t *blk = a.k_pool + ((size_t)page * a.Hkv + (h - a.Hq)) * (kPage * hd);
+            *(uint4 *)(blk + kblk_offset(slot, c * 8)) = plo;
+            *(uint4 *)(blk + kblk_offset(slot, half + c * 8)) = phi;
+        }
+    }
+    // values: 8 tokens x 8 elements change hands through LDS, then one 16-byte operand per lane when the group is a
+    // whole, aligned token group of one page; single elements otherwise (ragged tail, prefix not a multiple of 8)
+    const int v_units = a.Hkv * (hd >> 3);
+    const bool whole = (pos0 & 7) == 0 && local0 + 8 <= n_r;
+    const int page0 = whole ? page_of(pos0) : -1;
+    for (int ub = uy; ub < v_units; ub += ustep) {  // uniform trip count: the barriers below are the workgroup's
+        const int u = ub + ul;
+        const bool unit_ok = u < v_units;
+        const int kvh = unit_ok ? u / (hd >> 3) : 0, c = unit_ok ? u % (hd >> 3) : 0;
+        float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (unit_ok && tok_ok) load8(qd + kvd + kvh * hd + c * 8, vv);
+        vst[ul][j] = make_uint4(pack2(vv[0], vv[1]), pack2(vv[2], vv[3]), pack2(vv[4], vv[5]), pack2(vv[6], vv[7]));
+        __syncthreads();
+        if (unit_ok) {
+            bf16_t el[8];  // element j of the unit for tokens 0..7 of the group
+#pragma unroll
+            for (int k = 0; k < 8; ++k) el[k] = ((const bf16_t *)&vst[ul][k])[j];
+            if (whole) {
+                if (page0 >= 0) {
+                    bf16_t *blk = a.v_pool + ((size_t)page0 * a.Hkv + kvh) * (kPage * hd);
+                    const uint4 o = make_uint4((uint32_t)el[0] | ((uint32_t)el[1] << 16), (uint32_t)el[2] | ((uint32_t)el[3] << 16),
+                                               (uint32_t)el[4] | ((uint32_t)el[5] << 16), (uint32_t)el[6] | ((uint32_t)el[7] << 16));
+                    *(uint4 *)(blk + vblk_offset(pos0 & 15, c * 8 + j, hd)) = o;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (local0 + k >= n_r) break;
+                    const int pk = page_of(pos0 + k);
+                    if (pk >= 0) (a.v_pool + ((size_t)pk * a.Hkv + kvh) * (kPage * hd))[vblk_offset((pos0 + k) & 15, c * 8 + j, hd)] = el[k];
+                }
+            }
+        }
+        __syncthreads();
     }
 }
 

@@ -561,8 +561,11 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
         a.max_pages = prefill ? r.pb->max_pages : r.db->max_pages;
         a.k_pool = k_pool, a.v_pool = v_pool, a.n_pages = r.kv->n_pages, a.q_out = ws.q;
         Tracer tr(c, r.phase, NEXUS_K_ROPE_APPEND, r.s);
-        if (prefill) hipLaunchKernelGGL(rope_append_kernel<true>, dim3(r.T), dim3(256), 0, r.s, a);
-        else hipLaunchKernelGGL(rope_append_kernel<false>, dim3(r.T), dim3(256), 0, r.s, a);
+        // prefill: 4 groups of 8 rows per 32-row tile of the request-aligned rows (at most T / 32 + n_reqs tiles)
+        const int groups = 4 * (r.T / 32 + a.n_reqs);
+        const int share = std::max(1, std::min(8, 2048 / groups));  // workgroups per group, so that ~2048 are in the grid
+        if (prefill) hipLaunchKernelGGL(rope_append_prefill_kernel, dim3(groups, share), dim3(256), 0, r.s, a);
+        else hipLaunchKernelGGL(rope_append_decode_kernel, dim3(r.T), dim3(256), 0, r.s, a);
         HIP_TRY(hipGetLastError());
     }
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)m.head_dim);

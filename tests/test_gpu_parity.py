@@ -164,17 +164,19 @@ def test_random_small_workloads(nx, oracle, seed):
     g["ctx"].close()
 
 
-def test_8b_shaped_ragged_batch_every_output(nx, oracle):
+@pytest.mark.parametrize("chunks,prefixes", [([300, 477], [100, 2000]), ([700, 333], [300, 900])], ids=["777 rows", "1033 rows"])
+def test_8b_shaped_ragged_batch_every_output(nx, oracle, chunks, prefixes):
     """The tiled GEMMs (128 x 128, 256 x 128 and 256 x 256 tiles, split-K) at full width with token counts that fill
     none of their tiles evenly: two chunks of 300 and 477 tokens (777 rows: a last 32-row tile of 9, a last 128-token
-    block of 9) over prefixes of 100 and 2000, and 37 decode requests; every output and cache slot against the
-    oracle, on a split and serialized, bit-identical between the two."""
-    name = "8B-shaped ragged 777-token batch"
+    block of 9) over prefixes of 100 and 2000, or of 700 and 333 tokens (1033 rows: the long-batch kernels, whose
+    workgroups are 8 rows, with a last workgroup of one row), and 37 decode requests; every output and cache slot
+    against the oracle, on a split and serialized, bit-identical between the two."""
+    name = f"8B-shaped ragged {sum(chunks)}-token batch"
     _announce(name)
     sh = synth.SHAPES["llama3_8b"]
     rng = np.random.default_rng(7)
     ctx = [int(rng.integers(1, 3000)) for _ in range(37)]
-    wl = synth.make_workload(name, sh, 21, chunk_lens=[300, 477], prefix_lens=[100, 2000], decode_ctx=ctx, page_slack=3)
+    wl = synth.make_workload(name, sh, 21, chunk_lens=chunks, prefix_lens=prefixes, decode_ctx=ctx, page_slack=3)
     w = synth.make_weights(sh, 21)
     ref = run_oracle(oracle, wl, w)
     g = _gpu_run(nx, wl, w, "mixed", split=(192, 64))
