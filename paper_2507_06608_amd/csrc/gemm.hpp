@@ -111,6 +111,72 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, f32x16 (&acc)[F
     }
 }
 
+// The row-major epilogues (activations out, residual in, residual out, split-K partial sums) of the tiled GEMM, through LDS.  In the
+// accumulators a lane owns a token column and 4 consecutive features per register quad: stored as they stand, one
+// instruction puts 16 or 32 bytes into each of 32 different rows (and reads the residual the same way).  Here a
+// wavefront first lays a 32-token x 64-feature block of its accumulators into its own LDS scratch, token-major,
+// and then walks it row by row: 16 lanes cover the 64 features of a token, 4 features each, so the residual is
+// read and the result written in whole 128- or 256-byte runs.  Same values, same arithmetic, other lanes.
+// `scratch` is the wavefront's own kEpiScratch bytes; the workgroup has passed a barrier since its last operand read.
+constexpr int kEpiPitch = 68;                        // floats per token row: 64 + 4 (the column writes spread over the banks)
+constexpr int kEpiScratch = 32 * kEpiPitch * 4;      // bytes per wavefront
+template <int FW, int TW, int EPI>
+__device__ __forceinline__ void gemm_epilogue_rows(const GemmArgs &a, f32x16 (&acc)[FW][TW], int ft0, int tt0, int z, int lane, char *scratch) {
+    static_assert(EPI == EPI_ROWMAJOR || EPI == EPI_RES_IN || EPI == EPI_RES_OUT || EPI == EPI_PARTIAL, "row-major epilogues only");
+    float *sc = (float *)scratch;
+    const int g = lane >> 5, col = lane & 31;
+#pragma unroll
+    for (int j = 0; j < TW; ++j) {
+#pragma unroll
+        for (int i0 = 0; i0 < FW; i0 += 2) {
+            const int nfs = FW - i0 >= 2 ? 2 : 1;  // feature strips in this block
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                if (ii >= nfs) break;
+                const int i = i0 + ii < FW ? i0 + ii : FW - 1;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float4 v = {acc[i][j][4 * b], acc[i][j][4 * b + 1], acc[i][j][4 * b + 2], acc[i][j][4 * b + 3]};
+                    *(float4 *)(sc + col * kEpiPitch + ii * 32 + 8 * b + 4 * g) = v;
+                }
+            }
+            // LDS serves a wavefront's requests in order: the reads below see the writes above
+            const int cpt = nfs * 8;  // 4-feature chunks per token
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (k >= 4 * nfs) break;
+                const int idx = lane + 64 * k;
+                const int tok = idx / cpt, fc = idx % cpt;
+                const float4 v = *(const float4 *)(sc + tok * kEpiPitch + fc * 4);
+                const int t = (tt0 + j) * 32 + tok;
+                const int ft = ft0 + i0 + (fc >> 3);
+                if (t >= a.T || ft >= a.n_ftiles) continue;
+                const int f = ft * 32 + (fc & 7) * 4;
+                if constexpr (EPI == EPI_PARTIAL) {
+                    *(float4 *)(a.partial + ((size_t)z * a.T + t) * a.N + f) = v;
+                } else if constexpr (EPI == EPI_ROWMAJOR) {
+                    float w[4] = {v.x, v.y, v.z, v.w};
+                    if (a.bias) {
+                        const uint2 bb = *(const uint2 *)(a.bias + f);
+                        w[0] += bf2f(bb.x & 0xffff), w[1] += bf2f(bb.x >> 16);
+                        w[2] += bf2f(bb.y & 0xffff), w[3] += bf2f(bb.y >> 16);
+                    }
+                    const uint2 o = {packh2(w[0], w[1]), packh2(w[2], w[3])};
+                    *(uint2 *)((f16_t *)a.out + (size_t)t * a.ld_out + f) = o;
+                } else if constexpr (EPI == EPI_RES_IN) {
+                    const uint2 rr = *(const uint2 *)((const bf16_t *)a.res + (size_t)t * a.ld_out + f);
+                    const float4 o = {v.x + bf2f(rr.x & 0xffff), v.y + bf2f(rr.x >> 16), v.z + bf2f(rr.y & 0xffff), v.w + bf2f(rr.y >> 16)};
+                    *(float4 *)((float *)a.out + (size_t)t * a.ld_out + f) = o;
+                } else {
+                    const float4 rr = *(const float4 *)((const float *)a.res + (size_t)t * a.ld_out + f);
+                    const uint2 o = {pack2(v.x + rr.x, v.y + rr.y), pack2(v.z + rr.z, v.w + rr.w)};
+                    *(uint2 *)((bf16_t *)a.out + (size_t)t * a.ld_out + f) = o;
+                }
+            }
+        }
+    }
+}
+
 // s_waitcnt on the vector-memory counter alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, the other counters
 // left at their maxima).  Asynchronous global->LDS loads are tracked by this counter.
 template <int N>
@@ -276,6 +342,17 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
         for (int j = 0; j < TW; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    // what follows the k loop: the row-major epilogues go through LDS (every wavefront is done with the operand
+    // stages once the workgroup has passed the barrier), the tile-ordered one stores as it stands
+    auto finish = [&]() {
+        if constexpr (EPI != EPI_SWIGLU) {
+            static_assert(NW * kEpiScratch <= NST * STAGE, "the epilogue scratch lives in the operand ring");
+            __syncthreads();
+            gemm_epilogue_rows<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane, smem + w * kEpiScratch);
+        } else {
+            gemm_epilogue<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane);
+        }
+    };
 
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
@@ -448,7 +525,7 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
             if (NWL == NW || w < NWL) run(std::true_type{});
             else run(std::false_type{});
         }
-        gemm_epilogue<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane);
+        finish();
         return;
     }
     // ---- generic pipeline (four k-tiles per stage, or compiler-visible LDS reads) ----------------------------------------
@@ -480,7 +557,7 @@ __global__ __launch_bounds__(64 * WF * WT) void gemm_dl_kernel(GemmArgs a) {
     };
     for (int ks = 0; ks + 1 < nsteps; ++ks) stage(ks, std::true_type{});
     if (nsteps > 0) stage(nsteps - 1, std::false_type{});
-    gemm_epilogue<FW, TW, EPI>(a, acc, ft0 + wf * FW, tt0 + wt * TW, z, lane);
+    finish();
 }
 
 // ---- weight-streaming GEMM of a decode batch -------------------------------------------------------------------
