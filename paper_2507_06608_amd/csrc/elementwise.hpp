@@ -287,7 +287,8 @@ __global__ __launch_bounds__(256) void rope_append_decode_kernel(RopeArgs a) {
     };
     const int rope_units = (a.Hq + a.Hkv) * cph;
     const int v_units = a.Hkv * (hd >> 3);
-    for (int u = threadIdx.x; u < rope_units + v_units; u += 256) {
+    // gridDim.y workgroups share a token's units: a decode batch has too few tokens to put one on every CU
+    for (int u = threadIdx.x + 256 * blockIdx.y; u < rope_units + v_units; u += 256 * gridDim.y) {
         if (u < rope_units) {
             const int h = u / cph, c = u % cph;  // head (q heads first, then k heads), pair chunk
             float xl[8], xh[8], ol[8], oh[8];

@@ -565,7 +565,7 @@ static int run_layer(const PhaseRun &r, int layer, const bf16_t *x_in, bf16_t *y
         const int groups = 4 * (r.T / 32 + a.n_reqs);
         const int share = std::max(1, std::min(8, 2048 / groups));  // workgroups per group, so that ~2048 are in the grid
         if (prefill) hipLaunchKernelGGL(rope_append_prefill_kernel, dim3(groups, share), dim3(256), 0, r.s, a);
-        else hipLaunchKernelGGL(rope_append_decode_kernel, dim3(r.T), dim3(256), 0, r.s, a);
+        else hipLaunchKernelGGL(rope_append_decode_kernel, dim3(r.T, std::max(1, std::min(4, 256 / std::max(1, r.T)))), dim3(256), 0, r.s, a);
         HIP_TRY(hipGetLastError());
     }
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)m.head_dim);
