@@ -109,14 +109,15 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void *__restrict__ x
 // (8192 rows of 4096: 72 -> 53 us); with a few hundred rows the latter has four times the wavefronts to hide its
 // latencies with and wins, above all where the slices of a split-K GEMM are summed in passing (512 rows: 10 us
 // against 22).  A workgroup is kRmsWaves = 8 consecutive rows, because 8 rows of the tile-ordered output are one
-// 128-byte line (16 bytes of each): the wavefronts pass their normalised chunks through LDS, 64 chunks of every row
-// at a time, and write whole lines instead of 16-byte pieces of 64 different lines each.
+// 128-byte line (16 bytes of each): the wavefronts lay their normalised rows into LDS (8 rows, up to 128 KiB, one
+// barrier) and write whole lines instead of 16-byte pieces of 64 different lines each.
 constexpr int kRmsWaves = 8;
 template <int MAXC, int IN>  // 8-element chunks per lane, d <= MAXC * 64 * 8
 __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void *__restrict__ x, const bf16_t *__restrict__ g,
                                                                  f16_t *__restrict__ out_p32, int n_tokens, int d, int Kp, float eps,
                                                                  RmsPartial pp) {
-    __shared__ uint4 stage[2][kRmsWaves][65];  // two buffers of [row][chunk]; 65: the transposed reads spread over the banks
+    extern __shared__ uint4 stage[];  // [row][MAXC * 64 + 1 chunks] (+ 1: the transposed reads spread over the banks); sized by the host
+    constexpr int SP = MAXC * 64 + 1;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int t0 = xcd_run_index(blockIdx.x, gridDim.x) * kRmsWaves;
     const int t = t0 + w < n_tokens ? t0 + w : n_tokens - 1;  // (a wavefront past the last row touches no row: see nload)
@@ -209,11 +210,13 @@ __global__ __launch_bounds__(64 * kRmsWaves) void rmsnorm_wave_kernel(const void
                 o[e] = packh2(v[c][2 * e] * inv * bf2f(gw[e] & 0xffff), v[c][2 * e + 1] * inv * bf2f(gw[e] >> 16));
             o4 = make_uint4(o[0], o[1], o[2], o[3]);
         }
-        stage[c & 1][w][lane] = o4;
-        // one barrier per round: the buffer written in round c + 1 was last read in round c - 1, before this barrier
-        __syncthreads();
+        stage[w * SP + ci] = o4;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
         const int co = li + c * 64;
-        if (co < nchunk && t0 + r_out < n_tokens) *(uint4 *)(out_p32 + p32_offset(t0 + r_out, co * 8, Kp)) = stage[c & 1][r_out][li];
+        if (co < nchunk && t0 + r_out < n_tokens) *(uint4 *)(out_p32 + p32_offset(t0 + r_out, co * 8, Kp)) = stage[r_out * SP + co];
     }
 }
 

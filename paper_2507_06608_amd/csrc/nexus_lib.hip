@@ -434,10 +434,22 @@ static int run_rmsnorm(const PhaseRun &r, const void *x, const bf16_t *g, f16_t 
     const int Kp = p32_kp(d);
     if (r.T >= 1024) {  // problem-only choice (the two kernels sum the squares in different orders)
         const dim3 grid((r.T + kRmsWaves - 1) / kRmsWaves), block(64 * kRmsWaves);
-        if (d <= 1024) hipLaunchKernelGGL((rmsnorm_wave_kernel<2, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
-        else if (d <= 2048) hipLaunchKernelGGL((rmsnorm_wave_kernel<4, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
-        else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_wave_kernel<8, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
-        else hipLaunchKernelGGL((rmsnorm_wave_kernel<16, IN>), grid, block, 0, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);
+#define NX_RMS_WAVE(MAXC)                                                                                              \
+    {                                                                                                               \
+        auto kern = rmsnorm_wave_kernel<MAXC, IN>;                                                                    \
+        constexpr int smem = kRmsWaves * (MAXC * 64 + 1) * 16;                                                        \
+        static bool done = false;                                                                                   \
+        if (!done) {                                                                                                \
+            HIP_TRY(hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));     \
+            done = true;                                                                                            \
+        }                                                                                                           \
+        hipLaunchKernelGGL(kern, grid, block, smem, r.s, x, g, out_p32, r.T, d, Kp, c->m.rms_eps, pp);              \
+    }
+        if (d <= 1024) NX_RMS_WAVE(2)
+        else if (d <= 2048) NX_RMS_WAVE(4)
+        else if (d <= 4096) NX_RMS_WAVE(8)
+        else NX_RMS_WAVE(16)
+#undef NX_RMS_WAVE
     } else if (d <= 2048) hipLaunchKernelGGL((rmsnorm_kernel<1, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, Kp, c->m.rms_eps, pp);
     else if (d <= 4096) hipLaunchKernelGGL((rmsnorm_kernel<2, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, Kp, c->m.rms_eps, pp);
     else hipLaunchKernelGGL((rmsnorm_kernel<4, IN>), dim3(r.T), dim3(256), 0, r.s, x, g, out_p32, d, Kp, c->m.rms_eps, pp);
