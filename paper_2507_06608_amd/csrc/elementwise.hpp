@@ -386,18 +386,23 @@ __global__ __launch_bounds__(256) void rope_append_prefill_kernel(RopeArgs a) {
     };
     const int rope_units = (a.Hq + a.Hkv) * cph;
     const int uy = 32 * blockIdx.y, ustep = 32 * gridDim.y;  // the units are dealt to gridDim.y workgroups, 32 at a time
+    // cph divides 32 (head dimensions 64 and 128): a thread's units all have the same pair chunk, whose eight
+    // (cos, sin) it reads once instead of once per head
+    const int c = ul % cph;
+    float2 cs[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs[e] = tab[c * 8 + e];
     for (int u = uy + ul; u < rope_units; u += ustep) {
         if (!tok_ok) continue;
-        const int h = u / cph, c = u % cph;
+        const int h = u / cph;
         float xl[8], xh[8], ol[8], oh[8];
         load8(h * hd + c * 8, xl);
         load8(h * hd + half + c * 8, xh);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float x0 = xl[e], x1 = xh[e];
-            const float2 cs = tab[c * 8 + e];
-            ol[e] = x0 * cs.x - x1 * cs.y;
-            oh[e] = x1 * cs.x + x0 * cs.y;
+            ol[e] = x0 * cs[e].x - x1 * cs[e].y;
+            oh[e] = x1 * cs[e].x + x0 * cs[e].y;
         }
         const uint4 plo = make_uint4(pack2(ol[0], ol[1]), pack2(ol[2], ol[3]), pack2(ol[4], ol[5]), pack2(ol[6], ol[7]));
         const uint4 phi = make_uint4(pack2(oh[0], oh[1]), pack2(oh[2], oh[3]), pack2(oh[4], oh[5]), pack2(oh[6], oh[7]));
